@@ -1,0 +1,236 @@
+"""Seeded synthetic inputs for the HALO group-sparse FFN path.
+
+This module only manufactures inputs (weights, hidden states, packet-loss
+outcomes, workload shapes).  It contains none of the method's arithmetic:
+no predictor, ranking, scheduling or FFN step lives here.  Both the CPU
+oracle's tests and the HIP path's tests / benchmark draw their inputs from
+these functions, so that the two sides see bit-identical data.
+
+Generator.  Every tensor element is a pure function of
+(seed, tensor id, layer, step, flat index):
+
+    k  = fold(seed, tensor id, layer, step)        (splitmix64 finaliser chain)
+    u  = splitmix64_finaliser(k + (index+1) * 0x9E3779B97F4A7C15)
+    z  = Z[u >> 48]          Z = 65536 standard-normal quantiles at (i+1/2)/65536
+    v  = round_to_dtype(float32(sigma) * z)
+
+Only 64-bit integer operations and one table lookup are involved, so the
+same torch code gives the same bits on the CPU and on the GPU (which lets
+the 113 GB LLaMA-2-70B-shape stack be produced directly in HBM and
+re-produced one layer at a time on the host).  Uniform variates for the
+packet-loss outcomes are (u >> 11) * 2**-53.
+
+The workloads stand in for what the paper ran (GSM8K-derived 128+128 token
+requests on 4-bit LLaMA models, section V-A): same FFN shapes, random
+weights N(0, 0.02), hidden states N(0, 1).
+"""
+from __future__ import annotations
+
+import dataclasses
+import functools
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+import torch
+
+_M64 = (1 << 64) - 1
+_GAMMA = 0x9E3779B97F4A7C15
+_C1 = 0xBF58476D1CE4E5B9
+_C2 = 0x94D049BB133111EB
+
+# tensor ids (stream selectors)
+TID_X = 1
+TID_WG = 2
+TID_WU = 3
+TID_WDT = 4
+TID_AT = 5
+TID_BT = 6
+TID_DROP = 7
+TID_PLR = 8
+TID_MISC = 9
+
+
+def _mix_py(z: int) -> int:
+    z &= _M64
+    z = ((z ^ (z >> 30)) * _C1) & _M64
+    z = ((z ^ (z >> 27)) * _C2) & _M64
+    return z ^ (z >> 31)
+
+
+def stream_key(seed: int, tensor_id: int, layer: int = 0, step: int = 0) -> int:
+    k = _mix_py(seed + _GAMMA)
+    k = _mix_py(k ^ (tensor_id & _M64))
+    k = _mix_py(k ^ (layer & _M64))
+    k = _mix_py(k ^ (step & _M64))
+    return k
+
+
+def _s64(v: int) -> int:
+    """Two's-complement reinterpretation of an unsigned 64-bit value."""
+    v &= _M64
+    return v - (1 << 64) if v >= (1 << 63) else v
+
+
+def _lsr(z: torch.Tensor, s: int) -> torch.Tensor:
+    """Logical shift right on int64 tensors."""
+    return (z >> s) & ((1 << (64 - s)) - 1)
+
+
+def raw_u64(key: int, start: int, count: int, device="cpu") -> torch.Tensor:
+    """u for flat indices start .. start+count-1, as int64 bit patterns."""
+    idx = torch.arange(start + 1, start + count + 1, dtype=torch.int64, device=device)
+    z = idx * _s64(_GAMMA) + _s64(key)
+    z = (z ^ _lsr(z, 30)) * _s64(_C1)
+    z = (z ^ _lsr(z, 27)) * _s64(_C2)
+    return z ^ _lsr(z, 31)
+
+
+@functools.lru_cache(maxsize=1)
+def _quantile_table_np() -> np.ndarray:
+    from scipy.special import ndtri
+
+    p = (np.arange(65536, dtype=np.float64) + 0.5) / 65536.0
+    return ndtri(p).astype(np.float32)
+
+
+_table_cache = {}
+
+
+def quantile_table(device="cpu") -> torch.Tensor:
+    dev = torch.device(device)
+    key = (dev.type, dev.index)
+    if key not in _table_cache:
+        _table_cache[key] = torch.from_numpy(_quantile_table_np().copy()).to(dev)
+    return _table_cache[key]
+
+
+def normal(shape: Sequence[int], sigma: float, dtype: torch.dtype, key: int,
+           device="cpu", chunk: int = 1 << 25) -> torch.Tensor:
+    """Tensor of N(0, sigma^2) values (quantised to 65536 quantiles), rounded to dtype."""
+    n = int(np.prod(shape)) if len(shape) else 1
+    out = torch.empty(n, dtype=dtype, device=device)
+    tab = quantile_table(device)
+    sig = torch.tensor(float(sigma), dtype=torch.float32, device=device)
+    for s in range(0, n, chunk):
+        c = min(chunk, n - s)
+        u = raw_u64(key, s, c, device)
+        z = tab[_lsr(u, 48)]
+        out[s:s + c] = (z * sig).to(dtype)
+    return out.reshape(tuple(shape))
+
+
+def uniform01(count: int, key: int, start: int = 0) -> np.ndarray:
+    """float64 uniforms in [0,1) on the host."""
+    u = raw_u64(key, start, count, "cpu")
+    return (_lsr(u, 11).numpy().astype(np.float64)) * (2.0 ** -53)
+
+
+# --------------------------------------------------------------------------
+# Workloads
+# --------------------------------------------------------------------------
+
+@dataclasses.dataclass(frozen=True)
+class Workload:
+    name: str
+    d: int
+    ffn: int
+    group_size: int
+    rank: int
+    T: int
+    layers: int
+    dtype: str                 # "f32" | "bf16"
+    keep: Tuple[float, ...]
+    n_dev: int
+    plr: Optional[Tuple[float, ...]]   # None: seeded uniforms in [0, plr_max]
+    plr_max: float
+    steps: int
+    seed: int
+
+    @property
+    def n_groups(self) -> int:
+        return self.ffn // self.group_size
+
+    @property
+    def torch_dtype(self) -> torch.dtype:
+        return torch.float32 if self.dtype == "f32" else torch.bfloat16
+
+    def k_keep(self, keep: Optional[float] = None) -> int:
+        """Number of groups kept per token: nearest integer to keep*G, at least 1.
+        (A harness-side conversion; the library's interface takes the integer.)"""
+        keep = self.keep[0] if keep is None else keep
+        from fractions import Fraction
+        import math
+        q = Fraction(str(keep)) * self.n_groups + Fraction(1, 2)   # exact decimal arithmetic
+        return max(1, min(self.n_groups, math.floor(q)))
+
+    def device_plr(self) -> np.ndarray:
+        if self.plr is not None:
+            return np.asarray(self.plr, dtype=np.float64)
+        return uniform01(self.n_dev, stream_key(self.seed, TID_PLR)) * self.plr_max
+
+
+TINY = Workload("tiny", 256, 1024, 128, 64, 16, 1, "f32", (0.5,), 4,
+                (0.0, 0.0, 0.1, 0.3), 0.0, 1, 0)
+LLAMA7B_DECODE = Workload("llama7b_decode", 4096, 11008, 128, 256, 1, 1, "bf16", (0.5,), 4,
+                          (0.0, 0.05, 0.1, 0.2), 0.0, 1024, 1)
+LLAMA13B_STACK = Workload("llama13b_stack", 5120, 13824, 128, 256, 4, 40, "bf16",
+                          (0.3, 0.5, 0.7), 6, None, 0.3, 1, 2)
+LLAMA7B_PREFILL = Workload("llama7b_prefill", 4096, 11008, 128, 256, 512, 1, "bf16", (0.5,), 4,
+                           (0.0, 0.05, 0.1, 0.2), 0.0, 1, 3)
+LLAMA70B_STACK = Workload("llama70b_stack", 8192, 28672, 128, 512, 8, 80, "bf16", (0.5,), 8,
+                          (0.0, 0.0, 0.05, 0.05, 0.1, 0.1, 0.2, 0.3), 0.0, 1, 4)
+
+WORKLOADS = [TINY, LLAMA7B_DECODE, LLAMA13B_STACK, LLAMA7B_PREFILL, LLAMA70B_STACK]
+BY_NAME = {w.name: w for w in WORKLOADS}
+
+
+def small_variant(w: Workload, d: int, n_groups: int, rank: int, T: Optional[int] = None,
+                  layers: Optional[int] = None) -> Workload:
+    """Same structure as w at a reduced shape (for parity cases the oracle finishes fast)."""
+    return dataclasses.replace(w, name=w.name + "_small", d=d, ffn=n_groups * w.group_size,
+                               rank=rank, T=w.T if T is None else T,
+                               layers=w.layers if layers is None else layers)
+
+
+# --------------------------------------------------------------------------
+# Tensors of one layer
+# --------------------------------------------------------------------------
+
+W_SIGMA = 0.02
+X_SIGMA = 1.0
+
+
+def ffn_weights(w: Workload, layer: int = 0, device="cpu", copy: int = 0):
+    """(Wg, Wu, WdT), each [ffn][d] in the workload dtype.  Row m of each belongs to
+    neuron m; WdT is the down projection stored neuron-major (transposed).
+    `copy` selects an independent replica of the same shape (benchmark rotation)."""
+    dt = w.torch_dtype
+    lay = layer + 1000003 * copy
+    mk = lambda tid: normal((w.ffn, w.d), W_SIGMA, dt, stream_key(w.seed, tid, lay), device)
+    return mk(TID_WG), mk(TID_WU), mk(TID_WDT)
+
+
+def predictor_weights(w: Workload, layer: int = 0, device="cpu", copy: int = 0):
+    """(At [rank][d], Bt [G][rank]): the two predictor matrices, stored transposed."""
+    dt = w.torch_dtype
+    lay = layer + 1000003 * copy
+    At = normal((w.rank, w.d), W_SIGMA, dt, stream_key(w.seed, TID_AT, lay), device)
+    Bt = normal((w.n_groups, w.rank), W_SIGMA, dt, stream_key(w.seed, TID_BT, lay), device)
+    return At, Bt
+
+
+def hidden_states(w: Workload, step: int = 0, device="cpu", T: Optional[int] = None,
+                  dtype: Optional[torch.dtype] = None):
+    """x [T][d] ~ N(0,1) in the workload dtype (or `dtype`)."""
+    T = w.T if T is None else T
+    dt = w.torch_dtype if dtype is None else dtype
+    return normal((T, w.d), X_SIGMA, dt, stream_key(w.seed, TID_X, 0, step), device)
+
+
+def drop_outcomes(w: Workload, layer: int = 0, step: int = 0, T: Optional[int] = None,
+                  plr: Optional[np.ndarray] = None) -> np.ndarray:
+    """drop[t][dev] in {0,1}: Bernoulli(plr[dev]) per (token, layer, step, device)."""
+    T = w.T if T is None else T
+    plr = w.device_plr() if plr is None else np.asarray(plr, dtype=np.float64)
+    u = uniform01(T * w.n_dev, stream_key(w.seed, TID_DROP, layer, step)).reshape(T, w.n_dev)
+    return (u < plr[None, :]).astype(np.uint8)

@@ -1,0 +1,302 @@
+/*
+ * halo_ref.c -- CPU oracle for the HALO group-sparse FFN path.
+ *
+ * TEST INFRASTRUCTURE.  This file is the slow, plain definition that the HIP
+ * library is checked against.  It shares no code with that library and must
+ * never be linked into, imported by, or called from the product path; only
+ * the tests, the smoke check and the benchmark's CPU-baseline leg use it.
+ *
+ * Everything works on host pointers.  Floating-point inputs arrive as float
+ * arrays holding the storage-dtype values widened exactly (bf16 -> float is
+ * exact), so the oracle never needs to know the storage type.
+ *
+ * What is computed, and the passage of the paper each step follows:
+ *
+ *   halo_ref_schedule          Alg. 3 (PLR-aware ratio-guided scheduler) and the
+ *                              worked example of Sec. III-B.4.
+ *   halo_ref_predict_scores    Sec. III-B.2 (semantic-aware predictor): a
+ *                              two-matrix network D -> hidden -> N_g, one
+ *                              significance value per neuron group.
+ *   halo_ref_build_group_mask  Sec. III-B.3 item 1 (importance rank used as the
+ *                              reference list for the priority indices) and the
+ *                              relaxed synchronisation of the same section (a lost
+ *                              device's partial result is absent from the merge).
+ *   halo_ref_group_partials /
+ *   halo_ref_group_sparse_ffn  Sec. II-A "Neuron group": one MLP group = a block
+ *                              of gate rows, the same up rows and the matching
+ *                              down columns; the block output is the plain sum of
+ *                              the groups' partial results (merge at the master).
+ *
+ * Pins (see tests/test_oracle_*.py): Alg. 3's printed example; the 6144/256 = 24
+ * group count; dense SwiGLU via a float64 library matmul; sum of partials = dense;
+ * exact zeros for dropped / unselected groups; brute-force and library stable
+ * sorts for the ranking; hand-worked closed forms for the predictor and SiLU.
+ * The predictor's *quality* (does it rank real activations well) needs trained
+ * weights and is out of scope: parity unpinned for that property only.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define REF_OK 0
+#define REF_ERR -1
+
+/* ------------------------------------------------------------------------- */
+/* Alg. 3: PLR-aware ratio-guided scheduler.                                  */
+/*                                                                           */
+/* q = stable ascending argsort of the PLRs; the ratios are permuted by q;   */
+/* the priority indices 0..n_prio-1 (0 = most significant) are cut into n    */
+/* contiguous runs whose lengths follow the permuted ratios; run k goes to   */
+/* device q[k].  Cut points are round-half-up of n_prio * cumulative ratio,  */
+/* the last one forced to n_prio (this rounding reproduces the paper's       */
+/* 8-group example; a cumulative floor does not).  ratios == NULL means the  */
+/* homogeneous setting r_i = 1/n, done in integers.                          */
+/* ------------------------------------------------------------------------- */
+int halo_ref_schedule(int32_t n_prio, int32_t n_dev, const double *ratios,
+                      const double *plr, int8_t *prio_dev)
+{
+    if (n_prio < 0 || n_dev < 1 || n_dev > 127 || !plr || (!prio_dev && n_prio > 0))
+        return REF_ERR;
+    int q[128];
+    for (int i = 0; i < n_dev; ++i) {
+        if (!(plr[i] >= 0.0) || !(plr[i] <= 1.0)) return REF_ERR;
+        if (ratios && !(ratios[i] >= 0.0)) return REF_ERR;
+        q[i] = i;
+    }
+    /* insertion sort: stable, ascending PLR */
+    for (int i = 1; i < n_dev; ++i) {
+        int v = q[i], j = i - 1;
+        while (j >= 0 && plr[q[j]] > plr[v]) { q[j + 1] = q[j]; --j; }
+        q[j + 1] = v;
+    }
+    int64_t lo = 0;
+    double cum = 0.0;
+    for (int k = 0; k < n_dev; ++k) {
+        int64_t hi;
+        if (k == n_dev - 1) {
+            hi = n_prio;
+        } else if (!ratios) {
+            hi = (2 * (int64_t)n_prio * (k + 1) + n_dev) / (2 * (int64_t)n_dev);
+        } else {
+            cum = cum + ratios[q[k]];
+            volatile double prod = (double)n_prio * cum;   /* no fused multiply-add */
+            hi = (int64_t)floor(prod + 0.5);
+        }
+        if (hi > n_prio) hi = n_prio;
+        if (hi < lo) hi = lo;
+        for (int64_t p = lo; p < hi; ++p) prio_dev[p] = (int8_t)q[k];
+        lo = hi;
+    }
+    return REF_OK;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Predictor, Sec. III-B.2.   h = ReLU(x A),  s = h B,  no biases.            */
+/*                                                                           */
+/* The ranking must be reproduced bit for bit, so the float32 summation      */
+/* order is fixed.  One dot product of length n is taken as 64 interleaved   */
+/* partial sums: element i belongs to partial (i / 8) mod 64; each partial   */
+/* is a chain of fused multiply-adds over its elements in increasing i,      */
+/* starting from +0; the 64 partials are then combined pairwise with         */
+/* partner distance 32, 16, 8, 4, 2, 1 (every slot takes slot + partner      */
+/* slot, so after the last round slot 0 holds the total).                    */
+/* scores64 (optional) is the same network summed plainly in double.         */
+/* ------------------------------------------------------------------------- */
+static float dot_order64(const float *a, const float *b, int n)
+{
+    float p[64], nxt[64];
+    for (int l = 0; l < 64; ++l) p[l] = 0.0f;
+    for (int i = 0; i < n; ++i) {
+        int l = (i / 8) % 64;
+        p[l] = fmaf(a[i], b[i], p[l]);
+    }
+    for (int off = 32; off >= 1; off /= 2) {
+        for (int l = 0; l < 64; ++l) nxt[l] = p[l] + p[l ^ off];
+        memcpy(p, nxt, sizeof p);
+    }
+    return p[0];
+}
+
+int halo_ref_predict_scores(const float *x, int32_t T, int32_t d, int32_t r, int32_t G,
+                            const float *At /*[r][d]*/, const float *Bt /*[G][r]*/,
+                            float *scores /*[T][G]*/, double *scores64 /*[T][G] or NULL*/)
+{
+    if (!x || !At || !Bt || !scores || T < 0 || d < 1 || r < 1 || G < 1) return REF_ERR;
+    float *h = (float *)malloc(sizeof(float) * (size_t)r);
+    double *h64 = (double *)malloc(sizeof(double) * (size_t)r);
+    for (int t = 0; t < T; ++t) {
+        const float *xt = x + (size_t)t * d;
+#pragma omp parallel for schedule(static)
+        for (int j = 0; j < r; ++j) {
+            float v = dot_order64(xt, At + (size_t)j * d, d);
+            h[j] = v > 0.0f ? v : 0.0f;
+            if (scores64) {
+                double acc = 0.0;
+                for (int i = 0; i < d; ++i) acc += (double)xt[i] * (double)At[(size_t)j * d + i];
+                h64[j] = acc > 0.0 ? acc : 0.0;
+            }
+        }
+#pragma omp parallel for schedule(static)
+        for (int g = 0; g < G; ++g) {
+            scores[(size_t)t * G + g] = dot_order64(h, Bt + (size_t)g * r, r);
+            if (scores64) {
+                double acc = 0.0;
+                for (int j = 0; j < r; ++j) acc += h64[j] * (double)Bt[(size_t)g * r + j];
+                scores64[(size_t)t * G + g] = acc;
+            }
+        }
+    }
+    free(h);
+    free(h64);
+    return REF_OK;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Group mask, Sec. III-B.3.                                                  */
+/*                                                                           */
+/* Importance rank: groups sorted by predicted significance, highest first;  */
+/* equal values keep the lower group index first; NaN ranks after every      */
+/* number.  The group at rank p < K carries priority index p, is executed by */
+/* device prio_dev[p], and its partial result reaches the merge unless that  */
+/* device's upload was lost for this token.  Ranks >= K are not executed.    */
+/* ------------------------------------------------------------------------- */
+static int ranks_before(float sh, int h, float sg, int g)
+{
+    int nh = isnan(sh), ng = isnan(sg);
+    if (nh || ng) {
+        if (nh && ng) return h < g;
+        return ng;              /* a number ranks before a NaN */
+    }
+    if (sh > sg) return 1;
+    if (sh == sg) return h < g;
+    return 0;
+}
+
+int halo_ref_build_group_mask(const float *scores, int32_t T, int32_t G, int32_t K,
+                              const int8_t *prio_dev /*[K]*/, int32_t n_dev,
+                              const uint8_t *drop /*[T][n_dev] or NULL*/,
+                              int32_t *order /*[T][G]*/, int8_t *group_dev /*[T][G]*/,
+                              uint8_t *mask /*[T][G]*/, int32_t *surv_idx /*[T][K]*/,
+                              int32_t *n_surv /*[T]*/)
+{
+    if (!scores || !prio_dev || !order || !group_dev || !mask || !surv_idx || !n_surv)
+        return REF_ERR;
+    if (T < 0 || G < 1 || K < 0 || K > G || n_dev < 1) return REF_ERR;
+    for (int p = 0; p < K; ++p)
+        if (prio_dev[p] < 0 || prio_dev[p] >= n_dev) return REF_ERR;
+    for (int t = 0; t < T; ++t) {
+        const float *s = scores + (size_t)t * G;
+        int32_t *ord = order + (size_t)t * G;
+        for (int g = 0; g < G; ++g) {
+            int pos = 0;
+            for (int h = 0; h < G; ++h)
+                if (h != g && ranks_before(s[h], h, s[g], g)) ++pos;
+            ord[pos] = g;
+        }
+        for (int g = 0; g < G; ++g) {
+            group_dev[(size_t)t * G + g] = -1;
+            mask[(size_t)t * G + g] = 0;
+        }
+        for (int p = 0; p < K; ++p) {
+            int g = ord[p];
+            int dev = prio_dev[p];
+            group_dev[(size_t)t * G + g] = (int8_t)dev;
+            int lost = drop ? (drop[(size_t)t * n_dev + dev] != 0) : 0;
+            mask[(size_t)t * G + g] = lost ? 0 : 1;
+        }
+        int c = 0;
+        for (int g = 0; g < G; ++g)
+            if (mask[(size_t)t * G + g]) surv_idx[(size_t)t * K + c++] = g;
+        n_surv[t] = c;
+        for (; c < K; ++c) surv_idx[(size_t)t * K + c] = -1;
+    }
+    return REF_OK;
+}
+
+/* ------------------------------------------------------------------------- */
+/* One neuron group's partial result (Sec. II-A "Neuron group"), in double:  */
+/*   partial_g(x)[j] = sum_{m in g} WdT[m][j] * SiLU(Wg[m].x) * (Wu[m].x)     */
+/* with SiLU(z) = z / (1 + exp(-z)).                                          */
+/* ------------------------------------------------------------------------- */
+static void group_partial(const float *xt, int d, int gs, const float *Wg_g,
+                          const float *Wu_g, const float *WdT_g, double *act, double *out)
+{
+#pragma omp parallel for schedule(static)
+    for (int m = 0; m < gs; ++m) {
+        double gate = 0.0, up = 0.0;
+        const float *wg = Wg_g + (size_t)m * d, *wu = Wu_g + (size_t)m * d;
+        for (int i = 0; i < d; ++i) {
+            gate += (double)wg[i] * (double)xt[i];
+            up += (double)wu[i] * (double)xt[i];
+        }
+        act[m] = gate / (1.0 + exp(-gate)) * up;
+    }
+#pragma omp parallel for schedule(static)
+    for (int j = 0; j < d; ++j) {
+        double acc = 0.0;
+        for (int m = 0; m < gs; ++m) acc += act[m] * (double)WdT_g[(size_t)m * d + j];
+        out[j] = acc;
+    }
+}
+
+/* partials[t][g][:] for every (token, group); groups with mask 0 give exact zeros.
+   mask == NULL means every group is executed (the dense block, group by group). */
+int halo_ref_group_partials(const float *x, int32_t T, int32_t d, int32_t G, int32_t gs,
+                            const float *Wg, const float *Wu, const float *WdT,
+                            const uint8_t *mask /*[T][G] or NULL*/, double *partials /*[T][G][d]*/)
+{
+    if (!x || !Wg || !Wu || !WdT || !partials || T < 0 || d < 1 || G < 1 || gs < 1) return REF_ERR;
+    double *act = (double *)malloc(sizeof(double) * (size_t)gs);
+    for (int t = 0; t < T; ++t)
+        for (int g = 0; g < G; ++g) {
+            double *out = partials + ((size_t)t * G + g) * d;
+            if (mask && !mask[(size_t)t * G + g]) {
+                for (int j = 0; j < d; ++j) out[j] = 0.0;
+                continue;
+            }
+            size_t off = (size_t)g * gs * d;
+            group_partial(x + (size_t)t * d, d, gs, Wg + off, Wu + off, WdT + off, act, out);
+        }
+    free(act);
+    return REF_OK;
+}
+
+/* y[t] = sum over surviving groups (mask 1), ascending group index, of their partials. */
+int halo_ref_group_sparse_ffn(const float *x, int32_t T, int32_t d, int32_t G, int32_t gs,
+                              const float *Wg, const float *Wu, const float *WdT,
+                              const uint8_t *mask /*[T][G] or NULL*/, double *y /*[T][d]*/)
+{
+    if (!x || !Wg || !Wu || !WdT || !y || T < 0 || d < 1 || G < 1 || gs < 1) return REF_ERR;
+    double *act = (double *)malloc(sizeof(double) * (size_t)gs);
+    double *part = (double *)malloc(sizeof(double) * (size_t)d);
+    for (int t = 0; t < T; ++t) {
+        double *yt = y + (size_t)t * d;
+        for (int j = 0; j < d; ++j) yt[j] = 0.0;
+        for (int g = 0; g < G; ++g) {
+            if (mask && !mask[(size_t)t * G + g]) continue;
+            size_t off = (size_t)g * gs * d;
+            group_partial(x + (size_t)t * d, d, gs, Wg + off, Wu + off, WdT + off, act, part);
+            for (int j = 0; j < d; ++j) yt[j] += part[j];
+        }
+    }
+    free(act);
+    free(part);
+    return REF_OK;
+}
+
+/* The whole pass for one FFN block: predictor -> mask -> group-sparse FFN
+   (Sec. III-A, generation phase: Pred, Load, Comp and the merge, for one block). */
+int halo_ref_ffn_forward(const float *x, int32_t T, int32_t d, int32_t G, int32_t gs, int32_t r,
+                         const float *At, const float *Bt, const float *Wg, const float *Wu,
+                         const float *WdT, int32_t K, const int8_t *prio_dev, int32_t n_dev,
+                         const uint8_t *drop, double *y, float *scores, int32_t *order,
+                         int8_t *group_dev, uint8_t *mask, int32_t *surv_idx, int32_t *n_surv)
+{
+    int rc = halo_ref_predict_scores(x, T, d, r, G, At, Bt, scores, NULL);
+    if (rc) return rc;
+    rc = halo_ref_build_group_mask(scores, T, G, K, prio_dev, n_dev, drop, order, group_dev,
+                                   mask, surv_idx, n_surv);
+    if (rc) return rc;
+    return halo_ref_group_sparse_ffn(x, T, d, G, gs, Wg, Wu, WdT, mask, y);
+}
