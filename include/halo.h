@@ -1,0 +1,162 @@
+/*
+ * halo.h -- C boundary of the MI355X (gfx950) implementation of HALO's per-token
+ * neuron-group-sparse FFN path:  predictor -> group mask -> group-sparse SwiGLU FFN.
+ *
+ * Conventions (all entry points unless stated otherwise)
+ *   - Every data pointer is a DEVICE pointer owned by the caller, 16-byte aligned,
+ *     row-major and dense.  The library never allocates or frees device memory:
+ *     scratch comes from the caller's `workspace` (size from halo_workspace_bytes).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
+ *     validate their arguments on the host, enqueue kernels on that stream and
+ *     return without synchronising; HALO_OK means "enqueued".
+ *   - On any error nothing is enqueued and no output is touched.  No C++ exception
+ *     crosses this boundary.
+ *   - Weight element type is given by halo_shape.dtype: HALO_F32 (float) or
+ *     HALO_BF16 (bfloat16: the upper 16 bits of an IEEE float, round-to-nearest-even).
+ *     Hidden states x and the output y use the same type.  Scores are always float.
+ *   - Limits: d % 8 == 0, rank % 8 == 0, ffn == n_groups * group_size,
+ *     1 <= n_groups <= 1024, 1 <= n_dev <= 127, T >= 0 (T == 0 is a no-op).
+ *
+ * Weight layout ("FFN weights partitioned into neuron groups", paper Sec. II-A):
+ * neuron group g owns rows [g*group_size, (g+1)*group_size) of
+ *   Wg  [ffn][d]  gate projection,
+ *   Wu  [ffn][d]  up projection,
+ *   WdT [ffn][d]  down projection stored neuron-major (the transpose of the usual
+ *                 [d][ffn] matrix),
+ * so one group is three contiguous blocks of group_size*d elements.
+ */
+#ifndef HALO_H
+#define HALO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    HALO_OK = 0,
+    HALO_ERR_NULL = -1,      /* a required pointer is NULL */
+    HALO_ERR_SHAPE = -2,     /* shape fields inconsistent or outside the limits */
+    HALO_ERR_DTYPE = -3,     /* unknown dtype */
+    HALO_ERR_ARG = -4,       /* scalar argument out of range (k_keep, n_dev, T, alignment) */
+    HALO_ERR_WORKSPACE = -5, /* workspace NULL or smaller than halo_workspace_bytes */
+    HALO_ERR_HIP = -6        /* a HIP runtime call failed (launch error) */
+} halo_status;
+
+typedef enum { HALO_F32 = 0, HALO_BF16 = 1 } halo_dtype;
+
+typedef struct {
+    int32_t d;          /* hidden dimension D */
+    int32_t ffn;        /* FFN intermediate dimension */
+    int32_t group_size; /* neurons per group */
+    int32_t n_groups;   /* N_g = ffn / group_size */
+    int32_t rank;       /* predictor hidden dimension */
+    int32_t dtype;      /* halo_dtype */
+} halo_shape;
+
+/* Human-readable name of a status code (static string, never NULL). */
+const char *halo_status_string(int status);
+
+/*
+ * PLR-aware ratio-guided scheduler (paper Alg. 3 and the worked example of
+ * Sec. III-B.4).  HOST pointers, no GPU work.
+ *   n_prio   number of priority indices to distribute (0 = most significant);
+ *            the path uses n_prio = k_keep, i.e. the kept ranks are distributed.
+ *   ratios   [n_dev] workload ratios, non-negative (need not be normalised to
+ *            rounding error), or NULL for the homogeneous setting 1/n_dev.
+ *   plr      [n_dev] packet-loss rates in [0,1].
+ *   prio_dev [n_prio] out: device executing priority index p.  Devices are taken
+ *            in ascending PLR (ties: lower device index); device k of that order
+ *            receives the contiguous run [b_{k-1}, b_k), b_k = floor(n_prio *
+ *            (r_1+..+r_k) + 1/2), the last cut forced to n_prio.
+ * Errors: HALO_ERR_NULL, HALO_ERR_ARG (n_prio < 0, n_dev outside 1..127, NaN,
+ * negative ratio, PLR outside [0,1]).
+ */
+int halo_build_schedule(int32_t n_prio, int32_t n_dev, const double *ratios,
+                        const double *plr, int8_t *prio_dev);
+
+/*
+ * Upper bound, in bytes, of the scratch any entry point below needs for T tokens
+ * of this shape with k_keep groups kept per token.  Returns 0 for invalid arguments.
+ */
+size_t halo_workspace_bytes(const halo_shape *shape, int32_t T, int32_t k_keep);
+
+/*
+ * Semantic-aware predictor (paper Sec. III-B.2): one significance value per
+ * neuron group from the hidden state, through a two-matrix network
+ *     h = ReLU(x A),  scores = h B      (A: d x rank, B: rank x n_groups, no bias).
+ *   x      [T][d]          hidden states (dtype)
+ *   At     [rank][d]       A transposed (dtype)
+ *   Bt     [n_groups][rank] B transposed (dtype)
+ *   scores [T][n_groups]   out, float
+ * Arithmetic is float32 with a fixed summation order so that rankings are
+ * reproducible bit for bit: a dot product of length n keeps 64 partial sums,
+ * element i going to partial (i/8) mod 64 by fused multiply-add in increasing i
+ * from +0; partials are combined pairwise at distances 32,16,8,4,2,1.
+ * Uses workspace for h ([T][rank] float).
+ */
+int halo_predict_scores(const halo_shape *shape, const void *x, int32_t T, const void *At,
+                        const void *Bt, float *scores, void *workspace, size_t ws_bytes,
+                        void *stream);
+
+/*
+ * Importance rank -> priority index -> device -> surviving set (paper Sec. III-B.3:
+ * the Pred step's mapping, and the relaxed merge that skips lost uploads).
+ *   scores    [T][G] float
+ *   k_keep    groups executed per token (0..G): the k_keep highest-scoring groups.
+ *             Ranking: score descending, equal scores by lower group index, NaN last.
+ *   prio_dev  [k_keep] int8: device executing the group of rank p (from
+ *             halo_build_schedule, copied to the device by the caller); values must
+ *             lie in [0, n_dev) -- not checked on the device beyond a clamp-free read
+ *             of drop[], so the caller must guarantee it.
+ *   drop      [T][n_dev] uint8, non-zero = that device's partial result for that
+ *             token is lost; NULL = nothing is lost.
+ * Outputs (each may be NULL if not wanted, except mask):
+ *   order     [T][G] int32  group index at each rank (rank 0 = most significant)
+ *   group_dev [T][G] int8   device of each group, -1 if not executed
+ *   mask      [T][G] uint8  1 = executed and not lost (survives), else 0
+ *   surv_idx  [T][k_keep] int32 surviving group indices ascending, padded with -1
+ *   n_surv    [T] int32     number of surviving groups
+ */
+int halo_build_group_mask(const float *scores, int32_t T, int32_t G, int32_t k_keep,
+                          const int8_t *prio_dev, int32_t n_dev, const uint8_t *drop,
+                          int32_t *order, int8_t *group_dev, uint8_t *mask,
+                          int32_t *surv_idx, int32_t *n_surv, void *stream);
+
+/*
+ * Group-sparse SwiGLU FFN (paper Sec. II-A "Neuron group"; merge = plain sum of the
+ * groups' partial results, Sec. III-B.3):
+ *     y[t] = sum_{g : mask[t][g] != 0}  sum_{m in g}  WdT[m][:] * SiLU(Wg[m].x[t]) * (Wu[m].x[t])
+ * Only groups that survive for at least one token are read from memory; a group
+ * with mask 0 contributes exactly zero to that token; a token with no surviving
+ * group gets y[t] = 0.
+ *   x [T][d], Wg/Wu/WdT [ffn][d], mask [T][n_groups] uint8, y [T][d] out (dtype).
+ * Accumulation is float32; for bf16 with many tokens the matrix-core path rounds
+ * the activation to bf16 before the down projection.
+ */
+int halo_group_sparse_ffn(const halo_shape *shape, const void *x, int32_t T, const void *Wg,
+                          const void *Wu, const void *WdT, const uint8_t *mask, void *y,
+                          void *workspace, size_t ws_bytes, void *stream);
+
+/*
+ * One whole pass for an FFN block on one stream, no host synchronisation:
+ * halo_predict_scores -> halo_build_group_mask -> halo_group_sparse_ffn
+ * (paper Sec. III-A generation phase: Pred, Load, Comp and the merge for one block).
+ * x_pred is the hidden state the predictor reads ([T][d]; pass x itself to predict
+ * from the block's own input, or the previous layer's input for the paper's
+ * one-layer-ahead prediction).  Optional outputs (scores, order, group_dev, mask,
+ * surv_idx, n_surv) may each be NULL; they are then kept in the workspace.
+ */
+int halo_ffn_forward(const halo_shape *shape, const void *x, const void *x_pred, int32_t T,
+                     const void *At, const void *Bt, const void *Wg, const void *Wu,
+                     const void *WdT, int32_t k_keep, const int8_t *prio_dev, int32_t n_dev,
+                     const uint8_t *drop, void *y, float *scores, int32_t *order,
+                     int8_t *group_dev, uint8_t *mask, int32_t *surv_idx, int32_t *n_surv,
+                     void *workspace, size_t ws_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HALO_H */

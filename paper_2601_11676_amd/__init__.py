@@ -1,0 +1,10 @@
+"""MI355X-native HALO group-sparse FFN path: thin Python binding over libhalo.so.
+
+The functions here have the names of the C entry points (see include/halo.h) and do
+argument marshalling only; every step of the path runs in the HIP kernels.  PyTorch
+tensors are used for device memory and streams, nothing else.
+"""
+from .binding import (  # noqa: F401
+    HaloError, Shape, halo_build_schedule, halo_workspace_bytes, halo_predict_scores,
+    halo_build_group_mask, halo_group_sparse_ffn, halo_ffn_forward, library_path, load_library,
+)

@@ -1,0 +1,156 @@
+"""ctypes binding of libhalo.so: marshalling only (pointers, sizes, the current stream)."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libhalo.so")
+_lib = None
+
+HALO_F32, HALO_BF16 = 0, 1
+
+
+class HaloError(RuntimeError):
+    def __init__(self, fn: str, code: int):
+        self.code = code
+        msg = load_library().halo_status_string(code).decode()
+        super().__init__(f"{fn} failed: {msg} ({code})")
+
+
+class _CShape(C.Structure):
+    _fields_ = [("d", C.c_int32), ("ffn", C.c_int32), ("group_size", C.c_int32),
+                ("n_groups", C.c_int32), ("rank", C.c_int32), ("dtype", C.c_int32)]
+
+
+class Shape:
+    """halo_shape: d, ffn, group_size, n_groups, rank, dtype ('f32' | 'bf16')."""
+
+    def __init__(self, d: int, ffn: int, group_size: int, rank: int, dtype: str = "bf16",
+                 n_groups: Optional[int] = None):
+        self.d, self.ffn, self.group_size, self.rank = d, ffn, group_size, rank
+        self.n_groups = ffn // group_size if n_groups is None else n_groups
+        self.dtype = dtype
+        code = {"f32": HALO_F32, "bf16": HALO_BF16}.get(dtype, -1)
+        self.c = _CShape(d, ffn, group_size, self.n_groups, rank, code)
+
+    @property
+    def torch_dtype(self):
+        return torch.float32 if self.dtype == "f32" else torch.bfloat16
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libhalo.so (built in-tree by paper_2601_11676_amd.build).  There is no fallback:
+    a missing library is an error."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(f"{_LIB_PATH} is missing: run `python -m paper_2601_11676_amd.build`")
+    lib = C.CDLL(_LIB_PATH)
+    vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
+    ps = C.POINTER(_CShape)
+    lib.halo_status_string.restype = C.c_char_p
+    lib.halo_status_string.argtypes = [C.c_int]
+    lib.halo_build_schedule.restype = C.c_int
+    lib.halo_build_schedule.argtypes = [i32, i32, vp, vp, vp]
+    lib.halo_workspace_bytes.restype = sz
+    lib.halo_workspace_bytes.argtypes = [ps, i32, i32]
+    lib.halo_predict_scores.restype = C.c_int
+    lib.halo_predict_scores.argtypes = [ps, vp, i32, vp, vp, vp, vp, sz, vp]
+    lib.halo_build_group_mask.restype = C.c_int
+    lib.halo_build_group_mask.argtypes = [vp, i32, i32, i32, vp, i32, vp, vp, vp, vp, vp, vp, vp]
+    lib.halo_group_sparse_ffn.restype = C.c_int
+    lib.halo_group_sparse_ffn.argtypes = [ps, vp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.halo_ffn_forward.restype = C.c_int
+    lib.halo_ffn_forward.argtypes = [ps, vp, vp, i32, vp, vp, vp, vp, vp, i32, vp, i32, vp, vp,
+                                     vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    _lib = lib
+    return lib
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("device tensor expected")
+    if not t.is_contiguous():
+        raise ValueError("contiguous tensor expected")
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> C.c_void_p:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+def _check(fn: str, rc: int):
+    if rc != 0:
+        raise HaloError(fn, rc)
+
+
+def halo_build_schedule(n_prio: int, plr: Sequence[float],
+                        ratios: Optional[Sequence[float]] = None) -> np.ndarray:
+    """Host-only (Alg. 3).  Returns prio_dev as an int8 numpy array of length n_prio."""
+    plr_a = np.ascontiguousarray(np.asarray(plr, dtype=np.float64))
+    rat_a = None if ratios is None else np.ascontiguousarray(np.asarray(ratios, dtype=np.float64))
+    if rat_a is not None and rat_a.shape != plr_a.shape:
+        raise ValueError("ratios and plr must have one entry per device")
+    out = np.zeros(max(int(n_prio), 0), dtype=np.int8)
+    rc = load_library().halo_build_schedule(
+        int(n_prio), int(plr_a.shape[0]),
+        None if rat_a is None else rat_a.ctypes.data_as(C.c_void_p),
+        plr_a.ctypes.data_as(C.c_void_p), out.ctypes.data_as(C.c_void_p))
+    _check("halo_build_schedule", rc)
+    return out
+
+
+def halo_workspace_bytes(shape: Shape, T: int, k_keep: int) -> int:
+    return int(load_library().halo_workspace_bytes(C.byref(shape.c), int(T), int(k_keep)))
+
+
+def halo_predict_scores(shape: Shape, x, At, Bt, scores, workspace, stream=None) -> None:
+    T = x.shape[0]
+    rc = load_library().halo_predict_scores(C.byref(shape.c), _ptr(x), T, _ptr(At), _ptr(Bt),
+                                            _ptr(scores), _ptr(workspace), workspace.numel(),
+                                            _stream(stream))
+    _check("halo_predict_scores", rc)
+
+
+def halo_build_group_mask(scores, k_keep: int, prio_dev, n_dev: int, drop, mask, order=None,
+                          group_dev=None, surv_idx=None, n_surv=None, stream=None) -> None:
+    T, G = scores.shape
+    rc = load_library().halo_build_group_mask(_ptr(scores), T, G, int(k_keep), _ptr(prio_dev),
+                                              int(n_dev), _ptr(drop), _ptr(order), _ptr(group_dev),
+                                              _ptr(mask), _ptr(surv_idx), _ptr(n_surv),
+                                              _stream(stream))
+    _check("halo_build_group_mask", rc)
+
+
+def halo_group_sparse_ffn(shape: Shape, x, Wg, Wu, WdT, mask, y, workspace, stream=None) -> None:
+    T = x.shape[0]
+    rc = load_library().halo_group_sparse_ffn(C.byref(shape.c), _ptr(x), T, _ptr(Wg), _ptr(Wu),
+                                              _ptr(WdT), _ptr(mask), _ptr(y), _ptr(workspace),
+                                              workspace.numel(), _stream(stream))
+    _check("halo_group_sparse_ffn", rc)
+
+
+def halo_ffn_forward(shape: Shape, x, At, Bt, Wg, Wu, WdT, k_keep: int, prio_dev, n_dev: int,
+                     drop, y, workspace, x_pred=None, scores=None, order=None, group_dev=None,
+                     mask=None, surv_idx=None, n_surv=None, stream=None) -> None:
+    T = x.shape[0]
+    xp = x if x_pred is None else x_pred
+    rc = load_library().halo_ffn_forward(
+        C.byref(shape.c), _ptr(x), _ptr(xp), T, _ptr(At), _ptr(Bt), _ptr(Wg), _ptr(Wu), _ptr(WdT),
+        int(k_keep), _ptr(prio_dev), int(n_dev), _ptr(drop), _ptr(y), _ptr(scores), _ptr(order),
+        _ptr(group_dev), _ptr(mask), _ptr(surv_idx), _ptr(n_surv), _ptr(workspace),
+        workspace.numel(), _stream(stream))
+    _check("halo_ffn_forward", rc)

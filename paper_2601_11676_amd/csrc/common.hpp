@@ -1,0 +1,81 @@
+// Device-side helpers shared by the HIP kernels (gfx950, wave64).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace halo {
+
+typedef uint16_t bf16_t;   // storage only: upper half of an IEEE float
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // one 16-byte load
+
+constexpr int kWave = 64;
+
+__device__ __forceinline__ float bf16_lo(uint32_t v) { return __uint_as_float(v << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t v) { return __uint_as_float(v & 0xffff0000u); }
+
+// float -> bf16, round to nearest even; NaN stays NaN (quiet).
+__device__ __forceinline__ bf16_t f32_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x0040u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+// Eight consecutive elements -> eight floats.  p must be 16-byte aligned.
+__device__ __forceinline__ void load8(const float *__restrict__ p, float (&o)[8])
+{
+    float4 a = *reinterpret_cast<const float4 *>(p);
+    float4 b = *reinterpret_cast<const float4 *>(p + 4);
+    o[0] = a.x; o[1] = a.y; o[2] = a.z; o[3] = a.w;
+    o[4] = b.x; o[5] = b.y; o[6] = b.z; o[7] = b.w;
+}
+
+__device__ __forceinline__ void unpack8(const u32x4 &v, float (&o)[8])
+{
+    o[0] = bf16_lo(v.x); o[1] = bf16_hi(v.x);
+    o[2] = bf16_lo(v.y); o[3] = bf16_hi(v.y);
+    o[4] = bf16_lo(v.z); o[5] = bf16_hi(v.z);
+    o[6] = bf16_lo(v.w); o[7] = bf16_hi(v.w);
+}
+
+__device__ __forceinline__ void load8(const bf16_t *__restrict__ p, float (&o)[8])
+{
+    u32x4 v = *reinterpret_cast<const u32x4 *>(p);
+    unpack8(v, o);
+}
+
+__device__ __forceinline__ void store_out(float *p, float v) { *p = v; }
+__device__ __forceinline__ void store_out(bf16_t *p, float v) { *p = f32_to_bf16(v); }
+
+__device__ __forceinline__ void store8(float *p, const float (&v)[8])
+{
+    *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
+    *reinterpret_cast<float4 *>(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
+}
+
+__device__ __forceinline__ void store8(bf16_t *p, const float (&v)[8])
+{
+    u32x4 o;
+    o.x = (uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16);
+    o.y = (uint32_t)f32_to_bf16(v[2]) | ((uint32_t)f32_to_bf16(v[3]) << 16);
+    o.z = (uint32_t)f32_to_bf16(v[4]) | ((uint32_t)f32_to_bf16(v[5]) << 16);
+    o.w = (uint32_t)f32_to_bf16(v[6]) | ((uint32_t)f32_to_bf16(v[7]) << 16);
+    *reinterpret_cast<u32x4 *>(p) = o;
+}
+
+// Butterfly sum over the 64 lanes of a wave, partner distance 32,16,8,4,2,1.
+// Every lane ends with the same value (float addition is commutative).
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v = v + __shfl_xor(v, off, kWave);
+    return v;
+}
+
+__device__ __forceinline__ float silu_mul(float gate, float up)
+{
+    return gate / (1.0f + expf(-gate)) * up;
+}
+
+}  // namespace halo

@@ -1,0 +1,213 @@
+// C boundary of the library: argument validation, workspace carving, kernel enqueue.
+// See include/halo.h for the contract of every entry point.
+#include "../../include/halo.h"
+
+#include <cmath>
+
+#include "kernels.hpp"
+
+namespace {
+
+using namespace halo;
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+int check_shape(const halo_shape *s)
+{
+    if (!s) return HALO_ERR_NULL;
+    if (s->dtype != HALO_F32 && s->dtype != HALO_BF16) return HALO_ERR_DTYPE;
+    if (s->d < 8 || s->d % 8 || s->rank < 8 || s->rank % 8) return HALO_ERR_SHAPE;
+    if (s->group_size < 1 || s->n_groups < 1 || s->n_groups > 1024) return HALO_ERR_SHAPE;
+    if ((long long)s->n_groups * s->group_size != (long long)s->ffn) return HALO_ERR_SHAPE;
+    return HALO_OK;
+}
+
+inline bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+// Carves the caller's workspace.  The same routine sizes it (base == nullptr).
+struct Workspace {
+    float *h = nullptr;
+    float *scores = nullptr;
+    int32_t *order = nullptr;
+    int8_t *group_dev = nullptr;
+    uint8_t *mask = nullptr;
+    int32_t *surv_idx = nullptr;
+    int32_t *n_surv = nullptr;
+    DecodeScratch dec{};
+    size_t bytes = 0;
+
+    Workspace(const halo_shape &s, int T, int K, void *base)
+    {
+        char *p = static_cast<char *>(base);
+        size_t off = 0;
+        auto take = [&](size_t n) -> char * {
+            char *r = p ? p + off : nullptr;
+            off += align_up(n ? n : 1);
+            return r;
+        };
+        const size_t t = (size_t)(T > 0 ? T : 1), G = (size_t)s.n_groups;
+        h = reinterpret_cast<float *>(take(t * s.rank * sizeof(float)));
+        scores = reinterpret_cast<float *>(take(t * G * sizeof(float)));
+        order = reinterpret_cast<int32_t *>(take(t * G * sizeof(int32_t)));
+        group_dev = reinterpret_cast<int8_t *>(take(t * G));
+        mask = reinterpret_cast<uint8_t *>(take(t * G));
+        surv_idx = reinterpret_cast<int32_t *>(take(t * (size_t)(K > 0 ? K : 1) * sizeof(int32_t)));
+        n_surv = reinterpret_cast<int32_t *>(take(t * sizeof(int32_t)));
+        dec.ulist = reinterpret_cast<int32_t *>(take(G * sizeof(int32_t)));
+        dec.meta = reinterpret_cast<int32_t *>(take(256 * sizeof(int32_t)));
+        dec.act = reinterpret_cast<float *>(take(t * (size_t)s.ffn * sizeof(float)));
+        dec.n_split = decode_n_split((int)t, s.d);
+        dec.partial = reinterpret_cast<float *>(take((size_t)dec.n_split * t * s.d * sizeof(float)));
+        bytes = off;
+    }
+};
+
+}  // namespace
+
+extern "C" {
+
+const char *halo_status_string(int status)
+{
+    switch (status) {
+    case HALO_OK: return "ok";
+    case HALO_ERR_NULL: return "required pointer is NULL";
+    case HALO_ERR_SHAPE: return "inconsistent or unsupported shape";
+    case HALO_ERR_DTYPE: return "unknown dtype";
+    case HALO_ERR_ARG: return "argument out of range";
+    case HALO_ERR_WORKSPACE: return "workspace missing or too small";
+    case HALO_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+    }
+}
+
+int halo_build_schedule(int32_t n_prio, int32_t n_dev, const double *ratios, const double *plr,
+                        int8_t *prio_dev)
+{
+    if (!plr || (n_prio > 0 && !prio_dev)) return HALO_ERR_NULL;
+    if (n_prio < 0 || n_dev < 1 || n_dev > 127) return HALO_ERR_ARG;
+    for (int i = 0; i < n_dev; ++i) {
+        if (std::isnan(plr[i]) || plr[i] < 0.0 || plr[i] > 1.0) return HALO_ERR_ARG;
+        if (ratios && (std::isnan(ratios[i]) || ratios[i] < 0.0)) return HALO_ERR_ARG;
+    }
+    // devices in ascending PLR, ties by index: the position of device i is the number
+    // of devices that precede it in that order
+    int sorted[127];
+    for (int i = 0; i < n_dev; ++i) {
+        int pos = 0;
+        for (int j = 0; j < n_dev; ++j)
+            if (plr[j] < plr[i] || (plr[j] == plr[i] && j < i)) ++pos;
+        sorted[pos] = i;
+    }
+    long long begin = 0;
+    double cumulative = 0.0;
+    for (int k = 0; k < n_dev; ++k) {
+        long long end;
+        if (k + 1 == n_dev) {
+            end = n_prio;
+        } else if (!ratios) {
+            end = (2LL * n_prio * (k + 1) + n_dev) / (2LL * n_dev);
+        } else {
+            cumulative += ratios[sorted[k]];
+            volatile double scaled = (double)n_prio * cumulative;   // keep multiply and add unfused
+            end = (long long)std::floor(scaled + 0.5);
+        }
+        if (end > n_prio) end = n_prio;
+        if (end < begin) end = begin;
+        for (long long p = begin; p < end; ++p) prio_dev[p] = (int8_t)sorted[k];
+        begin = end;
+    }
+    return HALO_OK;
+}
+
+size_t halo_workspace_bytes(const halo_shape *shape, int32_t T, int32_t k_keep)
+{
+    if (check_shape(shape) != HALO_OK || T < 0 || k_keep < 0 || k_keep > shape->n_groups) return 0;
+    return Workspace(*shape, T, k_keep, nullptr).bytes;
+}
+
+int halo_predict_scores(const halo_shape *shape, const void *x, int32_t T, const void *At,
+                        const void *Bt, float *scores, void *workspace, size_t ws_bytes,
+                        void *stream)
+{
+    int rc = check_shape(shape);
+    if (rc) return rc;
+    if (T < 0) return HALO_ERR_ARG;
+    if (T == 0) return HALO_OK;
+    if (!x || !At || !Bt || !scores) return HALO_ERR_NULL;
+    if (misaligned(x) || misaligned(At) || misaligned(Bt) || misaligned(scores)) return HALO_ERR_ARG;
+    if (!workspace || misaligned(workspace)) return HALO_ERR_WORKSPACE;
+    Workspace ws(*shape, T, 0, workspace);
+    if (ws_bytes < ws.bytes) return HALO_ERR_WORKSPACE;
+    hipError_t e = launch_predictor(shape->dtype, x, T, shape->d, shape->rank, shape->n_groups, At, Bt,
+                                    ws.h, scores, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? HALO_OK : HALO_ERR_HIP;
+}
+
+int halo_build_group_mask(const float *scores, int32_t T, int32_t G, int32_t k_keep,
+                          const int8_t *prio_dev, int32_t n_dev, const uint8_t *drop,
+                          int32_t *order, int8_t *group_dev, uint8_t *mask, int32_t *surv_idx,
+                          int32_t *n_surv, void *stream)
+{
+    if (G < 1 || G > 1024) return HALO_ERR_SHAPE;
+    if (T < 0 || k_keep < 0 || k_keep > G || n_dev < 1 || n_dev > 127) return HALO_ERR_ARG;
+    if (T == 0) return HALO_OK;
+    if (!scores || !mask || (k_keep > 0 && !prio_dev)) return HALO_ERR_NULL;
+    hipError_t e = launch_group_mask(scores, T, G, k_keep, prio_dev, n_dev, drop, order, group_dev,
+                                     mask, surv_idx, n_surv, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? HALO_OK : HALO_ERR_HIP;
+}
+
+int halo_group_sparse_ffn(const halo_shape *shape, const void *x, int32_t T, const void *Wg,
+                          const void *Wu, const void *WdT, const uint8_t *mask, void *y,
+                          void *workspace, size_t ws_bytes, void *stream)
+{
+    int rc = check_shape(shape);
+    if (rc) return rc;
+    if (T < 0) return HALO_ERR_ARG;
+    if (T == 0) return HALO_OK;
+    if (!x || !Wg || !Wu || !WdT || !mask || !y) return HALO_ERR_NULL;
+    if (misaligned(x) || misaligned(Wg) || misaligned(Wu) || misaligned(WdT) || misaligned(y))
+        return HALO_ERR_ARG;
+    if (!workspace || misaligned(workspace)) return HALO_ERR_WORKSPACE;
+    Workspace ws(*shape, T, 0, workspace);
+    if (ws_bytes < ws.bytes) return HALO_ERR_WORKSPACE;
+    hipError_t e = launch_ffn_decode(shape->dtype, x, T, shape->d, shape->n_groups, shape->group_size,
+                                     Wg, Wu, WdT, mask, y, ws.dec, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? HALO_OK : HALO_ERR_HIP;
+}
+
+int halo_ffn_forward(const halo_shape *shape, const void *x, const void *x_pred, int32_t T,
+                     const void *At, const void *Bt, const void *Wg, const void *Wu,
+                     const void *WdT, int32_t k_keep, const int8_t *prio_dev, int32_t n_dev,
+                     const uint8_t *drop, void *y, float *scores, int32_t *order,
+                     int8_t *group_dev, uint8_t *mask, int32_t *surv_idx, int32_t *n_surv,
+                     void *workspace, size_t ws_bytes, void *stream)
+{
+    int rc = check_shape(shape);
+    if (rc) return rc;
+    if (T < 0 || k_keep < 0 || k_keep > shape->n_groups || n_dev < 1 || n_dev > 127) return HALO_ERR_ARG;
+    if (T == 0) return HALO_OK;
+    if (!x || !x_pred || !At || !Bt || !Wg || !Wu || !WdT || !y || (k_keep > 0 && !prio_dev))
+        return HALO_ERR_NULL;
+    if (misaligned(x) || misaligned(x_pred) || misaligned(At) || misaligned(Bt) || misaligned(Wg) ||
+        misaligned(Wu) || misaligned(WdT) || misaligned(y) || (scores && misaligned(scores)))
+        return HALO_ERR_ARG;
+    if (!workspace || misaligned(workspace)) return HALO_ERR_WORKSPACE;
+    Workspace ws(*shape, T, k_keep, workspace);
+    if (ws_bytes < ws.bytes) return HALO_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    float *sc = scores ? scores : ws.scores;
+    uint8_t *mk = mask ? mask : ws.mask;
+    hipError_t e = launch_predictor(shape->dtype, x_pred, T, shape->d, shape->rank, shape->n_groups,
+                                    At, Bt, ws.h, sc, s);
+    if (e != hipSuccess) return HALO_ERR_HIP;
+    e = launch_group_mask(sc, T, shape->n_groups, k_keep, prio_dev, n_dev, drop, order, group_dev, mk,
+                          surv_idx, n_surv, s);
+    if (e != hipSuccess) return HALO_ERR_HIP;
+    e = launch_ffn_decode(shape->dtype, x, T, shape->d, shape->n_groups, shape->group_size, Wg, Wu,
+                          WdT, mk, y, ws.dec, s);
+    return e == hipSuccess ? HALO_OK : HALO_ERR_HIP;
+}
+
+}  // extern "C"
