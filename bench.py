@@ -1,0 +1,242 @@
+#!/usr/bin/env python3
+"""Benchmark of the HALO group-sparse FFN path on one MI355X.
+
+One "step" = one whole pass (predictor -> group mask -> group-sparse SwiGLU FFN, i.e.
+halo_ffn_forward) over one batch of synthetic input.  The default workload is the
+LLaMA-7B-shape single-layer decode: d=4096, ffn=11008 as 86 groups of 128, bf16,
+one token per step, 43 groups kept, 4 simulated devices with loss rates
+{0, 0.05, 0.1, 0.2}, fresh hidden state and loss outcomes per step.
+
+Weights: the layer is replicated into --copies independent copies visited round-robin,
+so that consecutive steps read different HBM (a real decode walks 32 different layers
+per token; one 135 MB half-layer would otherwise sit in the 256 MB Infinity Cache).
+
+Timing: all inputs are resident in HBM before the clock starts.  The K timed steps are
+captured once into a HIP graph (the loop is launch-bound otherwise) and replayed between
+two device synchronisations.  A second, eager pass over the same K steps brackets the
+dominant kernel (FFN gate/up) with HIP events for the roofline figure.  The CPU oracle
+is then timed on a bounded sample of the same steps and its output compared.
+
+Prints one JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def read_traffic(kernel: str, workload: str):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary, or None."""
+    path = os.path.join(ROOT, "profiles", f"pmc_{kernel}_{workload}.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        if line.startswith("traffic_bytes_per_launch"):
+            try:
+                return float(line.split()[1])
+            except (IndexError, ValueError):
+                return None
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=1024)
+    ap.add_argument("--warmup", type=int, default=64)
+    ap.add_argument("--copies", type=int, default=16, help="independent weight copies rotated over")
+    ap.add_argument("--workload", default="llama7b_decode")
+    ap.add_argument("--no-graph", action="store_true", help="launch the timed steps eagerly")
+    ap.add_argument("--serial", action="store_true",
+                    help="predictor, mask and FFN back to back on one stream (halo_ffn_forward) instead "
+                         "of the predictor running one step ahead beside the FFN (halo_ffn_forward_ahead)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
+    ap.add_argument("--cpu-steps", type=int, default=64)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU by design (the simulated devices are a "
+              "group-to-device map plus drop flags on one GPU); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import halo_synth as hs
+    import paper_2601_11676_amd as H
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    H.load_library()
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    w = hs.BY_NAME[args.workload]
+    K, W, NC = args.steps, args.warmup, args.copies
+    T, G, d = w.T, w.n_groups, w.d
+    k_keep = w.k_keep()
+    shape = H.Shape(w.d, w.ffn, w.group_size, w.rank, w.dtype)
+    esz = 2 if w.dtype == "bf16" else 4
+
+    # ---- resident inputs -------------------------------------------------------------
+    copies = []
+    for c in range(NC):
+        Wg, Wu, WdT = hs.ffn_weights(w, 0, dev, copy=c)
+        At, Bt = hs.predictor_weights(w, 0, dev, copy=c)
+        copies.append((At, Bt, Wg, Wu, WdT))
+    n_all = W + K + 1                      # one extra input: the last step predicts one step ahead
+    xs = torch.stack([hs.hidden_states(w, s, dev) for s in range(n_all)])          # [n][T][d]
+    drops_np = np.stack([hs.drop_outcomes(w, 0, s) for s in range(n_all)])          # [n][T][n_dev]
+    drops = torch.from_numpy(drops_np).to(dev)
+    prio_dev_np = H.halo_build_schedule(k_keep, w.device_plr())
+    prio_dev = torch.from_numpy(prio_dev_np).to(dev)
+    ys = torch.zeros((n_all, T, d), dtype=w.torch_dtype, device=dev)
+    masks = torch.zeros((n_all, T, G), dtype=torch.uint8, device=dev)
+    ws = torch.empty(H.halo_workspace_bytes(shape, T, k_keep), dtype=torch.uint8, device=dev)
+    torch.cuda.synchronize()
+
+    def step_serial(s):
+        At, Bt, Wg, Wu, WdT = copies[s % NC]
+        H.halo_ffn_forward(shape, xs[s], At, Bt, Wg, Wu, WdT, k_keep, prio_dev, w.n_dev, drops[s],
+                           ys[s], ws, mask=masks[s])
+
+    def step_ahead(s):
+        # FFN of step s with the mask predicted one step earlier; beside it, in spare workgroups
+        # of the same launches, predictor + mask of step s+1 (the paper's Pred || Comp overlap)
+        _, _, Wg, Wu, WdT = copies[s % NC]
+        At, Bt = copies[(s + 1) % NC][:2]
+        H.halo_ffn_forward_ahead(shape, xs[s], Wg, Wu, WdT, masks[s], ys[s], xs[s + 1], At, Bt, k_keep,
+                                 prio_dev, w.n_dev, drops[s + 1], masks[s + 1], ws)
+
+    step = step_serial if args.serial else step_ahead
+
+    # ---- warm-up -----------------------------------------------------------------------
+    step_serial(0)                          # also provides masks[0] for the overlapped form
+    for s in range(W):
+        step(s)
+    torch.cuda.synchronize()
+    if not args.serial:
+        ws_scores = torch.empty((T, G), dtype=torch.float32, device=dev)
+
+        def prologue():                     # masks[W] for the first timed step (untimed)
+            At, Bt = copies[W % NC][:2]
+            H.halo_predict_scores(shape, xs[W], At, Bt, ws_scores, ws)
+            H.halo_build_group_mask(ws_scores, k_keep, prio_dev, w.n_dev, drops[W], masks[W])
+    else:
+        def prologue():
+            pass
+
+    # ---- timed: K steps ------------------------------------------------------------------
+    use_graph = not args.no_graph
+    if use_graph:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for s in range(W, W + K):
+                step(s)
+        torch.cuda.synchronize()
+        graph.replay()                      # untimed: first replay uploads the graph
+        prologue()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        graph.replay()
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+    else:
+        prologue()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for s in range(W, W + K):
+            step(s)
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+    y_timed = ys[W:W + K].clone()
+
+    # ---- dominant kernel under HIP events (eager pass over the same steps) -------------
+    prologue()
+    H.halo_profile_begin(K)
+    for s in range(W, W + K):
+        step(s)
+    torch.cuda.synchronize()
+    kern_ms, kern_n, kern_name = H.halo_profile_end()
+    same = bool(torch.equal(y_timed, ys[W:W + K]))       # graph replay == eager, bit for bit
+
+    mask_np = masks[W:W + K].cpu().numpy()
+    n_surv = mask_np.sum(axis=2)                          # [K][T]
+    union = mask_np.any(axis=1).sum(axis=1)               # [K] groups read per step
+    group_bytes = w.group_size * d * esz                  # one projection of one group
+    gate_up_bytes = float(union.sum()) * 2 * group_bytes  # over the K launches
+    ffn_bytes = float(union.sum()) * 3 * group_bytes
+    pred_bytes = K * (w.rank * d + G * w.rank) * esz
+    achieved = gate_up_bytes / (kern_ms * 1e-3) / 1e9 if kern_ms > 0 else 0.0
+    traffic = read_traffic(kern_name, w.name)
+
+    out = {
+        "metric": "FFN tokens/s (decode), LLaMA-7B shape, 50% groups kept",
+        "value": K * T / elapsed,
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": W,
+        "ms_per_step": elapsed / K * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": w.dtype,
+        "data": "synthetic",
+        "config": {"workload": w.name, "d": d, "ffn": w.ffn, "n_groups": G, "group_size": w.group_size,
+                   "rank": w.rank, "tokens_per_step": T, "k_keep": k_keep, "n_dev": w.n_dev,
+                   "plr": [float(v) for v in w.device_plr()], "seed": w.seed, "weight_copies": NC,
+                   "graph": use_graph, "predictor": "serial" if args.serial else "one step ahead, beside the FFN"},
+        "whole_pass": {
+            "mean_n_surv": float(n_surv.mean()),
+            "weight_GBps": ffn_bytes / elapsed / 1e9,
+            "total_GBps": (ffn_bytes + pred_bytes) / elapsed / 1e9,
+            "frac_of_hbm_peak": ffn_bytes / elapsed / 1e9 / HBM_PEAK_GBPS,
+            "graph_equals_eager": same,
+        },
+        "roofline": {
+            "bound": "hbm", "kernel": kern_name, "achieved": achieved, "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
+            "launches": int(kern_n), "avg_us": kern_ms / max(kern_n, 1) * 1e3,
+            "bytes_per_launch": gate_up_bytes / max(kern_n, 1),
+        },
+    }
+
+    # ---- CPU oracle on a bounded sample of the same steps (rank 0, N=1) -----------------
+    if not args.no_cpu:
+        from oracle import ref
+        At, Bt, Wg, Wu, WdT = (t.float().cpu().numpy() for t in copies[0])
+        sample = [s for s in range(W, W + K) if s % NC == 0][: args.cpu_steps]
+        if not sample:
+            sample = [W]
+        x_np = xs.float().cpu().numpy()
+        t0 = time.perf_counter()
+        outs = [ref.ffn_forward(x_np[s], At, Bt, Wg, Wu, WdT, w.group_size, k_keep, prio_dev_np,
+                                w.n_dev, drops_np[s]) for s in sample]
+        cpu_t = time.perf_counter() - t0
+        worst, masks_ok = 0.0, True
+        y_np = ys.float().cpu().numpy()
+        for s, o in zip(sample, outs):
+            masks_ok &= bool(np.array_equal(o["mask"], masks[s].cpu().numpy()))
+            den = np.linalg.norm(o["y"])
+            if den > 0:
+                worst = max(worst, float(np.linalg.norm(y_np[s] - o["y"]) / den))
+        out["cpu_baseline"] = {
+            "value": len(sample) * T / cpu_t, "unit": "tokens/s", "cores": ref.num_threads(),
+            "kind": "oracle",
+            "sample": f"{len(sample)} of the {K} timed steps (those on weight copy 0), whole pass each",
+            "ms_per_step": cpu_t / len(sample) * 1e3,
+            "gpu_vs_oracle_max_rel_l2": worst, "masks_bit_exact": masks_ok,
+        }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -108,9 +108,9 @@ int halo_predict_scores(const halo_shape *shape, const void *x, int32_t T, const
  *   k_keep    groups executed per token (0..G): the k_keep highest-scoring groups.
  *             Ranking: score descending, equal scores by lower group index, NaN last.
  *   prio_dev  [k_keep] int8: device executing the group of rank p (from
- *             halo_build_schedule, copied to the device by the caller); values must
- *             lie in [0, n_dev) -- not checked on the device beyond a clamp-free read
- *             of drop[], so the caller must guarantee it.
+ *             halo_build_schedule, copied to the device by the caller).  An entry
+ *             outside [0, n_dev) makes its group count as not executed
+ *             (group_dev -1, mask 0); nothing is read out of bounds.
  *   drop      [T][n_dev] uint8, non-zero = that device's partial result for that
  *             token is lost; NULL = nothing is lost.
  * Outputs (each may be NULL if not wanted, except mask):
@@ -155,6 +155,44 @@ int halo_ffn_forward(const halo_shape *shape, const void *x, const void *x_pred,
                      const uint8_t *drop, void *y, float *scores, int32_t *order,
                      int8_t *group_dev, uint8_t *mask, int32_t *surv_idx, int32_t *n_surv,
                      void *workspace, size_t ws_bytes, void *stream);
+
+/*
+ * Overlapped form of the whole pass (paper Sec. III-B.3 and its figure of the generation
+ * phase with overlapped processes: the Pred process for the next block runs beside the
+ * Load/Comp of the current one, one layer ahead).  On `stream`:
+ *   - group-sparse FFN of the current block, y = FFN(x; mask_cur), with a mask produced by
+ *     an earlier call (this one, halo_ffn_forward or halo_build_group_mask);
+ *   - predictor + group mask of the next block from x_pred_next with that block's
+ *     predictor weights -> mask_next (and the optional outputs, same meaning as in
+ *     halo_build_group_mask; NULL = not produced).
+ * For one token (bf16, d in {4096, 5120, 8192}, n_groups <= 256) the prediction occupies
+ * spare workgroups of the FFN's own two launches (first predictor layer beside gate/up,
+ * second layer + ranking + mask beside the down projection), so it costs no launch and no
+ * time on the critical path; for other shapes it is enqueued after the FFN.  Results are
+ * identical to the separate calls either way.  x_pred_next may be x (predicting from this
+ * block's input, as the paper does) but must not be y; mask_next must not alias mask_cur.
+ */
+int halo_ffn_forward_ahead(const halo_shape *shape, const void *x, int32_t T, const void *Wg,
+                           const void *Wu, const void *WdT, const uint8_t *mask_cur, void *y,
+                           const void *x_pred_next, const void *At_next, const void *Bt_next,
+                           int32_t k_keep, const int8_t *prio_dev, int32_t n_dev,
+                           const uint8_t *drop_next, float *scores_next, int32_t *order_next,
+                           int8_t *group_dev_next, uint8_t *mask_next, int32_t *surv_idx_next,
+                           int32_t *n_surv_next, void *workspace, size_t ws_bytes, void *stream);
+
+/*
+ * Benchmark aid (not part of the paper's method).  Between halo_profile_begin and
+ * halo_profile_end every call of halo_group_sparse_ffn / halo_ffn_forward brackets the
+ * FFN's dominant kernel -- the gate/up projection, which streams two thirds of the
+ * surviving groups' weight bytes -- with a pair of HIP events on the launch stream.
+ * halo_profile_end waits for the recorded events and returns the summed elapsed time
+ * (milliseconds), the number of launches timed, and the kernel's name (HOST pointers;
+ * each may be NULL).  At most max_launches launches are timed.  Do not use while a
+ * stream is being captured into a graph.  Errors: HALO_ERR_ARG (bad count, begin while
+ * active, end while inactive), HALO_ERR_HIP.
+ */
+int halo_profile_begin(int32_t max_launches);
+int halo_profile_end(double *total_ms, int64_t *launches, char *kernel_name, int32_t name_cap);
 
 #ifdef __cplusplus
 }

@@ -39,8 +39,22 @@
 #include <stdlib.h>
 #include <string.h>
 
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
 #define REF_OK 0
 #define REF_ERR -1
+
+/* Threads the parallel loops below will use (reported beside CPU timings). */
+int halo_ref_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
 
 /* ------------------------------------------------------------------------- */
 /* Alg. 3: PLR-aware ratio-guided scheduler.                                  */

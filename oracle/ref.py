@@ -34,6 +34,10 @@ def _f32(a) -> np.ndarray:
     return np.ascontiguousarray(np.asarray(a, dtype=np.float32))
 
 
+def num_threads() -> int:
+    return int(lib().halo_ref_num_threads())
+
+
 def schedule(n_prio: int, plr, ratios=None) -> np.ndarray:
     """prio_dev[p] = device that executes priority index p (Alg. 3)."""
     plr = np.ascontiguousarray(np.asarray(plr, dtype=np.float64))

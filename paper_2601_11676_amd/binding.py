@@ -73,6 +73,13 @@ def load_library():
     lib.halo_ffn_forward.restype = C.c_int
     lib.halo_ffn_forward.argtypes = [ps, vp, vp, i32, vp, vp, vp, vp, vp, i32, vp, i32, vp, vp,
                                      vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.halo_ffn_forward_ahead.restype = C.c_int
+    lib.halo_ffn_forward_ahead.argtypes = [ps, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, i32,
+                                           vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.halo_profile_begin.restype = C.c_int
+    lib.halo_profile_begin.argtypes = [i32]
+    lib.halo_profile_end.restype = C.c_int
+    lib.halo_profile_end.argtypes = [vp, vp, vp, i32]
     _lib = lib
     return lib
 
@@ -154,3 +161,30 @@ def halo_ffn_forward(shape: Shape, x, At, Bt, Wg, Wu, WdT, k_keep: int, prio_dev
         _ptr(group_dev), _ptr(mask), _ptr(surv_idx), _ptr(n_surv), _ptr(workspace),
         workspace.numel(), _stream(stream))
     _check("halo_ffn_forward", rc)
+
+
+def halo_ffn_forward_ahead(shape: Shape, x, Wg, Wu, WdT, mask_cur, y, x_pred_next, At_next, Bt_next,
+                           k_keep: int, prio_dev, n_dev: int, drop_next, mask_next, workspace,
+                           scores_next=None, order_next=None, group_dev_next=None,
+                           surv_idx_next=None, n_surv_next=None, stream=None) -> None:
+    T = x.shape[0]
+    rc = load_library().halo_ffn_forward_ahead(
+        C.byref(shape.c), _ptr(x), T, _ptr(Wg), _ptr(Wu), _ptr(WdT), _ptr(mask_cur), _ptr(y),
+        _ptr(x_pred_next), _ptr(At_next), _ptr(Bt_next), int(k_keep), _ptr(prio_dev), int(n_dev),
+        _ptr(drop_next), _ptr(scores_next), _ptr(order_next), _ptr(group_dev_next), _ptr(mask_next),
+        _ptr(surv_idx_next), _ptr(n_surv_next), _ptr(workspace), workspace.numel(),
+        _stream(stream))
+    _check("halo_ffn_forward_ahead", rc)
+
+
+def halo_profile_begin(max_launches: int) -> None:
+    _check("halo_profile_begin", load_library().halo_profile_begin(int(max_launches)))
+
+
+def halo_profile_end():
+    """Returns (total_ms, launches, kernel_name) of the dominant FFN kernel since begin."""
+    ms, n = C.c_double(0.0), C.c_int64(0)
+    name = C.create_string_buffer(64)
+    rc = load_library().halo_profile_end(C.byref(ms), C.byref(n), name, 64)
+    _check("halo_profile_end", rc)
+    return ms.value, n.value, name.value.decode()

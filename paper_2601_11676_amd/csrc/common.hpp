@@ -45,6 +45,29 @@ __device__ __forceinline__ void load8(const bf16_t *__restrict__ p, float (&o)[8
     unpack8(v, o);
 }
 
+// Eight consecutive elements kept as loaded (bf16 stays packed: half the registers) until used.
+template <typename WT> struct Piece8;
+template <> struct Piece8<float> {
+    float4 a, b;
+    __device__ __forceinline__ void zero() { a = make_float4(0, 0, 0, 0); b = a; }
+    __device__ __forceinline__ void load(const float *__restrict__ p)
+    {
+        a = *reinterpret_cast<const float4 *>(p);
+        b = *reinterpret_cast<const float4 *>(p + 4);
+    }
+    __device__ __forceinline__ void get(float (&o)[8]) const
+    {
+        o[0] = a.x; o[1] = a.y; o[2] = a.z; o[3] = a.w;
+        o[4] = b.x; o[5] = b.y; o[6] = b.z; o[7] = b.w;
+    }
+};
+template <> struct Piece8<bf16_t> {
+    u32x4 v;
+    __device__ __forceinline__ void zero() { v = u32x4{0u, 0u, 0u, 0u}; }
+    __device__ __forceinline__ void load(const bf16_t *__restrict__ p) { v = *reinterpret_cast<const u32x4 *>(p); }
+    __device__ __forceinline__ void get(float (&o)[8]) const { unpack8(v, o); }
+};
+
 __device__ __forceinline__ void store_out(float *p, float v) { *p = v; }
 __device__ __forceinline__ void store_out(bf16_t *p, float v) { *p = f32_to_bf16(v); }
 
@@ -71,6 +94,55 @@ __device__ __forceinline__ float wave_sum(float v)
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) v = v + __shfl_xor(v, off, kWave);
     return v;
+}
+
+// Dot product of length n (multiple of 8) in the fixed order the predictor's ranking
+// depends on: lane l takes elements i with (i/8) mod 64 == l by fused multiply-add in
+// increasing i starting from +0, then the butterfly above.  Call with a full wave.
+template <typename XT, typename WT>
+__device__ __forceinline__ float dot_order64(const XT *__restrict__ xp, const WT *__restrict__ wp,
+                                             int n, int lane)
+{
+    float p = 0.0f;
+    for (int c = lane; c * 8 < n; c += kWave) {
+        float a[8], b[8];
+        load8(xp + c * 8, a);
+        load8(wp + c * 8, b);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) p = __builtin_fmaf(a[e], b[e], p);
+    }
+    return wave_sum(p);
+}
+
+// Wave-wide sum through the DPP cross-lane paths (no LDS traffic); result is uniform.
+// Used where the summation order is free (FFN dot products), not by the predictor.
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float v)
+{
+    const int o = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true);
+    return v + __builtin_bit_cast(float, o);
+}
+
+__device__ __forceinline__ float wave_sum_fast(float v)
+{
+    v = dpp_add<0xB1>(v);    // quad_perm [1,0,3,2]
+    v = dpp_add<0x4E>(v);    // quad_perm [2,3,0,1]
+    v = dpp_add<0x141>(v);   // row_half_mirror
+    v = dpp_add<0x140>(v);   // row_mirror: every lane of a 16-lane row holds the row sum
+    const int iv = __builtin_bit_cast(int, v);
+    const float a = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 0));
+    const float b = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 16));
+    const float c = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 32));
+    const float d = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 48));
+    return (a + b) + (c + d);
+}
+
+// acc + a.lo*b.lo + a.hi*b.hi on packed bf16 pairs (v_dot2c_f32_bf16), float accumulate.
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float acc)
+{
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a),
+                                           __builtin_bit_cast(bf16x2_t, b), acc, false);
 }
 
 __device__ __forceinline__ float silu_mul(float gate, float up)

@@ -199,15 +199,60 @@ int halo_ffn_forward(const halo_shape *shape, const void *x, const void *x_pred,
     hipStream_t s = static_cast<hipStream_t>(stream);
     float *sc = scores ? scores : ws.scores;
     uint8_t *mk = mask ? mask : ws.mask;
+    // first predictor layer, then the second layer fused with the ranking / mask kernel
     hipError_t e = launch_predictor(shape->dtype, x_pred, T, shape->d, shape->rank, shape->n_groups,
-                                    At, Bt, ws.h, sc, s);
+                                    At, Bt, ws.h, nullptr, s);
     if (e != hipSuccess) return HALO_ERR_HIP;
-    e = launch_group_mask(sc, T, shape->n_groups, k_keep, prio_dev, n_dev, drop, order, group_dev, mk,
-                          surv_idx, n_surv, s);
+    e = launch_scores_and_mask(shape->dtype, ws.h, Bt, shape->rank, sc, T, shape->n_groups, k_keep,
+                               prio_dev, n_dev, drop, order, group_dev, mk, surv_idx, n_surv, s);
     if (e != hipSuccess) return HALO_ERR_HIP;
     e = launch_ffn_decode(shape->dtype, x, T, shape->d, shape->n_groups, shape->group_size, Wg, Wu,
                           WdT, mk, y, ws.dec, s);
     return e == hipSuccess ? HALO_OK : HALO_ERR_HIP;
+}
+
+int halo_ffn_forward_ahead(const halo_shape *shape, const void *x, int32_t T, const void *Wg,
+                           const void *Wu, const void *WdT, const uint8_t *mask_cur, void *y,
+                           const void *x_pred_next, const void *At_next, const void *Bt_next,
+                           int32_t k_keep, const int8_t *prio_dev, int32_t n_dev,
+                           const uint8_t *drop_next, float *scores_next, int32_t *order_next,
+                           int8_t *group_dev_next, uint8_t *mask_next, int32_t *surv_idx_next,
+                           int32_t *n_surv_next, void *workspace, size_t ws_bytes, void *stream)
+{
+    int rc = check_shape(shape);
+    if (rc) return rc;
+    if (T < 0 || k_keep < 0 || k_keep > shape->n_groups || n_dev < 1 || n_dev > 127) return HALO_ERR_ARG;
+    if (T == 0) return HALO_OK;
+    if (!x || !Wg || !Wu || !WdT || !mask_cur || !y || !x_pred_next || !At_next || !Bt_next ||
+        !mask_next || (k_keep > 0 && !prio_dev))
+        return HALO_ERR_NULL;
+    if (mask_next == mask_cur || y == x_pred_next) return HALO_ERR_ARG;
+    if (misaligned(x) || misaligned(Wg) || misaligned(Wu) || misaligned(WdT) || misaligned(y) ||
+        misaligned(x_pred_next) || misaligned(At_next) || misaligned(Bt_next) ||
+        (scores_next && misaligned(scores_next)))
+        return HALO_ERR_ARG;
+    if (!workspace || misaligned(workspace)) return HALO_ERR_WORKSPACE;
+    Workspace ws(*shape, T, k_keep, workspace);
+    if (ws_bytes < ws.bytes) return HALO_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    float *sc = scores_next ? scores_next : ws.scores;
+    AheadArgs ah{x_pred_next, At_next, Bt_next, shape->rank, k_keep, n_dev, prio_dev, drop_next, ws.h, sc,
+                 order_next, group_dev_next, mask_next, surv_idx_next, n_surv_next};
+    bool fused = false;
+    hipError_t e = launch_ffn_decode(shape->dtype, x, T, shape->d, shape->n_groups, shape->group_size, Wg,
+                                     Wu, WdT, mask_cur, y, ws.dec, s, &ah, &fused);
+    if (e != hipSuccess) return HALO_ERR_HIP;
+    if (!fused) {
+        // no path with spare workgroups for this shape: the prediction follows on the stream
+        e = launch_predictor(shape->dtype, x_pred_next, T, shape->d, shape->rank, shape->n_groups, At_next,
+                             Bt_next, ws.h, nullptr, s);
+        if (e != hipSuccess) return HALO_ERR_HIP;
+        e = launch_scores_and_mask(shape->dtype, ws.h, Bt_next, shape->rank, sc, T, shape->n_groups, k_keep,
+                                   prio_dev, n_dev, drop_next, order_next, group_dev_next, mask_next,
+                                   surv_idx_next, n_surv_next, s);
+        if (e != hipSuccess) return HALO_ERR_HIP;
+    }
+    return HALO_OK;
 }
 
 }  // extern "C"

@@ -1,5 +1,7 @@
 // Internal launcher interface between the C boundary (halo_api.hip) and the kernels.
 #pragma once
+#include <hip/hip_ext.h>
+
 #include "common.hpp"
 
 namespace halo {
@@ -13,6 +15,11 @@ hipError_t launch_group_mask(const float *scores, int T, int G, int K, const int
                              int n_dev, const uint8_t *drop, int32_t *order, int8_t *group_dev,
                              uint8_t *mask, int32_t *surv_idx, int32_t *n_surv, hipStream_t s);
 
+hipError_t launch_scores_and_mask(int dtype, const float *h, const void *Bt, int r, float *scores,
+                                  int T, int G, int K, const int8_t *prio_dev, int n_dev,
+                                  const uint8_t *drop, int32_t *order, int8_t *group_dev,
+                                  uint8_t *mask, int32_t *surv_idx, int32_t *n_surv, hipStream_t s);
+
 // ffn_decode.hip : float-ALU paths (any T; tuned for one token)
 struct DecodeScratch {
     int32_t *ulist;     // [G]   groups surviving for at least one token, ascending
@@ -22,8 +29,39 @@ struct DecodeScratch {
     int n_split;        // neuron subsets in the down projection
 };
 int decode_n_split(int T, int d);
+// The next block's prediction (predictor + mask from x_next), see halo_ffn_forward_ahead.
+struct AheadArgs {
+    const void *x_next, *At, *Bt;
+    int r, K, n_dev;
+    const int8_t *prio_dev;
+    const uint8_t *drop;
+    float *h, *scores;
+    int32_t *order;
+    int8_t *group_dev;
+    uint8_t *mask;
+    int32_t *surv_idx, *n_surv;
+};
 hipError_t launch_ffn_decode(int dtype, const void *x, int T, int d, int G, int gs, const void *Wg,
                              const void *Wu, const void *WdT, const uint8_t *mask, void *y,
-                             const DecodeScratch &ws, hipStream_t s);
+                             const DecodeScratch &ws, hipStream_t s, const AheadArgs *ahead = nullptr,
+                             bool *ahead_fused = nullptr);
+
+// profile.hip : optional HIP-event bracket around the dominant FFN kernel
+bool timer_acquire(hipEvent_t *start, hipEvent_t *stop);   // false: not profiling (or pool used up)
+void timer_commit(const char *kernel_name);
+
+// Launch `kernel`; while profiling is active its dispatch carries a start/stop event pair, so
+// the elapsed time is that of the kernel itself (no launch gap inside the bracket).
+template <typename F, typename... Args>
+inline void launch_timed(const char *name, F kernel, dim3 grid, dim3 block, hipStream_t s, Args... args)
+{
+    hipEvent_t e0, e1;
+    if (timer_acquire(&e0, &e1)) {
+        hipExtLaunchKernelGGL(kernel, grid, block, 0, s, e0, e1, 0, args...);
+        timer_commit(name);
+    } else {
+        kernel<<<grid, block, 0, s>>>(args...);
+    }
+}
 
 }  // namespace halo

@@ -21,17 +21,7 @@ __global__ __launch_bounds__(256) void dot_rows_kernel(const XT *__restrict__ X,
     const long long idx = (long long)blockIdx.x * 4 + wave;
     if (idx >= (long long)T * R) return;                 // uniform per wave
     const int t = (int)(idx / R), j = (int)(idx % R);
-    const XT *xp = X + (size_t)t * n;
-    const WT *wp = W + (size_t)j * n;
-    float p = 0.0f;
-    for (int c = lane; c * 8 < n; c += kWave) {
-        float a[8], b[8];
-        load8(xp + c * 8, a);
-        load8(wp + c * 8, b);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) p = __builtin_fmaf(a[e], b[e], p);
-    }
-    p = wave_sum(p);
+    const float p = dot_order64(X + (size_t)t * n, W + (size_t)j * n, n, lane);
     if (lane == 0) out[idx] = RELU ? (p > 0.0f ? p : 0.0f) : p;
 }
 
@@ -41,10 +31,12 @@ static hipError_t predict_t(const WT *x, int T, int d, int r, int G, const WT *A
 {
     long long n1 = (long long)T * r, n2 = (long long)T * G;
     dot_rows_kernel<WT, WT, true><<<dim3((unsigned)((n1 + 3) / 4)), dim3(256), 0, s>>>(x, At, h, T, r, d);
-    dot_rows_kernel<float, WT, false><<<dim3((unsigned)((n2 + 3) / 4)), dim3(256), 0, s>>>(h, Bt, scores, T, G, r);
+    if (scores)
+        dot_rows_kernel<float, WT, false><<<dim3((unsigned)((n2 + 3) / 4)), dim3(256), 0, s>>>(h, Bt, scores, T, G, r);
     return hipGetLastError();
 }
 
+// scores == nullptr: first layer only (h), the second layer is then fused into the mask kernel
 hipError_t launch_predictor(int dtype, const void *x, int T, int d, int r, int G, const void *At,
                             const void *Bt, float *h, float *scores, hipStream_t s)
 {

@@ -172,3 +172,71 @@ def test_predictor_entry_point_bit_exact_and_run_to_run_deterministic():
     c = ref.predict_scores(hz.to_np32(x), hz.to_np32(At), hz.to_np32(Bt))
     assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
     assert np.array_equal(a.view(np.uint32), c.view(np.uint32))
+
+
+def test_separate_entry_points_equal_the_fused_pass():
+    w = dataclasses.replace(hs.LLAMA13B_STACK, name="case", ffn=12 * 128, layers=1, seed=5)
+    _say("separate calls vs halo_ffn_forward")
+    s = hz.shape_of(w)
+    L = hz.Layer(w)
+    T, G, K = w.T, w.n_groups, 6
+    x = hs.hidden_states(w, 0, hz.DEV)
+    pd = H.halo_build_schedule(K, w.device_plr())
+    drop = hs.drop_outcomes(w)
+    fused = hz.gpu_forward(w, L, x, K, pd, drop)
+    ws = torch.empty(H.halo_workspace_bytes(s, T, K), dtype=torch.uint8, device=hz.DEV)
+    sc = torch.empty((T, G), dtype=torch.float32, device=hz.DEV)
+    H.halo_predict_scores(s, x, L.At, L.Bt, sc, ws)
+    mask = torch.empty((T, G), dtype=torch.uint8, device=hz.DEV)
+    order = torch.empty((T, G), dtype=torch.int32, device=hz.DEV)
+    H.halo_build_group_mask(sc, K, torch.from_numpy(pd).to(hz.DEV), w.n_dev,
+                            torch.from_numpy(drop).to(hz.DEV), mask, order=order)
+    y = torch.empty((T, w.d), dtype=torch.bfloat16, device=hz.DEV)
+    H.halo_group_sparse_ffn(s, x, L.Wg, L.Wu, L.WdT, mask, y, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(sc.cpu().numpy().view(np.uint32), fused["scores"].view(np.uint32))
+    assert np.array_equal(mask.cpu().numpy(), fused["mask"])
+    assert np.array_equal(order.cpu().numpy(), fused["order"])
+    assert np.array_equal(hz.to_np32(y).astype(np.float64), fused["y"])
+
+
+def test_one_step_ahead_overlap_equals_the_serial_pass():
+    # predictor + mask of step s+1 beside the FFN of step s
+    w = dataclasses.replace(hs.LLAMA7B_DECODE, name="case", ffn=20 * 128, seed=8)
+    _say("halo_ffn_forward_ahead vs halo_ffn_forward")
+    s = hz.shape_of(w)
+    L = hz.Layer(w)
+    T, G, K, n = w.T, w.n_groups, 10, 6
+    pd = H.halo_build_schedule(K, w.device_plr())
+    xs = [hs.hidden_states(w, i, hz.DEV) for i in range(n + 1)]
+    drops = [hs.drop_outcomes(w, 0, i) for i in range(n + 1)]
+    serial = [hz.gpu_forward(w, L, xs[i], K, pd, drops[i]) for i in range(n)]
+    ws = torch.empty(H.halo_workspace_bytes(s, T, K), dtype=torch.uint8, device=hz.DEV)
+    pdd = torch.from_numpy(pd).to(hz.DEV)
+    dd = [torch.from_numpy(d).to(hz.DEV) for d in drops]
+    masks = torch.zeros((n + 1, T, G), dtype=torch.uint8, device=hz.DEV)
+    ys = torch.zeros((n, T, w.d), dtype=torch.bfloat16, device=hz.DEV)
+    sc = torch.empty((T, G), dtype=torch.float32, device=hz.DEV)
+    H.halo_predict_scores(s, xs[0], L.At, L.Bt, sc, ws)
+    H.halo_build_group_mask(sc, K, pdd, w.n_dev, dd[0], masks[0])
+    for i in range(n):
+        H.halo_ffn_forward_ahead(s, xs[i], L.Wg, L.Wu, L.WdT, masks[i], ys[i], xs[i + 1], L.At, L.Bt,
+                                 K, pdd, w.n_dev, dd[i + 1], masks[i + 1], ws)
+    torch.cuda.synchronize()
+    for i in range(n):
+        assert np.array_equal(masks[i].cpu().numpy(), serial[i]["mask"]), i
+        assert np.array_equal(hz.to_np32(ys[i]).astype(np.float64), serial[i]["y"]), i
+    # and the whole thing once more inside a captured graph, replayed twice
+    g = torch.cuda.CUDAGraph()
+    ys2 = torch.zeros_like(ys)
+    masks2 = masks.clone()
+    with torch.cuda.graph(g):
+        for i in range(n):
+            H.halo_ffn_forward_ahead(s, xs[i], L.Wg, L.Wu, L.WdT, masks2[i], ys2[i], xs[i + 1], L.At,
+                                     L.Bt, K, pdd, w.n_dev, dd[i + 1], masks2[i + 1], ws)
+    for _ in range(2):
+        ys2.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(ys2, ys) and torch.equal(masks2, masks)
