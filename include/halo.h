@@ -19,11 +19,14 @@
  *
  * Weight layout ("FFN weights partitioned into neuron groups", paper Sec. II-A):
  * neuron group g owns rows [g*group_size, (g+1)*group_size) of
- *   Wg  [ffn][d]  gate projection,
- *   Wu  [ffn][d]  up projection,
- *   WdT [ffn][d]  down projection stored neuron-major (the transpose of the usual
- *                 [d][ffn] matrix),
- * so one group is three contiguous blocks of group_size*d elements.
+ *   Wg [ffn][d]  gate projection,
+ *   Wu [ffn][d]  up projection,
+ * and block g of
+ *   Wd [n_groups][d][group_size]  down projection, group-blocked:
+ *                Wd[g][j][m] = weight from neuron g*group_size+m to output j,
+ * so one group is three contiguous blocks of group_size*d elements, and within the down
+ * block the neurons of the group are contiguous for every output.  (From the usual
+ * [d][ffn] down matrix W: Wd = W.view(d, n_groups, group_size).permute(1, 0, 2).)
  */
 #ifndef HALO_H
 #define HALO_H
@@ -128,16 +131,18 @@ int halo_build_group_mask(const float *scores, int32_t T, int32_t G, int32_t k_k
 /*
  * Group-sparse SwiGLU FFN (paper Sec. II-A "Neuron group"; merge = plain sum of the
  * groups' partial results, Sec. III-B.3):
- *     y[t] = sum_{g : mask[t][g] != 0}  sum_{m in g}  WdT[m][:] * SiLU(Wg[m].x[t]) * (Wu[m].x[t])
+ *     y[t][j] = sum_{g : mask[t][g] != 0}  sum_{m < group_size}
+ *                   Wd[g][j][m] * SiLU(Wg[g*group_size+m].x[t]) * (Wu[g*group_size+m].x[t])
  * Only groups that survive for at least one token are read from memory; a group
  * with mask 0 contributes exactly zero to that token; a token with no surviving
  * group gets y[t] = 0.
- *   x [T][d], Wg/Wu/WdT [ffn][d], mask [T][n_groups] uint8, y [T][d] out (dtype).
- * Accumulation is float32; for bf16 with many tokens the matrix-core path rounds
- * the activation to bf16 before the down projection.
+ *   x [T][d], Wg/Wu [ffn][d], Wd [n_groups][d][group_size], mask [T][n_groups] uint8,
+ *   y [T][d] out (dtype).
+ * Accumulation is float32; for bf16 with more than one token the matrix-core path rounds
+ * the activation SiLU(gate)*up to bf16 before the down projection.
  */
 int halo_group_sparse_ffn(const halo_shape *shape, const void *x, int32_t T, const void *Wg,
-                          const void *Wu, const void *WdT, const uint8_t *mask, void *y,
+                          const void *Wu, const void *Wd, const uint8_t *mask, void *y,
                           void *workspace, size_t ws_bytes, void *stream);
 
 /*
@@ -151,7 +156,7 @@ int halo_group_sparse_ffn(const halo_shape *shape, const void *x, int32_t T, con
  */
 int halo_ffn_forward(const halo_shape *shape, const void *x, const void *x_pred, int32_t T,
                      const void *At, const void *Bt, const void *Wg, const void *Wu,
-                     const void *WdT, int32_t k_keep, const int8_t *prio_dev, int32_t n_dev,
+                     const void *Wd, int32_t k_keep, const int8_t *prio_dev, int32_t n_dev,
                      const uint8_t *drop, void *y, float *scores, int32_t *order,
                      int8_t *group_dev, uint8_t *mask, int32_t *surv_idx, int32_t *n_surv,
                      void *workspace, size_t ws_bytes, void *stream);
@@ -173,7 +178,7 @@ int halo_ffn_forward(const halo_shape *shape, const void *x, const void *x_pred,
  * block's input, as the paper does) but must not be y; mask_next must not alias mask_cur.
  */
 int halo_ffn_forward_ahead(const halo_shape *shape, const void *x, int32_t T, const void *Wg,
-                           const void *Wu, const void *WdT, const uint8_t *mask_cur, void *y,
+                           const void *Wu, const void *Wd, const uint8_t *mask_cur, void *y,
                            const void *x_pred_next, const void *At_next, const void *Bt_next,
                            int32_t k_keep, const int8_t *prio_dev, int32_t n_dev,
                            const uint8_t *drop_next, float *scores_next, int32_t *order_next,

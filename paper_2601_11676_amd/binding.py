@@ -104,6 +104,14 @@ def _check(fn: str, rc: int):
         raise HaloError(fn, rc)
 
 
+def pack_down_proj(WdT: torch.Tensor, group_size: int) -> torch.Tensor:
+    """Re-arrange a neuron-major down projection WdT [ffn][d] (row n = the weights leaving
+    neuron n) into the library's group-blocked layout Wd [n_groups][d][group_size].
+    Data movement only."""
+    ffn, d = WdT.shape
+    return WdT.view(ffn // group_size, group_size, d).permute(0, 2, 1).contiguous()
+
+
 def halo_build_schedule(n_prio: int, plr: Sequence[float],
                         ratios: Optional[Sequence[float]] = None) -> np.ndarray:
     """Host-only (Alg. 3).  Returns prio_dev as an int8 numpy array of length n_prio."""
@@ -142,39 +150,72 @@ def halo_build_group_mask(scores, k_keep: int, prio_dev, n_dev: int, drop, mask,
     _check("halo_build_group_mask", rc)
 
 
-def halo_group_sparse_ffn(shape: Shape, x, Wg, Wu, WdT, mask, y, workspace, stream=None) -> None:
+def halo_group_sparse_ffn(shape: Shape, x, Wg, Wu, Wd, mask, y, workspace, stream=None) -> None:
     T = x.shape[0]
     rc = load_library().halo_group_sparse_ffn(C.byref(shape.c), _ptr(x), T, _ptr(Wg), _ptr(Wu),
-                                              _ptr(WdT), _ptr(mask), _ptr(y), _ptr(workspace),
+                                              _ptr(Wd), _ptr(mask), _ptr(y), _ptr(workspace),
                                               workspace.numel(), _stream(stream))
     _check("halo_group_sparse_ffn", rc)
 
 
-def halo_ffn_forward(shape: Shape, x, At, Bt, Wg, Wu, WdT, k_keep: int, prio_dev, n_dev: int,
+def halo_ffn_forward(shape: Shape, x, At, Bt, Wg, Wu, Wd, k_keep: int, prio_dev, n_dev: int,
                      drop, y, workspace, x_pred=None, scores=None, order=None, group_dev=None,
                      mask=None, surv_idx=None, n_surv=None, stream=None) -> None:
     T = x.shape[0]
     xp = x if x_pred is None else x_pred
     rc = load_library().halo_ffn_forward(
-        C.byref(shape.c), _ptr(x), _ptr(xp), T, _ptr(At), _ptr(Bt), _ptr(Wg), _ptr(Wu), _ptr(WdT),
+        C.byref(shape.c), _ptr(x), _ptr(xp), T, _ptr(At), _ptr(Bt), _ptr(Wg), _ptr(Wu), _ptr(Wd),
         int(k_keep), _ptr(prio_dev), int(n_dev), _ptr(drop), _ptr(y), _ptr(scores), _ptr(order),
         _ptr(group_dev), _ptr(mask), _ptr(surv_idx), _ptr(n_surv), _ptr(workspace),
         workspace.numel(), _stream(stream))
     _check("halo_ffn_forward", rc)
 
 
-def halo_ffn_forward_ahead(shape: Shape, x, Wg, Wu, WdT, mask_cur, y, x_pred_next, At_next, Bt_next,
+def halo_ffn_forward_ahead(shape: Shape, x, Wg, Wu, Wd, mask_cur, y, x_pred_next, At_next, Bt_next,
                            k_keep: int, prio_dev, n_dev: int, drop_next, mask_next, workspace,
                            scores_next=None, order_next=None, group_dev_next=None,
                            surv_idx_next=None, n_surv_next=None, stream=None) -> None:
     T = x.shape[0]
     rc = load_library().halo_ffn_forward_ahead(
-        C.byref(shape.c), _ptr(x), T, _ptr(Wg), _ptr(Wu), _ptr(WdT), _ptr(mask_cur), _ptr(y),
+        C.byref(shape.c), _ptr(x), T, _ptr(Wg), _ptr(Wu), _ptr(Wd), _ptr(mask_cur), _ptr(y),
         _ptr(x_pred_next), _ptr(At_next), _ptr(Bt_next), int(k_keep), _ptr(prio_dev), int(n_dev),
         _ptr(drop_next), _ptr(scores_next), _ptr(order_next), _ptr(group_dev_next), _ptr(mask_next),
         _ptr(surv_idx_next), _ptr(n_surv_next), _ptr(workspace), workspace.numel(),
         _stream(stream))
     _check("halo_ffn_forward_ahead", rc)
+
+
+def prepared(fn, *args, **kwargs):
+    """Marshal the arguments of one of the halo_* calls above once and return a zero-argument
+    callable that repeats exactly that call (same pointers, same stream).  For launch-bound
+    loops where per-call Python marshalling would dominate; the caller keeps the tensors alive."""
+    lib = load_library()
+    captured = []
+
+    class _Recorder:
+        def __getattr__(self, name):
+            cfn = getattr(lib, name)
+
+            def rec(*cargs):
+                captured.append((cfn, cargs, name))
+                return 0
+            return rec
+
+    global _lib
+    real, _lib = _lib, _Recorder()
+    try:
+        fn(*args, **kwargs)
+    finally:
+        _lib = real
+    if len(captured) != 1:
+        raise RuntimeError("prepared() expects a function that makes exactly one library call")
+    cfn, cargs, name = captured[0]
+
+    def call():
+        rc = cfn(*cargs)
+        if rc != 0:
+            raise HaloError(name, rc)
+    return call
 
 
 def halo_profile_begin(max_launches: int) -> None:

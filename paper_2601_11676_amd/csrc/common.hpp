@@ -13,6 +13,9 @@ constexpr int kWave = 64;
 __device__ __forceinline__ float bf16_lo(uint32_t v) { return __uint_as_float(v << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t v) { return __uint_as_float(v & 0xffff0000u); }
 
+__device__ __forceinline__ float to_float(float v) { return v; }
+__device__ __forceinline__ float to_float(uint16_t v) { return __uint_as_float((uint32_t)v << 16); }
+
 // float -> bf16, round to nearest even; NaN stays NaN (quiet).
 __device__ __forceinline__ bf16_t f32_to_bf16(float f)
 {

@@ -1,24 +1,26 @@
 // Group-sparse SwiGLU FFN on the float ALUs (paper Sec. II-A neuron groups; merge = sum).
 //
-//   y[t] = sum_{g in S_t} sum_{m in g} WdT[m][:] * SiLU(Wg[m].x[t]) * (Wu[m].x[t])
+//   y[t] = sum_{g in S_t} sum_{m in g} Wd[g][:][m] * SiLU(Wg[g*gs+m].x[t]) * (Wu[g*gs+m].x[t])
 //
-// With one or a few tokens the block is a memory-bound matrix-vector product: every
-// weight element of a surviving group is read once and used T times, so the kernels
-// are organised around streaming those rows from HBM with 16-byte loads per lane and
-// nothing else competing for bandwidth.  Two phases:
-//   gate/up : one wave per neuron; lanes stride the row in 16-byte pieces, the two
-//             dot products are reduced across the wave, lane 0 stores the activation.
-//   down    : a workgroup owns a 512-column slice of d (8 columns per lane) and a
-//             subset of the surviving neurons; a small kernel then adds the subsets'
-//             partial column sums in a fixed order (deterministic, no float atomics).
+// With one token the block is a memory-bound matrix-vector product: every weight element
+// of a surviving group is read once, so the kernels are organised around streaming those
+// bytes from HBM with 16-byte loads per lane and nothing else competing for bandwidth.
+//   gate/up : one wave per neuron; lanes stride the row in 16-byte pieces, the two dot
+//             products are reduced across the wave, lane 0 stores the activation.
+//   down    : the down projection is stored group-blocked, Wd[g][j][m]; 16 lanes share one
+//             output row j (256 bytes per group), a wave covers four rows and walks the
+//             surviving groups, so no partial sums ever leave the workgroup.
 // Groups that no token keeps are never addressed.
+//
+// This file holds the one-token hot path and a generic path (any T, d, group size, f32 or
+// bf16) that favours simplicity; a few tokens in bf16 go to the matrix-core path instead.
 #include "kernels.hpp"
 #include "mask_device.hpp"
 
 namespace halo {
 
 // ---------------------------------------------------------------------------
-// union of surviving groups over the tokens (generic path)
+// union of surviving groups over the tokens
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void union_kernel(const uint8_t *__restrict__ mask, int T, int G,
                                                     int32_t *__restrict__ ulist,
@@ -43,6 +45,12 @@ __global__ __launch_bounds__(256) void union_kernel(const uint8_t *__restrict__ 
         for (int h = 0; h < G; ++h) c += any[h];
         meta[0] = c;
     }
+}
+
+hipError_t launch_union(const uint8_t *mask, int T, int G, int32_t *ulist, int32_t *meta, hipStream_t s)
+{
+    union_kernel<<<dim3(1), dim3(256), 0, s>>>(mask, T, G, ulist, meta);
+    return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------
@@ -95,83 +103,41 @@ __global__ __launch_bounds__(256) void gate_up_generic(
 }
 
 // ---------------------------------------------------------------------------
-// generic down: grid (ceil(d/512), n_split)
+// generic down: one wave per output row j; lanes stride the group's neurons
 // ---------------------------------------------------------------------------
 template <typename WT, int TT>
 __global__ __launch_bounds__(256) void down_generic(
-    const float *__restrict__ act, int act_stride, int T, int d, int gs,
-    const WT *__restrict__ WdT, const int32_t *__restrict__ ulist, const int32_t *__restrict__ meta,
-    float *__restrict__ partial)
+    const float *__restrict__ act, int act_stride, int T, int d, int gs, const WT *__restrict__ Wd,
+    const int32_t *__restrict__ ulist, const int32_t *__restrict__ meta, WT *__restrict__ y)
 {
-    __shared__ float red[4][TT][512];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int n_split = gridDim.y, i = blockIdx.y;
-    const int col0 = blockIdx.x * 512 + lane * 8;
-    const bool col_ok = col0 < d;
-    const int total = meta[0] * gs;
-    const int per = (total + n_split - 1) / n_split;
-    const int n0 = i * per, n1 = min(total, n0 + per);
+    const int j = blockIdx.x * 4 + wave;
+    if (j >= d) return;
+    const int n_u = meta[0];
     for (int t0 = 0; t0 < T; t0 += TT) {
-        float acc[TT][8];
+        float acc[TT];
 #pragma unroll
-        for (int tt = 0; tt < TT; ++tt)
+        for (int tt = 0; tt < TT; ++tt) acc[tt] = 0.0f;
+        for (int u = 0; u < n_u; ++u) {
+            const WT *w = Wd + ((size_t)ulist[u] * d + j) * gs;
+            for (int m = lane; m < gs; m += kWave) {
+                const float wv = to_float(w[m]);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) acc[tt][e] = 0.0f;
-        if (col_ok) {
-            for (int n = n0 + wave; n < n1; n += 4) {
-                const int u = n / gs, m = n - u * gs;
-                const size_t row = (size_t)ulist[u] * gs + m;
-                float w[8];
-                load8(WdT + row * d + col0, w);
-#pragma unroll
-                for (int tt = 0; tt < TT; ++tt) {
-                    if (t0 + tt < T) {
-                        const float a = act[(size_t)(t0 + tt) * act_stride + n];
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) acc[tt][e] = __builtin_fmaf(a, w[e], acc[tt][e]);
-                    }
-                }
+                for (int tt = 0; tt < TT; ++tt)
+                    if (t0 + tt < T)
+                        acc[tt] = __builtin_fmaf(wv, act[(size_t)(t0 + tt) * act_stride + u * gs + m], acc[tt]);
             }
         }
 #pragma unroll
-        for (int tt = 0; tt < TT; ++tt)
-#pragma unroll
-            for (int e = 0; e < 8; ++e) red[wave][tt][lane * 8 + e] = acc[tt][e];
-        __syncthreads();
-        for (int k = threadIdx.x; k < TT * 512; k += 256) {
-            const int tt = k / 512, c = k - tt * 512;
-            const int t = t0 + tt, col = blockIdx.x * 512 + c;
-            if (t < T && col < d) {
-                const float v = ((red[0][tt][c] + red[1][tt][c]) + red[2][tt][c]) + red[3][tt][c];
-                partial[((size_t)i * T + t) * d + col] = v;
-            }
+        for (int tt = 0; tt < TT; ++tt) {
+            const float v = wave_sum(acc[tt]);
+            if (lane == 0 && t0 + tt < T) store_out(y + (size_t)(t0 + tt) * d + j, v);
         }
-        __syncthreads();
     }
-}
-
-// y[k] = sum_i partial[i][k] (k over T*d).  64 outputs per workgroup; four quarter-sums over
-// i = q, q+4, ... are formed concurrently and combined in a fixed order.
-template <typename WT>
-__global__ __launch_bounds__(256) void finalize_generic(const float *__restrict__ partial,
-                                                        int n_split, long long td,
-                                                        WT *__restrict__ y)
-{
-    __shared__ float red[4][64];
-    const int c = threadIdx.x & 63, q = threadIdx.x >> 6;
-    const long long k = (long long)blockIdx.x * 64 + c;
-    float v = 0.0f;
-    if (k < td) {
-#pragma unroll 8
-        for (int i = q; i < n_split; i += 4) v += partial[(size_t)i * td + k];
-    }
-    red[q][c] = v;
-    __syncthreads();
-    if (q == 0 && k < td) store_out(y + k, ((red[0][c] + red[1][c]) + red[2][c]) + red[3][c]);
 }
 
 // ---------------------------------------------------------------------------
-// one token, bf16, d = NCH*512, G <= 256: the decode hot path
+// one token, bf16, d = NCH*512, group size 128, G <= 256: the decode hot path
 // ---------------------------------------------------------------------------
 // The token's mask as up to four 64-bit words held in scalar registers (one ballot per
 // 64 groups); every wave builds them itself, so no LDS and no workgroup barrier sit
@@ -265,7 +231,7 @@ __device__ __forceinline__ float gate_up_dot(const RowPair<NCH> &r, const u32x4 
 template <int NCH>
 __device__ __forceinline__ void gate_up_t1_body(
     const bf16_t *__restrict__ x, int G, int gs, const bf16_t *__restrict__ Wg,
-    const bf16_t *__restrict__ Wu, const uint8_t *__restrict__ mask, float *__restrict__ act,
+    const bf16_t *__restrict__ Wu, const uint8_t *__restrict__ mask, bf16_t *__restrict__ act,
     int vblock, int nblocks)
 {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -293,39 +259,29 @@ __device__ __forceinline__ void gate_up_t1_body(
     while (n + 2 < n1) {
         load_rows<NCH>(B, Wg, Wu, row_of(n + 1), lane);
         const float va = gate_up_dot<NCH>(A, xr);
-        if (lane == 0) act[n] = va;
+        if (lane == 0) act[n] = f32_to_bf16(va);
         load_rows<NCH>(A, Wg, Wu, row_of(n + 2), lane);
         const float vb = gate_up_dot<NCH>(B, xr);
-        if (lane == 0) act[n + 1] = vb;
+        if (lane == 0) act[n + 1] = f32_to_bf16(vb);
         n += 2;
     }
     if (n + 1 < n1) {
         load_rows<NCH>(B, Wg, Wu, row_of(n + 1), lane);
         const float va = gate_up_dot<NCH>(A, xr);
-        if (lane == 0) act[n] = va;
+        if (lane == 0) act[n] = f32_to_bf16(va);
         const float vb = gate_up_dot<NCH>(B, xr);
-        if (lane == 0) act[n + 1] = vb;
+        if (lane == 0) act[n + 1] = f32_to_bf16(vb);
     } else {
         const float va = gate_up_dot<NCH>(A, xr);
-        if (lane == 0) act[n] = va;
+        if (lane == 0) act[n] = f32_to_bf16(va);
     }
-}
-
-// arrival counters of the down-projection kernel that follows on the stream
-template <int NCH>
-__device__ __forceinline__ void reset_counters(int32_t *counters)
-{
-    if (threadIdx.x < NCH)
-        __hip_atomic_store(counters + threadIdx.x, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 template <int NCH>
 __global__ __launch_bounds__(256) void gate_up_t1(
     const bf16_t *__restrict__ x, int G, int gs, const bf16_t *__restrict__ Wg,
-    const bf16_t *__restrict__ Wu, const uint8_t *__restrict__ mask, float *__restrict__ act,
-    int32_t *__restrict__ counters)
+    const bf16_t *__restrict__ Wu, const uint8_t *__restrict__ mask, bf16_t *__restrict__ act)
 {
-    if (blockIdx.x == 0) reset_counters<NCH>(counters);
     gate_up_t1_body<NCH>(x, G, gs, Wg, Wu, mask, act, blockIdx.x, gridDim.x);
 }
 
@@ -335,9 +291,9 @@ __global__ __launch_bounds__(256) void gate_up_t1(
 template <int NCH>
 __global__ __launch_bounds__(256) void gate_up_pred_t1(
     const bf16_t *__restrict__ x, int G, int gs, const bf16_t *__restrict__ Wg,
-    const bf16_t *__restrict__ Wu, const uint8_t *__restrict__ mask, float *__restrict__ act,
-    int32_t *__restrict__ counters, const bf16_t *__restrict__ x_next,
-    const bf16_t *__restrict__ At_next, int r, float *__restrict__ h_next, int n_pred)
+    const bf16_t *__restrict__ Wu, const uint8_t *__restrict__ mask, bf16_t *__restrict__ act,
+    const bf16_t *__restrict__ x_next, const bf16_t *__restrict__ At_next, int r,
+    float *__restrict__ h_next, int n_pred)
 {
     if ((int)blockIdx.x < n_pred) {
         const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -348,34 +304,33 @@ __global__ __launch_bounds__(256) void gate_up_pred_t1(
         }
         return;
     }
-    const int vblock = blockIdx.x - n_pred;
-    if (vblock == 0) reset_counters<NCH>(counters);
-    gate_up_t1_body<NCH>(x, G, gs, Wg, Wu, mask, act, vblock, gridDim.x - n_pred);
+    gate_up_t1_body<NCH>(x, G, gs, Wg, Wu, mask, act, blockIdx.x - n_pred, gridDim.x - n_pred);
 }
 
-// grid (d/512, n_split): partial[i][:] = sum over neuron subset i of act[n] * WdT[row(n)][:].
-// A workgroup owns 512 columns (8 per lane); its eight waves interleave the subset's rows,
-// eight rows in flight per wave.  The workgroup that arrives last at a column slice adds
-// the n_split partial sums in index order (so the result does not depend on arrival order)
-// and writes y.  Partials and the arrival counter are exchanged with device-scope atomic
-// loads and stores, which are coherent across the chip's L2 slices without a cache-wide
-// write-back; no workgroup ever waits for another.
-constexpr int kDownUnroll = 8;
-constexpr int kDownWaves = 8;
+// Down projection for one token.  16 lanes share an output row (16 bytes each = the 128
+// neurons of a group), a wave covers four rows, and two waves share those four rows, one
+// taking the even and one the odd surviving groups.  A workgroup of 2*RQ waves owns 4*RQ
+// consecutive rows, i.e. 1 KiB * RQ contiguous bytes of every surviving group's block.
+// Each lane accumulates over its groups, the 16 lanes of a row are summed once at the end
+// and the two halves meet in LDS, so y is written directly: no partial sums in memory, no
+// second pass.  The activation arrives in bf16 and meets the weights in the packed dot.
+constexpr int kDownBatch = 8;    // groups in flight per wave
 
+template <int RQ>
 struct DownShared {
     int list[256];
-    float red[kDownWaves][512];
-    int ticket;
+    float half[RQ][64];
 };
 
-__device__ __forceinline__ void down_t1_body(
-    DownShared &sh, int d, int G, int gs, const bf16_t *__restrict__ WdT,
-    const uint8_t *__restrict__ mask, const float *__restrict__ act, float *partial,
-    int32_t *counters, bf16_t *__restrict__ y, int cb, int i, int n_split)
+template <int RQ>
+__device__ __forceinline__ void down_t1_body(DownShared<RQ> &sh, int d, int G,
+                                             const bf16_t *__restrict__ Wd,
+                                             const uint8_t *__restrict__ mask,
+                                             const bf16_t *__restrict__ act, bf16_t *__restrict__ y,
+                                             int vblock)
 {
+    constexpr int gs = 128;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int col0 = cb * 512 + lane * 8;
     const MaskWords mw = load_mask_words(mask, G, lane);
     if (wave == 0) {
         int base = 0;
@@ -387,64 +342,49 @@ __device__ __forceinline__ void down_t1_body(
         }
     }
     __syncthreads();
-    const long long total = (long long)mw.count * gs;
-    const int n0 = (int)(total * i / n_split), n1 = (int)(total * (i + 1) / n_split);
-    float acc[8];
+    const int count = mw.count;
+    const int rq = wave % RQ, half = wave / RQ;                     // row quad, even/odd groups
+    const int row = (vblock * RQ + rq) * 4 + (lane >> 4);           // output index j
+    const int piece = (lane & 15) * 8;                              // first neuron of this lane's piece
+    const bf16_t *wbase = Wd + (size_t)row * gs + piece;
+    const size_t gstride = (size_t)d * gs;
+    float acc0 = 0.0f, acc1 = 0.0f;
+    for (int u0 = half; u0 < count; u0 += 2 * kDownBatch) {
+        u32x4 v[kDownBatch], a[kDownBatch];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) acc[e] = 0.0f;
-    for (int n = n0 + wave; n < n1; n += kDownWaves * kDownUnroll) {
-        u32x4 v[kDownUnroll];
-        float a[kDownUnroll];
-#pragma unroll
-        for (int q = 0; q < kDownUnroll; ++q) {
-            int nn = n + kDownWaves * q;
-            const bool ok = nn < n1;
-            nn = ok ? nn : n;        // past the end: reload an in-range row with weight 0
-            const int u = nn / gs, m = nn - u * gs;
-            const size_t row = (size_t)sh.list[u] * gs + m;
-            v[q] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(WdT + row * d + col0));
-            a[q] = ok ? act[nn] : 0.0f;
+        for (int q = 0; q < kDownBatch; ++q) {
+            const int u = u0 + 2 * q < count ? u0 + 2 * q : u0;     // past the end: an in-range duplicate
+            v[q] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(wbase + sh.list[u] * gstride));
+            a[q] = *reinterpret_cast<const u32x4 *>(act + u * gs + piece);
         }
 #pragma unroll
-        for (int q = 0; q < kDownUnroll; ++q) {
-            float w[8];
-            unpack8(v[q], w);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) acc[e] = __builtin_fmaf(a[q], w[e], acc[e]);
+        for (int q = 0; q < kDownBatch; ++q) {
+            if (u0 + 2 * q < count) {
+                acc0 = dot2_bf16(v[q].x, a[q].x, acc0);
+                acc1 = dot2_bf16(v[q].y, a[q].y, acc1);
+                acc0 = dot2_bf16(v[q].z, a[q].z, acc0);
+                acc1 = dot2_bf16(v[q].w, a[q].w, acc1);
+            }
         }
     }
-#pragma unroll
-    for (int e = 0; e < 8; ++e) sh.red[wave][lane * 8 + e] = acc[e];
+    float v = acc0 + acc1;
+    v = dpp_add<0xB1>(v);    // the 16 lanes of a row: quad_perm, quad_perm, half mirror, mirror
+    v = dpp_add<0x4E>(v);
+    v = dpp_add<0x141>(v);
+    v = dpp_add<0x140>(v);
+    if (half == 1) sh.half[rq][lane] = v;
     __syncthreads();
-    const int c = threadIdx.x;     // 512 threads, 512 columns
-    {
-        float sum = 0.0f;
-#pragma unroll
-        for (int q = 0; q < kDownWaves; ++q) sum += sh.red[q][c];
-        __hip_atomic_store(partial + (size_t)i * d + cb * 512 + c, sum, __ATOMIC_RELAXED,
-                           __HIP_MEMORY_SCOPE_AGENT);
-    }
-    __syncthreads();               // waits for this workgroup's stores before it takes a ticket
-    if (threadIdx.x == 0)
-        sh.ticket = __hip_atomic_fetch_add(counters + cb, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __syncthreads();
-    if (sh.ticket != n_split - 1) return;
-    float v = 0.0f;
-#pragma unroll 8
-    for (int k = 0; k < n_split; ++k)
-        v += __hip_atomic_load(partial + (size_t)k * d + cb * 512 + c, __ATOMIC_RELAXED,
-                               __HIP_MEMORY_SCOPE_AGENT);
-    y[cb * 512 + c] = f32_to_bf16(v);
-    if (threadIdx.x == 0)
-        __hip_atomic_store(counters + cb, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (half == 0 && (lane & 15) == 0) y[row] = f32_to_bf16(v + sh.half[rq][lane]);
 }
 
-__global__ __launch_bounds__(kDownWaves * 64) void down_t1(
-    int d, int G, int gs, const bf16_t *__restrict__ WdT, const uint8_t *__restrict__ mask,
-    const float *__restrict__ act, float *partial, int32_t *counters, bf16_t *__restrict__ y)
+template <int RQ>
+__global__ __launch_bounds__(RQ * 128) void down_t1(int d, int G, const bf16_t *__restrict__ Wd,
+                                                    const uint8_t *__restrict__ mask,
+                                                    const bf16_t *__restrict__ act,
+                                                    bf16_t *__restrict__ y)
 {
-    __shared__ DownShared sh;
-    down_t1_body(sh, d, G, gs, WdT, mask, act, partial, counters, y, blockIdx.x, blockIdx.y, gridDim.y);
+    __shared__ DownShared<RQ> sh;
+    down_t1_body<RQ>(sh, d, G, Wd, mask, act, y, blockIdx.x);
 }
 
 // Arguments of the prediction for the next block that rides along with this block's kernels.
@@ -463,41 +403,30 @@ struct AheadDev {
 };
 
 // The down projection, with the second predictor layer + ranking + mask of the NEXT block in
-// workgroup 0 (it is the longest dependent chain, so it is dispatched first).  1-D grid:
-// block 0 = mask, block 1 + cb + ncb * i = down-projection workgroup (cb, i).
-__global__ __launch_bounds__(kDownWaves * 64) void down_mask_t1(
-    int d, int G, int gs, const bf16_t *__restrict__ WdT, const uint8_t *__restrict__ mask,
-    const float *__restrict__ act, float *partial, int32_t *counters, bf16_t *__restrict__ y,
-    int ncb, int n_split, AheadDev nx)
+// workgroup 0 (it is the longest dependent chain, so it is dispatched first).
+template <int RQ>
+__global__ __launch_bounds__(RQ * 128) void down_mask_t1(int d, int G, const bf16_t *__restrict__ Wd,
+                                                         const uint8_t *__restrict__ mask,
+                                                         const bf16_t *__restrict__ act,
+                                                         bf16_t *__restrict__ y, AheadDev nx)
 {
-    __shared__ DownShared sh;
+    __shared__ DownShared<RQ> sh;
     __shared__ MaskShared msh;
     if (blockIdx.x == 0) {
-        mask_scores_block<kDownWaves * 64, bf16_t, true>(msh, threadIdx.x, nx.h, nx.Bt, nx.r, nx.scores, G,
-                                                         nx.K, nx.prio_dev, nx.n_dev, nx.drop, nx.order,
-                                                         nx.group_dev, nx.mask, nx.surv_idx, nx.n_surv);
+        mask_scores_block<RQ * 128, bf16_t, true>(msh, threadIdx.x, nx.h, nx.Bt, nx.r, nx.scores, G, nx.K,
+                                                  nx.prio_dev, nx.n_dev, nx.drop, nx.order, nx.group_dev,
+                                                  nx.mask, nx.surv_idx, nx.n_surv);
         return;
     }
-    const int flat = blockIdx.x - 1;
-    down_t1_body(sh, d, G, gs, WdT, mask, act, partial, counters, y, flat % ncb, flat / ncb, n_split);
+    down_t1_body<RQ>(sh, d, G, Wd, mask, act, y, blockIdx.x - 1);
 }
 
 // ---------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------
-int decode_n_split(int T, int d)
-{
-    const int ncb = (d + 511) / 512;
-    if (T == 1) return 256 / ncb > 0 ? 256 / ncb : 1;   // one workgroup per compute unit
-    int n = 1024 / ncb;
-    if (n > 64) n = 64;
-    while (n > 1 && (long long)n * T > 1024) n /= 2;   // bound the partial-sum buffer
-    return n < 1 ? 1 : n;
-}
-
 template <typename WT>
 static hipError_t decode_generic(const WT *x, int T, int d, int G, int gs, const WT *Wg,
-                                 const WT *Wu, const WT *WdT, const uint8_t *mask, WT *y,
+                                 const WT *Wu, const WT *Wd, const uint8_t *mask, WT *y,
                                  const DecodeScratch &ws, hipStream_t s)
 {
     constexpr int TT = 4;
@@ -507,11 +436,8 @@ static hipError_t decode_generic(const WT *x, int T, int d, int G, int gs, const
     if (blocks > 2048) blocks = 2048;
     launch_timed("gate_up_generic", gate_up_generic<WT, TT>, dim3(blocks), dim3(256), s, x, T, d, G, gs,
                  Wg, Wu, mask, (const int32_t *)ws.ulist, (const int32_t *)ws.meta, ws.act, ffn);
-    const int ncb = (d + 511) / 512;
-    down_generic<WT, TT><<<dim3(ncb, ws.n_split), dim3(256), 0, s>>>(ws.act, ffn, T, d, gs, WdT,
-                                                                   ws.ulist, ws.meta, ws.partial);
-    const long long td = (long long)T * d;
-    finalize_generic<WT><<<dim3((unsigned)((td + 63) / 64)), dim3(256), 0, s>>>(ws.partial, ws.n_split, td, y);
+    down_generic<WT, TT><<<dim3((d + 3) / 4), dim3(256), 0, s>>>(ws.act, ffn, T, d, gs, Wd, ws.ulist,
+                                                               ws.meta, y);
     return hipGetLastError();
 }
 
@@ -519,26 +445,25 @@ constexpr int kGateUpBlocks = 256;   // one workgroup (four waves) per compute u
 
 template <int NCH>
 static hipError_t decode_t1(const bf16_t *x, int G, int gs, const bf16_t *Wg, const bf16_t *Wu,
-                            const bf16_t *WdT, const uint8_t *mask, bf16_t *y,
+                            const bf16_t *Wd, const uint8_t *mask, bf16_t *y,
                             const DecodeScratch &ws, const AheadArgs *ah, hipStream_t s)
 {
     constexpr int d = NCH * 512;
-    int32_t *counters = ws.meta + 16;
+    constexpr int RQ = d / 1024;         // 256 workgroups x RQ row quads cover the d/4 quads
+    bf16_t *act = reinterpret_cast<bf16_t *>(ws.act);
     if (!ah) {
         launch_timed("gate_up_t1", gate_up_t1<NCH>, dim3(kGateUpBlocks), dim3(256), s, x, G, gs, Wg, Wu,
-                     mask, ws.act, counters);
-        down_t1<<<dim3(NCH, ws.n_split), dim3(kDownWaves * 64), 0, s>>>(d, G, gs, WdT, mask, ws.act,
-                                                                      ws.partial, counters, y);
+                     mask, act);
+        down_t1<RQ><<<dim3(256), dim3(RQ * 128), 0, s>>>(d, G, Wd, mask, act, y);
         return hipGetLastError();
     }
     const int n_pred = (ah->r + 3) / 4;
     launch_timed("gate_up_pred_t1", gate_up_pred_t1<NCH>, dim3(kGateUpBlocks + n_pred), dim3(256), s, x, G,
-                 gs, Wg, Wu, mask, ws.act, counters, (const bf16_t *)ah->x_next, (const bf16_t *)ah->At,
-                 ah->r, ah->h, n_pred);
+                 gs, Wg, Wu, mask, act, (const bf16_t *)ah->x_next, (const bf16_t *)ah->At, ah->r, ah->h,
+                 n_pred);
     AheadDev nx{ah->h, (const bf16_t *)ah->Bt, ah->r, ah->K, ah->n_dev, ah->prio_dev, ah->drop,
                 ah->scores, ah->order, ah->group_dev, ah->mask, ah->surv_idx, ah->n_surv};
-    down_mask_t1<<<dim3(1 + NCH * ws.n_split), dim3(kDownWaves * 64), 0, s>>>(
-        d, G, gs, WdT, mask, ws.act, ws.partial, counters, y, NCH, ws.n_split, nx);
+    down_mask_t1<RQ><<<dim3(257), dim3(RQ * 128), 0, s>>>(d, G, Wd, mask, act, y, nx);
     return hipGetLastError();
 }
 
@@ -546,17 +471,17 @@ static hipError_t decode_t1(const bf16_t *x, int G, int gs, const bf16_t *Wg, co
 // kernels.  Only the one-token path can do that; *ahead_fused tells the caller whether it did
 // (if not, the caller enqueues the prediction itself).
 hipError_t launch_ffn_decode(int dtype, const void *x, int T, int d, int G, int gs, const void *Wg,
-                             const void *Wu, const void *WdT, const uint8_t *mask, void *y,
+                             const void *Wu, const void *Wd, const uint8_t *mask, void *y,
                              const DecodeScratch &ws, hipStream_t s, const AheadArgs *ahead,
                              bool *ahead_fused)
 {
     if (ahead_fused) *ahead_fused = false;
     if (dtype == 0)
         return decode_generic<float>((const float *)x, T, d, G, gs, (const float *)Wg, (const float *)Wu,
-                                     (const float *)WdT, mask, (float *)y, ws, s);
+                                     (const float *)Wd, mask, (float *)y, ws, s);
     const bf16_t *bx = (const bf16_t *)x, *bg = (const bf16_t *)Wg, *bu = (const bf16_t *)Wu,
-                 *bd = (const bf16_t *)WdT;
-    if (T == 1 && G <= 256 && (d == 4096 || d == 5120 || d == 8192)) {
+                 *bd = (const bf16_t *)Wd;
+    if (T == 1 && G <= 256 && gs == 128 && (d == 4096 || d == 5120 || d == 8192)) {
         const AheadArgs *ah = (ahead && ahead_fused) ? ahead : nullptr;
         if (ah) *ahead_fused = true;
         switch (d) {
@@ -565,6 +490,8 @@ hipError_t launch_ffn_decode(int dtype, const void *x, int T, int d, int G, int 
         default: return decode_t1<16>(bx, G, gs, bg, bu, bd, mask, (bf16_t *)y, ws, ah, s);
         }
     }
+    if (mfma_path_supported(T, d, gs))
+        return launch_ffn_mfma(bx, T, d, G, gs, bg, bu, bd, mask, (bf16_t *)y, ws, s);
     return decode_generic<bf16_t>(bx, T, d, G, gs, bg, bu, bd, mask, (bf16_t *)y, ws, s);
 }
 

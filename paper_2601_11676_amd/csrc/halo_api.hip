@@ -57,8 +57,6 @@ struct Workspace {
         dec.ulist = reinterpret_cast<int32_t *>(take(G * sizeof(int32_t)));
         dec.meta = reinterpret_cast<int32_t *>(take(256 * sizeof(int32_t)));
         dec.act = reinterpret_cast<float *>(take(t * (size_t)s.ffn * sizeof(float)));
-        dec.n_split = decode_n_split((int)t, s.d);
-        dec.partial = reinterpret_cast<float *>(take((size_t)dec.n_split * t * s.d * sizeof(float)));
         bytes = off;
     }
 };
@@ -159,27 +157,27 @@ int halo_build_group_mask(const float *scores, int32_t T, int32_t G, int32_t k_k
 }
 
 int halo_group_sparse_ffn(const halo_shape *shape, const void *x, int32_t T, const void *Wg,
-                          const void *Wu, const void *WdT, const uint8_t *mask, void *y,
+                          const void *Wu, const void *Wd, const uint8_t *mask, void *y,
                           void *workspace, size_t ws_bytes, void *stream)
 {
     int rc = check_shape(shape);
     if (rc) return rc;
     if (T < 0) return HALO_ERR_ARG;
     if (T == 0) return HALO_OK;
-    if (!x || !Wg || !Wu || !WdT || !mask || !y) return HALO_ERR_NULL;
-    if (misaligned(x) || misaligned(Wg) || misaligned(Wu) || misaligned(WdT) || misaligned(y))
+    if (!x || !Wg || !Wu || !Wd || !mask || !y) return HALO_ERR_NULL;
+    if (misaligned(x) || misaligned(Wg) || misaligned(Wu) || misaligned(Wd) || misaligned(y))
         return HALO_ERR_ARG;
     if (!workspace || misaligned(workspace)) return HALO_ERR_WORKSPACE;
     Workspace ws(*shape, T, 0, workspace);
     if (ws_bytes < ws.bytes) return HALO_ERR_WORKSPACE;
     hipError_t e = launch_ffn_decode(shape->dtype, x, T, shape->d, shape->n_groups, shape->group_size,
-                                     Wg, Wu, WdT, mask, y, ws.dec, static_cast<hipStream_t>(stream));
+                                     Wg, Wu, Wd, mask, y, ws.dec, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? HALO_OK : HALO_ERR_HIP;
 }
 
 int halo_ffn_forward(const halo_shape *shape, const void *x, const void *x_pred, int32_t T,
                      const void *At, const void *Bt, const void *Wg, const void *Wu,
-                     const void *WdT, int32_t k_keep, const int8_t *prio_dev, int32_t n_dev,
+                     const void *Wd, int32_t k_keep, const int8_t *prio_dev, int32_t n_dev,
                      const uint8_t *drop, void *y, float *scores, int32_t *order,
                      int8_t *group_dev, uint8_t *mask, int32_t *surv_idx, int32_t *n_surv,
                      void *workspace, size_t ws_bytes, void *stream)
@@ -188,10 +186,10 @@ int halo_ffn_forward(const halo_shape *shape, const void *x, const void *x_pred,
     if (rc) return rc;
     if (T < 0 || k_keep < 0 || k_keep > shape->n_groups || n_dev < 1 || n_dev > 127) return HALO_ERR_ARG;
     if (T == 0) return HALO_OK;
-    if (!x || !x_pred || !At || !Bt || !Wg || !Wu || !WdT || !y || (k_keep > 0 && !prio_dev))
+    if (!x || !x_pred || !At || !Bt || !Wg || !Wu || !Wd || !y || (k_keep > 0 && !prio_dev))
         return HALO_ERR_NULL;
     if (misaligned(x) || misaligned(x_pred) || misaligned(At) || misaligned(Bt) || misaligned(Wg) ||
-        misaligned(Wu) || misaligned(WdT) || misaligned(y) || (scores && misaligned(scores)))
+        misaligned(Wu) || misaligned(Wd) || misaligned(y) || (scores && misaligned(scores)))
         return HALO_ERR_ARG;
     if (!workspace || misaligned(workspace)) return HALO_ERR_WORKSPACE;
     Workspace ws(*shape, T, k_keep, workspace);
@@ -207,12 +205,12 @@ int halo_ffn_forward(const halo_shape *shape, const void *x, const void *x_pred,
                                prio_dev, n_dev, drop, order, group_dev, mk, surv_idx, n_surv, s);
     if (e != hipSuccess) return HALO_ERR_HIP;
     e = launch_ffn_decode(shape->dtype, x, T, shape->d, shape->n_groups, shape->group_size, Wg, Wu,
-                          WdT, mk, y, ws.dec, s);
+                          Wd, mk, y, ws.dec, s);
     return e == hipSuccess ? HALO_OK : HALO_ERR_HIP;
 }
 
 int halo_ffn_forward_ahead(const halo_shape *shape, const void *x, int32_t T, const void *Wg,
-                           const void *Wu, const void *WdT, const uint8_t *mask_cur, void *y,
+                           const void *Wu, const void *Wd, const uint8_t *mask_cur, void *y,
                            const void *x_pred_next, const void *At_next, const void *Bt_next,
                            int32_t k_keep, const int8_t *prio_dev, int32_t n_dev,
                            const uint8_t *drop_next, float *scores_next, int32_t *order_next,
@@ -223,11 +221,11 @@ int halo_ffn_forward_ahead(const halo_shape *shape, const void *x, int32_t T, co
     if (rc) return rc;
     if (T < 0 || k_keep < 0 || k_keep > shape->n_groups || n_dev < 1 || n_dev > 127) return HALO_ERR_ARG;
     if (T == 0) return HALO_OK;
-    if (!x || !Wg || !Wu || !WdT || !mask_cur || !y || !x_pred_next || !At_next || !Bt_next ||
+    if (!x || !Wg || !Wu || !Wd || !mask_cur || !y || !x_pred_next || !At_next || !Bt_next ||
         !mask_next || (k_keep > 0 && !prio_dev))
         return HALO_ERR_NULL;
     if (mask_next == mask_cur || y == x_pred_next) return HALO_ERR_ARG;
-    if (misaligned(x) || misaligned(Wg) || misaligned(Wu) || misaligned(WdT) || misaligned(y) ||
+    if (misaligned(x) || misaligned(Wg) || misaligned(Wu) || misaligned(Wd) || misaligned(y) ||
         misaligned(x_pred_next) || misaligned(At_next) || misaligned(Bt_next) ||
         (scores_next && misaligned(scores_next)))
         return HALO_ERR_ARG;
@@ -240,7 +238,7 @@ int halo_ffn_forward_ahead(const halo_shape *shape, const void *x, int32_t T, co
                  order_next, group_dev_next, mask_next, surv_idx_next, n_surv_next};
     bool fused = false;
     hipError_t e = launch_ffn_decode(shape->dtype, x, T, shape->d, shape->n_groups, shape->group_size, Wg,
-                                     Wu, WdT, mask_cur, y, ws.dec, s, &ah, &fused);
+                                     Wu, Wd, mask_cur, y, ws.dec, s, &ah, &fused);
     if (e != hipSuccess) return HALO_ERR_HIP;
     if (!fused) {
         // no path with spare workgroups for this shape: the prediction follows on the stream

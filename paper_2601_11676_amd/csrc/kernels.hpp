@@ -25,10 +25,8 @@ struct DecodeScratch {
     int32_t *ulist;     // [G]   groups surviving for at least one token, ascending
     int32_t *meta;      // [16 + ...] meta[0] = |ulist|; meta[16..] arrival counters
     float *act;         // [T][ffn] activations SiLU(gate)*up, compacted by union slot
-    float *partial;     // [n_split][T][d] partial down-projection sums
-    int n_split;        // neuron subsets in the down projection
+                        // (the matrix-core path stores bf16 in the same buffer)
 };
-int decode_n_split(int T, int d);
 // The next block's prediction (predictor + mask from x_next), see halo_ffn_forward_ahead.
 struct AheadArgs {
     const void *x_next, *At, *Bt;
@@ -42,9 +40,17 @@ struct AheadArgs {
     int32_t *surv_idx, *n_surv;
 };
 hipError_t launch_ffn_decode(int dtype, const void *x, int T, int d, int G, int gs, const void *Wg,
-                             const void *Wu, const void *WdT, const uint8_t *mask, void *y,
+                             const void *Wu, const void *Wd, const uint8_t *mask, void *y,
                              const DecodeScratch &ws, hipStream_t s, const AheadArgs *ahead = nullptr,
                              bool *ahead_fused = nullptr);
+
+hipError_t launch_union(const uint8_t *mask, int T, int G, int32_t *ulist, int32_t *meta, hipStream_t s);
+
+// ffn_mfma.hip : bf16 matrix-core path for a few tokens (2 <= T <= 16)
+bool mfma_path_supported(int T, int d, int gs);
+hipError_t launch_ffn_mfma(const bf16_t *x, int T, int d, int G, int gs, const bf16_t *Wg,
+                           const bf16_t *Wu, const bf16_t *Wd, const uint8_t *mask, bf16_t *y,
+                           const DecodeScratch &ws, hipStream_t s);
 
 // profile.hip : optional HIP-event bracket around the dominant FFN kernel
 bool timer_acquire(hipEvent_t *start, hipEvent_t *stop);   // false: not profiling (or pool used up)
@@ -53,15 +59,22 @@ void timer_commit(const char *kernel_name);
 // Launch `kernel`; while profiling is active its dispatch carries a start/stop event pair, so
 // the elapsed time is that of the kernel itself (no launch gap inside the bracket).
 template <typename F, typename... Args>
-inline void launch_timed(const char *name, F kernel, dim3 grid, dim3 block, hipStream_t s, Args... args)
+inline void launch_timed_lds(const char *name, F kernel, dim3 grid, dim3 block, size_t lds_bytes,
+                             hipStream_t s, Args... args)
 {
     hipEvent_t e0, e1;
     if (timer_acquire(&e0, &e1)) {
-        hipExtLaunchKernelGGL(kernel, grid, block, 0, s, e0, e1, 0, args...);
+        hipExtLaunchKernelGGL(kernel, grid, block, (uint32_t)lds_bytes, s, e0, e1, 0, args...);
         timer_commit(name);
     } else {
-        kernel<<<grid, block, 0, s>>>(args...);
+        kernel<<<grid, block, lds_bytes, s>>>(args...);
     }
+}
+
+template <typename F, typename... Args>
+inline void launch_timed(const char *name, F kernel, dim3 grid, dim3 block, hipStream_t s, Args... args)
+{
+    launch_timed_lds(name, kernel, grid, block, 0, s, args...);
 }
 
 }  // namespace halo

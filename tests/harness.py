@@ -24,6 +24,7 @@ class Layer:
     def __init__(self, w: hs.Workload, layer: int = 0, copy: int = 0):
         self.w = w
         self.Wg, self.Wu, self.WdT = hs.ffn_weights(w, layer, DEV, copy)
+        self.Wd = H.pack_down_proj(self.WdT, w.group_size)     # the library's group-blocked layout
         self.At, self.Bt = hs.predictor_weights(w, layer, DEV, copy)
         self._host = None
 
@@ -47,7 +48,7 @@ def gpu_forward(w, layer: Layer, x, K, prio_dev_np, drop_np, x_pred=None):
     mask = torch.empty((T, G), dtype=torch.uint8, device=DEV)
     surv_idx = torch.empty((T, max(K, 1)), dtype=torch.int32, device=DEV)[:, :K].contiguous()
     n_surv = torch.empty((T,), dtype=torch.int32, device=DEV)
-    H.halo_ffn_forward(s, x, layer.At, layer.Bt, layer.Wg, layer.Wu, layer.WdT, K, pd, w.n_dev, dr,
+    H.halo_ffn_forward(s, x, layer.At, layer.Bt, layer.Wg, layer.Wu, layer.Wd, K, pd, w.n_dev, dr,
                        y, ws, x_pred=x_pred, scores=scores, order=order, group_dev=group_dev,
                        mask=mask, surv_idx=surv_idx, n_surv=n_surv)
     torch.cuda.synchronize()

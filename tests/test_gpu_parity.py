@@ -139,11 +139,12 @@ def test_ffn_entry_point_with_handmade_masks():
             m = np.tile(np.array(pattern, np.uint8), (T, 1))
             if T > 1:
                 m[1] = 0
-            Wg2, Wu2, Wd2 = L.Wg.clone(), L.Wu.clone(), L.WdT.clone()
+            Wg2, Wu2, Wd2 = L.Wg.clone(), L.Wu.clone(), L.Wd.clone()
             for g in range(6):
                 if not m[:, g].any():
-                    for W in (Wg2, Wu2, Wd2):
-                        W[g * 128:(g + 1) * 128] = float("nan")
+                    Wg2[g * 128:(g + 1) * 128] = float("nan")
+                    Wu2[g * 128:(g + 1) * 128] = float("nan")
+                    Wd2[g] = float("nan")
             y = torch.full((T, w.d), float("nan"), dtype=torch.bfloat16, device=hz.DEV)
             H.halo_group_sparse_ffn(s, x, Wg2, Wu2, Wd2, torch.from_numpy(m).to(hz.DEV), y, ws)
             torch.cuda.synchronize()
@@ -192,7 +193,7 @@ def test_separate_entry_points_equal_the_fused_pass():
     H.halo_build_group_mask(sc, K, torch.from_numpy(pd).to(hz.DEV), w.n_dev,
                             torch.from_numpy(drop).to(hz.DEV), mask, order=order)
     y = torch.empty((T, w.d), dtype=torch.bfloat16, device=hz.DEV)
-    H.halo_group_sparse_ffn(s, x, L.Wg, L.Wu, L.WdT, mask, y, ws)
+    H.halo_group_sparse_ffn(s, x, L.Wg, L.Wu, L.Wd, mask, y, ws)
     torch.cuda.synchronize()
     assert np.array_equal(sc.cpu().numpy().view(np.uint32), fused["scores"].view(np.uint32))
     assert np.array_equal(mask.cpu().numpy(), fused["mask"])
@@ -220,7 +221,7 @@ def test_one_step_ahead_overlap_equals_the_serial_pass():
     H.halo_predict_scores(s, xs[0], L.At, L.Bt, sc, ws)
     H.halo_build_group_mask(sc, K, pdd, w.n_dev, dd[0], masks[0])
     for i in range(n):
-        H.halo_ffn_forward_ahead(s, xs[i], L.Wg, L.Wu, L.WdT, masks[i], ys[i], xs[i + 1], L.At, L.Bt,
+        H.halo_ffn_forward_ahead(s, xs[i], L.Wg, L.Wu, L.Wd, masks[i], ys[i], xs[i + 1], L.At, L.Bt,
                                  K, pdd, w.n_dev, dd[i + 1], masks[i + 1], ws)
     torch.cuda.synchronize()
     for i in range(n):
@@ -232,7 +233,7 @@ def test_one_step_ahead_overlap_equals_the_serial_pass():
     masks2 = masks.clone()
     with torch.cuda.graph(g):
         for i in range(n):
-            H.halo_ffn_forward_ahead(s, xs[i], L.Wg, L.Wu, L.WdT, masks2[i], ys2[i], xs[i + 1], L.At,
+            H.halo_ffn_forward_ahead(s, xs[i], L.Wg, L.Wu, L.Wd, masks2[i], ys2[i], xs[i + 1], L.At,
                                      L.Bt, K, pdd, w.n_dev, dd[i + 1], masks2[i + 1], ws)
     for _ in range(2):
         ys2.zero_()
@@ -240,3 +241,37 @@ def test_one_step_ahead_overlap_equals_the_serial_pass():
         g.replay()
         torch.cuda.synchronize()
         assert torch.equal(ys2, ys) and torch.equal(masks2, masks)
+
+
+@pytest.mark.parametrize("T,d,G,r", [
+    (2, 1024, 5, 64),
+    (4, 5120, 9, 256),       # LLaMA-13B row length, 4 tokens
+    (8, 8192, 7, 512),       # LLaMA-2-70B row length, 8 tokens
+    (16, 4096, 6, 256),
+    (5, 4096, 20, 256),      # union larger than any token's set; ragged neuron runs per wave
+    (3, 640, 3, 40),         # d a multiple of 128 but not of 256
+])
+def test_few_tokens_matrix_core_path(T, d, G, r):
+    w = dataclasses.replace(hs.LLAMA13B_STACK, name="case", d=d, ffn=G * 128, rank=r, T=T, layers=1, seed=17)
+    _say(f"few tokens T={T} d={d} G={G}")
+    L = hz.Layer(w)
+    x = hs.hidden_states(w, 0, hz.DEV)
+    for K in (max(1, G // 2), G):
+        pd = H.halo_build_schedule(K, w.device_plr())
+        drop = hs.drop_outcomes(w, T=T)
+        g = hz.gpu_forward(w, L, x, K, pd, drop)
+        c = hz.oracle_forward(w, L, x, K, pd, drop)
+        hz.assert_parity(g, c, TOL["bf16"], f"few tokens K={K}")
+
+
+@pytest.mark.parametrize("wl,keep", [(hs.LLAMA13B_STACK, 0.5), (hs.LLAMA70B_STACK, 0.5)])
+def test_full_size_single_layer_of_the_stacks(wl, keep):
+    _say(f"{wl.name} one full-size layer")
+    L = hz.Layer(wl, layer=3)
+    x = hs.hidden_states(wl, 0, hz.DEV)
+    K = wl.k_keep(keep)
+    pd = H.halo_build_schedule(K, wl.device_plr())
+    drop = hs.drop_outcomes(wl, 3, 0)
+    g = hz.gpu_forward(wl, L, x, K, pd, drop)
+    c = hz.oracle_forward(wl, L, x, K, pd, drop)
+    hz.assert_parity(g, c, TOL["bf16"], wl.name)
