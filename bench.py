@@ -61,6 +61,9 @@ def main():
                          "of the predictor running one step ahead beside the FFN (halo_ffn_forward_ahead)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
     ap.add_argument("--cpu-steps", type=int, default=64)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="instead of the benchmark, run 8 plain device-to-device copies of 256 MiB "
+                         "(a kernel of known traffic) for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU by design (the simulated devices are a "
@@ -78,6 +81,16 @@ def main():
     H.load_library()
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        n = 256 << 20
+        src = torch.full((n,), 7, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(8):
+            dst.copy_(src)          # one elementwise copy kernel: reads n bytes, writes n bytes
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": {"bytes_read": n, "bytes_written": n, "launches": 8}}))
+        return
     w = hs.BY_NAME[args.workload]
     K, W, NC = args.steps, args.warmup, args.copies
     T, G, d = w.T, w.n_groups, w.d

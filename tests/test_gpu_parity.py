@@ -275,3 +275,49 @@ def test_full_size_single_layer_of_the_stacks(wl, keep):
     g = hz.gpu_forward(wl, L, x, K, pd, drop)
     c = hz.oracle_forward(wl, L, x, K, pd, drop)
     hz.assert_parity(g, c, TOL["bf16"], wl.name)
+
+
+@pytest.mark.parametrize("keep", [0.3, 0.5, 0.7])
+def test_llama13b_stack_teacher_forced(keep):
+    w = hs.LLAMA13B_STACK
+    _say(f"13B stack keep={keep}")
+    check = (0, 1, 2, 20, 39)
+    recs, pd_np, K, h = hz.run_stack_gpu(w, keep, check_layers=check)
+    assert torch.isfinite(h).all()
+    for l in check:
+        hz.check_stack_layer(w, l, recs[l], pd_np, K, TOL["bf16"])
+
+
+def test_llama70b_stack_teacher_forced():
+    w = hs.LLAMA70B_STACK
+    _say("70B stack")
+    check = (0, 1, 2, 40, 79)
+    recs, pd_np, K, h = hz.run_stack_gpu(w, 0.5, check_layers=check)
+    assert torch.isfinite(h).all()
+    for l in check:
+        hz.check_stack_layer(w, l, recs[l], pd_np, K, TOL["bf16"])
+
+
+def test_llama7b_prefill_sampled_tokens():
+    w = hs.LLAMA7B_PREFILL
+    _say("7B prefill, 512 tokens")
+    L = hz.Layer(w)
+    x = hs.hidden_states(w, 0, hz.DEV)
+    K = w.k_keep()
+    pd = H.halo_build_schedule(K, w.device_plr())
+    drop = hs.drop_outcomes(w)
+    g = hz.gpu_forward(w, L, x, K, pd, drop)
+    # scores / ranking / masks for every token; y for a sample of tokens the oracle does one by one
+    At, Bt, Wg, Wu, WdT = L.host()
+    xn = hz.to_np32(x)
+    sc = ref.predict_scores(xn, At, Bt)
+    assert np.array_equal(g["scores"].view(np.uint32), sc.view(np.uint32))
+    m = ref.build_group_mask(sc, K, pd, w.n_dev, drop)
+    for k in hz.INT_KEYS:
+        assert np.array_equal(g[k], m[k]), k
+    sample = [0, 1, 2, 63, 64, 255, 256, 300, 417, 510, 511] + [int(t) for t in np.where(m["n_surv"] == m["n_surv"].min())[0][:2]]
+    y_ref = ref.group_sparse_ffn(xn[sample], Wg, Wu, WdT, w.group_size, m["mask"][sample])
+    for k, t in enumerate(sample):
+        err = np.linalg.norm(g["y"][t] - y_ref[k]) / np.linalg.norm(y_ref[k])
+        assert err <= TOL["bf16"], (t, err)
+    assert np.isfinite(g["y"]).all()
