@@ -492,6 +492,8 @@ hipError_t launch_ffn_decode(int dtype, const void *x, int T, int d, int G, int 
     }
     if (mfma_path_supported(T, d, gs))
         return launch_ffn_mfma(bx, T, d, G, gs, bg, bu, bd, mask, (bf16_t *)y, ws, s);
+    if (prefill_path_supported(T, d, gs))
+        return launch_ffn_prefill(bx, T, d, G, gs, bg, bu, bd, mask, (bf16_t *)y, ws, s);
     return decode_generic<bf16_t>(bx, T, d, G, gs, bg, bu, bd, mask, (bf16_t *)y, ws, s);
 }
 

@@ -57,6 +57,9 @@ struct Workspace {
         dec.ulist = reinterpret_cast<int32_t *>(take(G * sizeof(int32_t)));
         dec.meta = reinterpret_cast<int32_t *>(take(256 * sizeof(int32_t)));
         dec.act = reinterpret_cast<float *>(take(t * (size_t)s.ffn * sizeof(float)));
+        dec.tok_list = reinterpret_cast<int32_t *>(take(G * t * sizeof(int32_t)));
+        dec.tok_cnt = reinterpret_cast<int32_t *>(take(G * sizeof(int32_t)));
+        dec.slot = reinterpret_cast<int32_t *>(take(G * t * sizeof(int32_t)));
         bytes = off;
     }
 };

@@ -25,7 +25,10 @@ struct DecodeScratch {
     int32_t *ulist;     // [G]   groups surviving for at least one token, ascending
     int32_t *meta;      // [16 + ...] meta[0] = |ulist|; meta[16..] arrival counters
     float *act;         // [T][ffn] activations SiLU(gate)*up, compacted by union slot
-                        // (the matrix-core path stores bf16 in the same buffer)
+                        // (the matrix-core paths store bf16 in the same buffer)
+    int32_t *tok_list;  // [G][T] prefill: tokens that keep each group, ascending
+    int32_t *tok_cnt;   // [G]
+    int32_t *slot;      // [T][G] position of the token in its group's list, -1 = not kept
 };
 // The next block's prediction (predictor + mask from x_next), see halo_ffn_forward_ahead.
 struct AheadArgs {
@@ -51,6 +54,12 @@ bool mfma_path_supported(int T, int d, int gs);
 hipError_t launch_ffn_mfma(const bf16_t *x, int T, int d, int G, int gs, const bf16_t *Wg,
                            const bf16_t *Wu, const bf16_t *Wd, const uint8_t *mask, bf16_t *y,
                            const DecodeScratch &ws, hipStream_t s);
+
+// ffn_prefill.hip : bf16 matrix-core path for many tokens
+bool prefill_path_supported(int T, int d, int gs);
+hipError_t launch_ffn_prefill(const bf16_t *x, int T, int d, int G, int gs, const bf16_t *Wg,
+                              const bf16_t *Wu, const bf16_t *Wd, const uint8_t *mask, bf16_t *y,
+                              const DecodeScratch &ws, hipStream_t s);
 
 // profile.hip : optional HIP-event bracket around the dominant FFN kernel
 bool timer_acquire(hipEvent_t *start, hipEvent_t *stop);   // false: not profiling (or pool used up)

@@ -321,3 +321,24 @@ def test_llama7b_prefill_sampled_tokens():
         err = np.linalg.norm(g["y"][t] - y_ref[k]) / np.linalg.norm(y_ref[k])
         assert err <= TOL["bf16"], (t, err)
     assert np.isfinite(g["y"]).all()
+
+
+@pytest.mark.parametrize("T,d,G,r,keepall", [
+    (17, 256, 5, 64, False),      # just above the few-token path; ragged last token tile
+    (40, 512, 7, 64, False),
+    (300, 256, 6, 64, True),      # a group kept by more than 256 tokens: two token chunks
+    (129, 384, 4, 40, False),     # ragged 128-token output tile; d multiple of 128 only
+])
+def test_many_tokens_matrix_core_path_all_tokens(T, d, G, r, keepall):
+    w = dataclasses.replace(hs.LLAMA7B_PREFILL, name="case", d=d, ffn=G * 128, rank=r, T=T, seed=23)
+    _say(f"many tokens T={T} d={d} G={G}")
+    L = hz.Layer(w)
+    x = hs.hidden_states(w, 0, hz.DEV)
+    K = G if keepall else max(1, G // 2)
+    pd = H.halo_build_schedule(K, w.device_plr())
+    drop = hs.drop_outcomes(w, T=T)
+    if not keepall:
+        drop[3] = 1                # one token loses every device: exact zeros expected
+    g = hz.gpu_forward(w, L, x, K, pd, drop)
+    c = hz.oracle_forward(w, L, x, K, pd, drop)
+    hz.assert_parity(g, c, TOL["bf16"], "many tokens")
