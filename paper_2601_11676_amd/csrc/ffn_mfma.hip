@@ -6,9 +6,9 @@
 // tokens at once (v_mfma_f32_16x16x32_bf16: 16 weight rows x 16 tokens x 32 elements).
 //
 //   gate/up : each wave owns a contiguous run of the union's neurons (runs differ by at
-//             most one), cut into tiles of <= 16 rows; a lane loads 64 contiguous bytes of
-//             its row per step; the token fragments come from an LDS copy of x.
-//             act[t][n] = mask ? SiLU(gate)*up : 0 is stored in bf16.
+//             most one), cut into tiles of <= 16 rows, and sweeps the rows in 512-element
+//             chunks; the token fragments are read from x directly (it is small and stays
+//             in cache).  act[t][n] = mask ? SiLU(gate)*up : 0 is stored in bf16.
 //   down    : Wd is group-blocked, Wd[g][j][m]; a workgroup owns 16 output rows j, its four
 //             waves split the union's groups, partial tiles are added through LDS and y is
 //             written directly.
@@ -28,77 +28,102 @@ __device__ __forceinline__ f32x4_t mfma16(const u32x4 &a, const u32x4 &b, const 
                                                    __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
 }
 
-constexpr int kXPad = 8;   // bf16 elements of padding per LDS row of x: rows start 16 bytes apart in bank space
+// Both kernels fetch weights the way the one-token path does -- a wave reads 1 KiB of
+// consecutive bytes per instruction, non-temporal -- and re-shape them into the matrix
+// instruction's operand layout through a private LDS region of the wave (16-byte writes in
+// row order, 16-byte reads in operand order; rows are padded by 16 bytes so that the reads
+// of a 16-lane group hit distinct banks).  Letting each lane fetch its own operand piece
+// instead touches 4x more cache lines per instruction and ran at 40 % of this.
+constexpr int kChunk = 512;                 // row elements per fetch instruction (64 lanes x 8)
+constexpr int kChunkRow = kChunk + 8;       // padded LDS row, elements
 
-// grid: any number of 256-thread workgroups; dynamic LDS = T * (d + kXPad) * 2 bytes
+// grid: any number of 256-thread workgroups; LDS = 4 waves x 16 rows x 1040 B.
+// Waves take contiguous runs of about 12 neurons (fewer waves work when the union is small, so
+// that a tile is not mostly padding); the gate rows of a chunk are multiplied while the up
+// rows of the same chunk are in flight, and the up rows while the next chunk's gate rows are.
+struct RowRegs {
+    u32x4 v[16];
+};
+
 __global__ __launch_bounds__(256) void gate_up_mt(
     const bf16_t *__restrict__ x, int T, int d, int G, int gs, const bf16_t *__restrict__ Wg,
     const bf16_t *__restrict__ Wu, const uint8_t *__restrict__ mask, const int32_t *__restrict__ ulist,
     const int32_t *__restrict__ meta, bf16_t *__restrict__ act, int act_stride)
 {
-    extern __shared__ __attribute__((aligned(16))) char smem[];
-    bf16_t *xl = reinterpret_cast<bf16_t *>(smem);
-    const int xs = d + kXPad;
+    __shared__ __attribute__((aligned(16))) bf16_t sW[4][16 * kChunkRow];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int pieces = d / 8;
-    for (int idx = tid; idx < T * pieces; idx += 256) {
-        const int t = idx / pieces, c = idx - t * pieces;
-        *reinterpret_cast<u32x4 *>(xl + (size_t)t * xs + c * 8) =
-            *reinterpret_cast<const u32x4 *>(x + (size_t)t * d + c * 8);
-    }
-    __syncthreads();
+    bf16_t *my = sW[wave];
     const long long total = (long long)meta[0] * gs;
-    const int nw = gridDim.x * 4, w = blockIdx.x * 4 + wave;
+    int nw = gridDim.x * 4;
+    const long long want = (total + 11) / 12;
+    if (want < nw) nw = want < 1 ? 1 : (int)want;
+    const int w = blockIdx.x * 4 + wave;
+    if (w >= nw) return;
     const int n0 = (int)(total * w / nw), n1 = (int)(total * (w + 1) / nw);
     const int L = n1 - n0;
     if (L <= 0) return;
     const int ntile = (L + 15) / 16;
     const int i = lane & 15, q = lane >> 4;
     const int tok = i < T ? i : T - 1;                      // columns >= T repeat the last token, unused
-    const bf16_t *xrow = xl + (size_t)tok * xs + q * 32;
+    const bf16_t *xrow = x + (size_t)tok * d + q * 8;
+    const int nck = (d + kChunk - 1) / kChunk;              // the last chunk may be 128, 256 or 384 wide
     for (int tile = 0; tile < ntile; ++tile) {
         const int r0 = n0 + (int)((long long)L * tile / ntile);
         const int r1 = n0 + (int)((long long)L * (tile + 1) / ntile);     // r1 - r0 <= 16
-        const int n = r0 + i < r1 ? r0 + i : r1 - 1;       // rows past the tile repeat its last row
-        const int u = n / gs;
-        const size_t wrow = (size_t)ulist[u] * gs + (n - u * gs);
-        const bf16_t *pg = Wg + wrow * d + q * 32;
-        const bf16_t *pu = Wu + wrow * d + q * 32;
+        const int cnt = r1 - r0;
+        size_t wrow[16];                                    // wave-uniform
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            const int n = k < cnt ? r0 + k : r1 - 1;
+            const int u = n / gs;
+            wrow[k] = ((size_t)ulist[u] * gs + (n - u * gs)) * d;
+        }
+        auto width_of = [&](int c) { return min(kChunk, d - c * kChunk); };
+        auto fetch = [&](RowRegs &r, const bf16_t *W, int c) {
+            const bool on = lane * 8 < width_of(c);
+#pragma unroll
+            for (int k = 0; k < 16; ++k) {
+                r.v[k] = u32x4{0u, 0u, 0u, 0u};
+                if (k < cnt && on)
+                    r.v[k] = __builtin_nontemporal_load(
+                        reinterpret_cast<const u32x4 *>(W + wrow[k] + c * kChunk + lane * 8));
+            }
+        };
+        auto fetch_x = [&](u32x4 (&b)[16], int c) {
+            const int steps = width_of(c) / 32;
+#pragma unroll
+            for (int s = 0; s < 16; ++s)
+                b[s] = s < steps ? *reinterpret_cast<const u32x4 *>(xrow + c * kChunk + s * 32)
+                                 : u32x4{0u, 0u, 0u, 0u};
+        };
+        auto multiply = [&](const RowRegs &r, const u32x4 (&b)[16], int c, f32x4_t &acc) {
+            const int steps = width_of(c) / 32;
+#pragma unroll
+            for (int k = 0; k < 16; ++k)
+                *reinterpret_cast<u32x4 *>(my + k * kChunkRow + lane * 8) = r.v[k];
+#pragma unroll
+            for (int s = 0; s < 16; ++s) {
+                if (s < steps) {
+                    const u32x4 a = *reinterpret_cast<const u32x4 *>(my + i * kChunkRow + s * 32 + q * 8);
+                    acc = mfma16(a, b[s], acc);
+                }
+            }
+        };
         f32x4_t cg = {0.f, 0.f, 0.f, 0.f}, cu = {0.f, 0.f, 0.f, 0.f};
-        // 256 elements of every row per step: sixteen 16-byte loads in flight per lane
-        int ks = 0;
-        for (; ks + 256 <= d; ks += 256) {
-            u32x4 ag[8], au[8], b[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int off = ks + (j >> 2) * 128 + (j & 3) * 8;
-                ag[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(pg + off));
-                au[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(pu + off));
-            }
-#pragma unroll
-            for (int j = 0; j < 8; ++j)
-                b[j] = *reinterpret_cast<const u32x4 *>(xrow + ks + (j >> 2) * 128 + (j & 3) * 8);
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                cg = mfma16(ag[j], b[j], cg);
-                cu = mfma16(au[j], b[j], cu);
-            }
+        RowRegs R0, R1;
+        u32x4 b[16];
+        fetch_x(b, 0);
+        fetch(R0, Wg, 0);
+        for (int c = 0; c + 1 < nck; ++c) {
+            fetch(R1, Wu, c);
+            multiply(R0, b, c, cg);
+            fetch(R0, Wg, c + 1);
+            multiply(R1, b, c, cu);
+            fetch_x(b, c + 1);
         }
-        for (; ks < d; ks += 128) {
-            u32x4 ag[4], au[4], b[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                ag[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(pg + ks + j * 8));
-                au[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(pu + ks + j * 8));
-            }
-#pragma unroll
-            for (int j = 0; j < 4; ++j) b[j] = *reinterpret_cast<const u32x4 *>(xrow + ks + j * 8);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                cg = mfma16(ag[j], b[j], cg);
-                cu = mfma16(au[j], b[j], cu);
-            }
-        }
+        fetch(R1, Wu, nck - 1);
+        multiply(R0, b, nck - 1, cg);
+        multiply(R1, b, nck - 1, cu);
         // D: column = token i, rows 4q..4q+3 of the tile
         if (i < T) {
 #pragma unroll
@@ -114,14 +139,18 @@ __global__ __launch_bounds__(256) void gate_up_mt(
     }
 }
 
-// grid: d/16 workgroups of 256 threads; gs % 32 == 0
-constexpr int kDownGroups = 4;     // groups in flight per wave
+// grid: d/16 workgroups of 256 threads; group size 128.  A workgroup owns 16 output rows; a
+// group's 16 x 128 tile of Wd is 4 KiB of consecutive bytes, fetched by four instructions.
+constexpr int kDownGroups = 4;              // groups in flight per wave
+constexpr int kTileRow = 128 + 8;           // padded LDS row, elements
 
 __global__ __launch_bounds__(256) void down_mt(
-    int T, int d, int gs, const bf16_t *__restrict__ Wd, const int32_t *__restrict__ ulist,
+    int T, int d, const bf16_t *__restrict__ Wd, const int32_t *__restrict__ ulist,
     const int32_t *__restrict__ meta, const bf16_t *__restrict__ act, int act_stride,
     bf16_t *__restrict__ y)
 {
+    constexpr int gs = 128;
+    __shared__ __attribute__((aligned(16))) bf16_t sT[4][kDownGroups][16 * kTileRow];
     __shared__ float red[4][64][4];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int i = lane & 15, q = lane >> 4;
@@ -129,41 +158,37 @@ __global__ __launch_bounds__(256) void down_mt(
     const int n_u = meta[0];
     const int u0 = n_u * wave / 4, u1 = n_u * (wave + 1) / 4;
     const int tok = i < T ? i : T - 1;
-    const int ksteps = gs / 32;
     const bf16_t *arow = act + (size_t)tok * act_stride + q * 8;
     const size_t gstride = (size_t)d * gs;
-    const bf16_t *wrow = Wd + (size_t)(j0 + i) * gs + q * 8;
+    const bf16_t *wtile = Wd + (size_t)j0 * gs + lane * 8;          // + n*512 elements for instruction n
     f32x4_t c = {0.f, 0.f, 0.f, 0.f};
-    if (ksteps == 4) {
-        for (int ub = u0; ub < u1; ub += kDownGroups) {
-            u32x4 a[kDownGroups][4], b[kDownGroups][4];
+    for (int ub = u0; ub < u1; ub += kDownGroups) {
+        u32x4 r[kDownGroups][4], b[kDownGroups][4];
 #pragma unroll
-            for (int k = 0; k < kDownGroups; ++k) {
-                const int u = ub + k < u1 ? ub + k : ub;           // past the end: in-range duplicate
-                const bf16_t *pw = wrow + ulist[u] * gstride;
-                const bf16_t *pa = arow + (size_t)u * gs;
+        for (int k = 0; k < kDownGroups; ++k) {
+            const int u = ub + k < u1 ? ub + k : ub;                 // past the end: in-range duplicate
+            const bf16_t *pw = wtile + ulist[u] * gstride;
+            const bf16_t *pa = arow + (size_t)u * gs;
 #pragma unroll
-                for (int s = 0; s < 4; ++s) {
-                    a[k][s] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(pw + s * 32));
-                    b[k][s] = *reinterpret_cast<const u32x4 *>(pa + s * 32);
-                }
-            }
-#pragma unroll
-            for (int k = 0; k < kDownGroups; ++k) {
-                if (ub + k < u1) {
-#pragma unroll
-                    for (int s = 0; s < 4; ++s) c = mfma16(a[k][s], b[k][s], c);
-                }
+            for (int n = 0; n < 4; ++n) {
+                r[k][n] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(pw + n * 512));
+                b[k][n] = *reinterpret_cast<const u32x4 *>(pa + n * 32);
             }
         }
-    } else {
-        for (int u = u0; u < u1; ++u) {
-            const bf16_t *pw = wrow + ulist[u] * gstride;
-            const bf16_t *pa = arow + (size_t)u * gs;
-            for (int s = 0; s < ksteps; ++s) {
-                const u32x4 a = *reinterpret_cast<const u32x4 *>(pw + s * 32);
-                const u32x4 b = *reinterpret_cast<const u32x4 *>(pa + s * 32);
-                c = mfma16(a, b, c);
+        // instruction n, lane l holds row 4n + l/16, elements (l%16)*8..+7
+#pragma unroll
+        for (int k = 0; k < kDownGroups; ++k)
+#pragma unroll
+            for (int n = 0; n < 4; ++n)
+                *reinterpret_cast<u32x4 *>(&sT[wave][k][(4 * n + q) * kTileRow + i * 8]) = r[k][n];
+#pragma unroll
+        for (int k = 0; k < kDownGroups; ++k) {
+            if (ub + k < u1) {
+#pragma unroll
+                for (int s = 0; s < 4; ++s) {
+                    const u32x4 a = *reinterpret_cast<const u32x4 *>(&sT[wave][k][i * kTileRow + s * 32 + q * 8]);
+                    c = mfma16(a, b[k][s], c);
+                }
             }
         }
     }
@@ -182,23 +207,9 @@ __global__ __launch_bounds__(256) void down_mt(
 // ---------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------
-static int max_lds_bytes()
-{
-    static int cached = -1;
-    if (cached < 0) {
-        int dev = 0, v = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess)
-            v = 65536;
-        cached = v;
-    }
-    return cached;
-}
-
 bool mfma_path_supported(int T, int d, int gs)
 {
-    if (T < 2 || T > 16 || d % 128 != 0 || gs % 32 != 0) return false;
-    return (long long)T * (d + kXPad) * 2 <= max_lds_bytes();
+    return T >= 2 && T <= 16 && d % 128 == 0 && gs == 128;
 }
 
 hipError_t launch_ffn_mfma(const bf16_t *x, int T, int d, int G, int gs, const bf16_t *Wg,
@@ -209,17 +220,10 @@ hipError_t launch_ffn_mfma(const bf16_t *x, int T, int d, int G, int gs, const b
     bf16_t *act = reinterpret_cast<bf16_t *>(ws.act);
     hipError_t e = launch_union(mask, T, G, ws.ulist, ws.meta, s);
     if (e != hipSuccess) return e;
-    const size_t lds = (size_t)T * (d + kXPad) * 2;
-    static size_t lds_enabled = 0;
-    if (lds > 65536 && lds > lds_enabled) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(gate_up_mt),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        lds_enabled = lds;
-    }
-    launch_timed_lds("gate_up_mt", gate_up_mt, dim3(256), dim3(256), lds, s, x, T, d, G, gs, Wg, Wu, mask,
-                     (const int32_t *)ws.ulist, (const int32_t *)ws.meta, act, ffn);
-    down_mt<<<dim3(d / 16), dim3(256), 0, s>>>(T, d, gs, Wd, ws.ulist, ws.meta, act, ffn, y);
+    // one workgroup per compute unit (the kernel holds two row batches in registers, one wave per SIMD)
+    launch_timed("gate_up_mt", gate_up_mt, dim3(256), dim3(256), s, x, T, d, G, gs, Wg, Wu, mask,
+                 (const int32_t *)ws.ulist, (const int32_t *)ws.meta, act, ffn);
+    down_mt<<<dim3(d / 16), dim3(256), 0, s>>>(T, d, Wd, ws.ulist, ws.meta, act, ffn, y);
     return hipGetLastError();
 }
 
