@@ -1,21 +1,33 @@
 #!/usr/bin/env python3
 """Benchmark of the HALO group-sparse FFN path on one MI355X.
 
-One "step" = one whole pass (predictor -> group mask -> group-sparse SwiGLU FFN, i.e.
-halo_ffn_forward) over one batch of synthetic input.  The default workload is the
-LLaMA-7B-shape single-layer decode: d=4096, ffn=11008 as 86 groups of 128, bf16,
-one token per step, 43 groups kept, 4 simulated devices with loss rates
-{0, 0.05, 0.1, 0.2}, fresh hidden state and loss outcomes per step.
+One "step" = one whole pass (predictor -> group mask -> group-sparse SwiGLU FFN) over one
+batch of synthetic input.  The default workload is the LLaMA-7B-shape single-layer decode:
+d=4096, ffn=11008 as 86 groups of 128, bf16, one token per step, 43 groups kept, 4 simulated
+devices with loss rates {0, 0.05, 0.1, 0.2}, fresh hidden state and loss outcomes per step.
+`--workload` also accepts llama7b_prefill (512 tokens per step, matrix-core roofline),
+llama13b_stack and llama70b_stack (one layer of that shape per step, 4 / 8 tokens) and tiny.
 
-Weights: the layer is replicated into --copies independent copies visited round-robin,
-so that consecutive steps read different HBM (a real decode walks 32 different layers
-per token; one 135 MB half-layer would otherwise sit in the 256 MB Infinity Cache).
+Form of the pass.  By default each step calls halo_ffn_forward_ahead: the FFN of step s with
+the mask predicted one step earlier, and beside it -- in spare workgroups of the same two
+launches -- predictor + mask of step s+1 (the paper's Pred || Load/Comp overlap, one layer
+ahead).  Every step therefore runs the predictor, the mask and the FFN once.  `--serial` uses
+halo_ffn_forward (predictor, mask, FFN back to back) instead; workloads with more than one
+token always do.
+
+Weights: the layer is replicated into --copies independent copies visited round-robin, so
+that consecutive steps read different HBM (a real decode walks 32 different layers per token;
+one 135 MB half-layer would otherwise sit in the 256 MB Infinity Cache).
 
 Timing: all inputs are resident in HBM before the clock starts.  The K timed steps are
-captured once into a HIP graph (the loop is launch-bound otherwise) and replayed between
-two device synchronisations.  A second, eager pass over the same K steps brackets the
-dominant kernel (FFN gate/up) with HIP events for the roofline figure.  The CPU oracle
-is then timed on a bounded sample of the same steps and its output compared.
+captured once into a HIP graph (the loop is launch-bound otherwise) and one replay is timed
+between two device synchronisations: `value`.  A second, eager pass over the same K steps
+attaches a HIP event pair to the dispatch of the dominant kernel (FFN gate/up) of every
+--time-every-th step for the `roofline` object; the other launches are plain, so the host
+stays ahead of the GPU and the kernel is measured in the same back-to-back regime as the
+graph.  `roofline.traffic` is read from the committed rocprofv3 --pmc summary under
+profiles/ (null if there is none for this kernel and workload).  The CPU oracle is then timed
+on a bounded sample of the same steps and its outputs compared with the GPU's.
 
 Prints one JSON line.
 """
@@ -61,6 +73,9 @@ def main():
                          "of the predictor running one step ahead beside the FFN (halo_ffn_forward_ahead)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
     ap.add_argument("--cpu-steps", type=int, default=64)
+    ap.add_argument("--time-every", type=int, default=4,
+                    help="attach HIP events to one dominant-kernel launch in this many (event launches are "
+                         "slow on the host; timing all of them starves the GPU and slows the kernel itself)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="instead of the benchmark, run 8 plain device-to-device copies of 256 MiB "
                          "(a kernel of known traffic) for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE")
@@ -189,10 +204,14 @@ def main():
 
     # ---- dominant kernel under HIP events (eager pass over the same steps) -------------
     prologue()
-    H.halo_profile_begin(K)
+    H.halo_profile_begin(K, args.time_every)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
     for s in range(W, W + K):
         step(s)
+    t_enq = time.perf_counter() - t0
     torch.cuda.synchronize()
+    t_eager = time.perf_counter() - t0
     kern_ms, kern_n, kern_name = H.halo_profile_end()
     same = bool(torch.equal(y_timed, ys[W:W + K]))       # graph replay == eager, bit for bit
 
@@ -203,11 +222,14 @@ def main():
     gate_up_bytes = float(union.sum()) * 2 * group_bytes  # over the K launches
     ffn_bytes = float(union.sum()) * 3 * group_bytes
     pred_bytes = K * (w.rank * d + G * w.rank) * esz
+    # bytes of exactly the launches that were timed (every args.time_every-th step)
+    timed_union = union[::args.time_every][:kern_n]
+    gate_up_bytes = float(timed_union.sum()) * 2 * group_bytes
     achieved = gate_up_bytes / (kern_ms * 1e-3) / 1e9 if kern_ms > 0 else 0.0
     traffic = read_traffic(kern_name, w.name)
     if kern_name.endswith("_pf"):
         # many tokens: the dominant kernel is a dense contraction on the matrix cores
-        flops = float(n_surv.sum()) * w.group_size * d * 2 * 2          # gate and up, 2 flop per MAC
+        flops = float(n_surv[::args.time_every][:kern_n].sum()) * w.group_size * d * 2 * 2   # gate and up, 2 flop per MAC
         roof = {"bound": "mfma", "kernel": kern_name, "achieved": flops / (kern_ms * 1e-3) / 1e12,
                 "peak": 2500.0, "unit": "TFLOP/s", "frac": flops / (kern_ms * 1e-3) / 1e12 / 2500.0,
                 "traffic": traffic, "launches": int(kern_n), "avg_us": kern_ms / max(kern_n, 1) * 1e3,
@@ -243,6 +265,7 @@ def main():
             "total_GBps": (ffn_bytes + pred_bytes) / elapsed / 1e9,
             "frac_of_hbm_peak": ffn_bytes / elapsed / 1e9 / HBM_PEAK_GBPS,
             "graph_equals_eager": same,
+            "event_pass_us_per_step": t_eager / K * 1e6, "event_pass_host_us_per_step": t_enq / K * 1e6,
         },
         "roofline": roof,
     }

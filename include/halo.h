@@ -192,11 +192,13 @@ int halo_ffn_forward_ahead(const halo_shape *shape, const void *x, int32_t T, co
  * surviving groups' weight bytes -- with a pair of HIP events on the launch stream.
  * halo_profile_end waits for the recorded events and returns the summed elapsed time
  * (milliseconds), the number of launches timed, and the kernel's name (HOST pointers;
- * each may be NULL).  At most max_launches launches are timed.  Do not use while a
- * stream is being captured into a graph.  Errors: HALO_ERR_ARG (bad count, begin while
- * active, end while inactive), HALO_ERR_HIP.
+ * each may be NULL).  One launch in `every` is timed (an event-carrying launch costs the
+ * host several times a plain one, so timing every launch can leave the GPU waiting for the
+ * host and change what is measured), at most max_launches in total.  Do not use while a
+ * stream is being captured into a graph.  Errors: HALO_ERR_ARG (bad count or stride, begin
+ * while active, end while inactive), HALO_ERR_HIP.
  */
-int halo_profile_begin(int32_t max_launches);
+int halo_profile_begin(int32_t max_launches, int32_t every);
 int halo_profile_end(double *total_ms, int64_t *launches, char *kernel_name, int32_t name_cap);
 
 #ifdef __cplusplus

@@ -77,7 +77,7 @@ def load_library():
     lib.halo_ffn_forward_ahead.argtypes = [ps, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, i32,
                                            vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.halo_profile_begin.restype = C.c_int
-    lib.halo_profile_begin.argtypes = [i32]
+    lib.halo_profile_begin.argtypes = [i32, i32]
     lib.halo_profile_end.restype = C.c_int
     lib.halo_profile_end.argtypes = [vp, vp, vp, i32]
     _lib = lib
@@ -218,8 +218,8 @@ def prepared(fn, *args, **kwargs):
     return call
 
 
-def halo_profile_begin(max_launches: int) -> None:
-    _check("halo_profile_begin", load_library().halo_profile_begin(int(max_launches)))
+def halo_profile_begin(max_launches: int, every: int = 1) -> None:
+    _check("halo_profile_begin", load_library().halo_profile_begin(int(max_launches), int(every)))
 
 
 def halo_profile_end():

@@ -441,7 +441,9 @@ static hipError_t decode_generic(const WT *x, int T, int d, int G, int gs, const
     return hipGetLastError();
 }
 
-constexpr int kGateUpBlocks = 256;   // one workgroup (four waves) per compute unit
+// One workgroup (four waves) per compute unit.  Measured in place: 384 or 512 workgroups, or
+// dispatching the predictor's workgroups after the gate/up ones, are all slower.
+constexpr int kGateUpBlocks = 256;
 
 template <int NCH>
 static hipError_t decode_t1(const bf16_t *x, int G, int gs, const bf16_t *Wg, const bf16_t *Wu,

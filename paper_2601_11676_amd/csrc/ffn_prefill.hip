@@ -6,11 +6,12 @@
 //
 //   group_tokens : for every group, the ascending list of tokens that keep it, and for
 //                  every (token, group) the token's slot in that list (-1 = not kept).
-//   gate_up_pf   : one workgroup = 32 neurons of one group x up to 256 of the group's
-//                  tokens.  The 64 weight rows (32 gate + 32 up) are staged through LDS once
-//                  per 64-element K step and shared by the four waves; each wave owns 64
+//   gate_up_pf   : one workgroup = 64 neurons of one group x up to 128 of the group's
+//                  tokens.  The 128 weight rows (64 gate + 64 up) are staged through LDS once
+//                  per 64-element K step and shared by the four waves; each wave owns 32
 //                  tokens and loads their x rows (gathered by the token list) straight into
-//                  registers as the B operand.  Every weight byte is read once from HBM.
+//                  registers as the B operand.  A group's weights are read once from HBM and
+//                  once more from cache per further 128 tokens.
 //                  act[g][slot][m] = SiLU(gate) * up in bf16.
 //   down_pf      : output-stationary: one workgroup = 128 tokens x 64 outputs, walking all
 //                  groups; a token that does not keep a group feeds zeros, so it contributes
@@ -63,119 +64,140 @@ __global__ __launch_bounds__(256) void group_tokens_kernel(const uint8_t *__rest
 }
 
 // ---------------------------------------------------------------------------
-// gate/up: grid (G * gs/32, ceil(T/256)), 256 threads
+// gate/up: grid (G * gs/NB, ceil(T/128)), 256 threads
 // ---------------------------------------------------------------------------
 constexpr int kKS = 64;             // K elements per LDS stage
 constexpr int kARow = kKS + 8;      // padded LDS row (elements): 144 bytes, conflict-free 16-byte reads
 
+template <int TT>
 struct BFrags {
-    u32x4 v[2][4];                  // [k half of the stage][token tile]
+    u32x4 v[2][TT];                 // [k half of the stage][token tile]
 };
 
+// TT = 16-token tiles per wave (a workgroup covers 4 * TT * 16 tokens of the group's list);
+// NB = neurons per workgroup (32 or 64).  More neurons per workgroup means each gathered x
+// row is fetched fewer times: x does not stay in the 4 MB L2 next to the weight stream, and
+// its re-fetches were what bounded the 32-neuron form.
+template <int TT, int NB>
 __global__ __launch_bounds__(256) void gate_up_pf(
     const bf16_t *__restrict__ x, int T, int d, int gs, const bf16_t *__restrict__ Wg,
     const bf16_t *__restrict__ Wu, const int32_t *__restrict__ tok_list,
     const int32_t *__restrict__ tok_cnt, bf16_t *__restrict__ act)
 {
-    __shared__ __attribute__((aligned(16))) bf16_t sA[2][64 * kARow];
+    constexpr int HT = NB / 16;                              // 16-row tiles per matrix
+    constexpr int NP = NB / 32;                              // staging passes per matrix
+    __shared__ __attribute__((aligned(16))) bf16_t sA[2][2 * NB * kARow];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int i16 = lane & 15, q = lane >> 4;
-    const int per_group = gs / 32;
+    const int per_group = gs / NB;
     const int g = blockIdx.x / per_group, nt = blockIdx.x - g * per_group;
     const int cnt = tok_cnt[g];
-    const int c0 = blockIdx.y * 256;
+    constexpr int kTok = 4 * TT * 16;                        // tokens per workgroup
+    const int c0 = blockIdx.y * kTok;
     if (c0 >= cnt) return;                                   // uniform for the workgroup
     const int32_t *list = tok_list + (size_t)g * T;
-    // this wave's tokens: slots c0 + wave*64 + tt*16 + i16
-    const bf16_t *xrow[4];
+    // this wave's tokens: slots c0 + (wave*TT + tt)*16 + i16
+    const bf16_t *xrow[TT];
 #pragma unroll
-    for (int tt = 0; tt < 4; ++tt) {
-        int sl = c0 + wave * 64 + tt * 16 + i16;
+    for (int tt = 0; tt < TT; ++tt) {
+        int sl = c0 + (wave * TT + tt) * 16 + i16;
         sl = sl < cnt ? sl : cnt - 1;                        // past the end: a valid duplicate, never stored
         xrow[tt] = x + (size_t)list[sl] * d + q * 8;
     }
-    // staging role of this thread: row sr (0..31 gate, 32..63 up), 16-byte pieces sp and sp + 4 of 8
-    const int sr = tid >> 2, sp = tid & 3;
-    const size_t neuron0 = (size_t)g * gs + nt * 32;
-    const bf16_t *wsrc = (sr < 32 ? Wg + (neuron0 + sr) * d : Wu + (neuron0 + sr - 32) * d) + sp * 8;
-    bf16_t *wdst0 = &sA[0][sr * kARow + sp * 8], *wdst1 = &sA[1][sr * kARow + sp * 8];
+    // staging role of this thread: eight threads share a row's 128-byte segment; per pass the
+    // thread takes gate row sr + 32*p and up row sr + 32*p (LDS rows r and NB + r), piece sp
+    const int sr = tid >> 3, sp = tid & 7;
+    const size_t neuron0 = (size_t)g * gs + nt * NB;
+    const bf16_t *wsrc_g = Wg + (neuron0 + sr) * d + sp * 8;
+    const bf16_t *wsrc_u = Wu + (neuron0 + sr) * d + sp * 8;
+    const int dst_off = sr * kARow + sp * 8;
 
-    f32x4_t acc[4][4];
+    f32x4_t acc[2 * HT][TT];
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt)
+    for (int mt = 0; mt < 2 * HT; ++mt)
 #pragma unroll
-        for (int tt = 0; tt < 4; ++tt) acc[mt][tt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        for (int tt = 0; tt < TT; ++tt) acc[mt][tt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-    auto load_a = [&](int k0, u32x4 &r0, u32x4 &r1) {
-        r0 = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(wsrc + k0));
-        r1 = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(wsrc + k0 + 32));
+    struct AStage {
+        u32x4 g[NP], u[NP];
     };
-    auto store_a = [&](bf16_t *dst, const u32x4 &r0, const u32x4 &r1) {
-        *reinterpret_cast<u32x4 *>(dst) = r0;
-        *reinterpret_cast<u32x4 *>(dst + 32) = r1;
+    auto load_a = [&](int k0, AStage &r) {
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+            r.g[p] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(wsrc_g + (size_t)p * 32 * d + k0));
+            r.u[p] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(wsrc_u + (size_t)p * 32 * d + k0));
+        }
     };
-    auto load_b = [&](int k0, BFrags &b) {
+    auto store_a = [&](bf16_t *buf, const AStage &r) {
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+            *reinterpret_cast<u32x4 *>(buf + dst_off + p * 32 * kARow) = r.g[p];
+            *reinterpret_cast<u32x4 *>(buf + dst_off + (NB + p * 32) * kARow) = r.u[p];
+        }
+    };
+    auto load_b = [&](int k0, BFrags<TT> &b) {
 #pragma unroll
         for (int kh = 0; kh < 2; ++kh)
 #pragma unroll
-            for (int tt = 0; tt < 4; ++tt)
+            for (int tt = 0; tt < TT; ++tt)
                 b.v[kh][tt] = *reinterpret_cast<const u32x4 *>(xrow[tt] + k0 + kh * 32);
     };
-    auto compute = [&](const bf16_t *a_lds, const BFrags &b) {
+    auto compute = [&](const bf16_t *a_lds, const BFrags<TT> &b) {
 #pragma unroll
         for (int kh = 0; kh < 2; ++kh) {
-            u32x4 a[4];
+            u32x4 a[2 * HT];
 #pragma unroll
-            for (int mt = 0; mt < 4; ++mt)
+            for (int mt = 0; mt < 2 * HT; ++mt)
                 a[mt] = *reinterpret_cast<const u32x4 *>(a_lds + (mt * 16 + i16) * kARow + kh * 32 + q * 8);
 #pragma unroll
-            for (int mt = 0; mt < 4; ++mt)
+            for (int mt = 0; mt < 2 * HT; ++mt)
 #pragma unroll
-                for (int tt = 0; tt < 4; ++tt) acc[mt][tt] = mfma16p(a[mt], b.v[kh][tt], acc[mt][tt]);
+                for (int tt = 0; tt < TT; ++tt) acc[mt][tt] = mfma16p(a[mt], b.v[kh][tt], acc[mt][tt]);
         }
     };
 
     // software pipeline over K: while stage s is multiplied, stage s+1's weights travel
     // global -> registers -> the other LDS buffer and its x fragments travel to registers
     const int nstage = d / kKS;                 // even (d % 128 == 0)
-    u32x4 ra0, ra1;
-    BFrags b0, b1;
-    load_a(0, ra0, ra1);
+    AStage ra;
+    BFrags<TT> b0, b1;
+    bf16_t *wdst0 = sA[0], *wdst1 = sA[1];
+    load_a(0, ra);
     load_b(0, b0);
-    store_a(wdst0, ra0, ra1);
+    store_a(wdst0, ra);
     __syncthreads();
     int s = 0;
     for (; s + 2 < nstage; s += 2) {
-        load_a((s + 1) * kKS, ra0, ra1);
+        load_a((s + 1) * kKS, ra);
         load_b((s + 1) * kKS, b1);
         compute(sA[0], b0);
-        store_a(wdst1, ra0, ra1);
+        store_a(wdst1, ra);
         __syncthreads();
-        load_a((s + 2) * kKS, ra0, ra1);
+        load_a((s + 2) * kKS, ra);
         load_b((s + 2) * kKS, b0);
         compute(sA[1], b1);
-        store_a(wdst0, ra0, ra1);
+        store_a(wdst0, ra);
         __syncthreads();
     }
-    load_a((s + 1) * kKS, ra0, ra1);
+    load_a((s + 1) * kKS, ra);
     load_b((s + 1) * kKS, b1);
     compute(sA[0], b0);
-    store_a(wdst1, ra0, ra1);
+    store_a(wdst1, ra);
     __syncthreads();
     compute(sA[1], b1);
 
-    // D: column = token i16 of tile tt, rows 4q..4q+3 of neuron tile (mt 0,1 = gate; 2,3 = up)
+    // D: column = token i16 of tile tt, rows 4q..4q+3 of a neuron tile (tiles 0..HT-1 gate, HT.. up)
 #pragma unroll
-    for (int tt = 0; tt < 4; ++tt) {
-        const int sl = c0 + wave * 64 + tt * 16 + i16;
+    for (int tt = 0; tt < TT; ++tt) {
+        const int sl = c0 + (wave * TT + tt) * 16 + i16;
         if (sl < cnt) {
 #pragma unroll
-            for (int mt = 0; mt < 2; ++mt) {
-                uint32_t lo = (uint32_t)f32_to_bf16(silu_mul(acc[mt][tt][0], acc[mt + 2][tt][0])) |
-                              ((uint32_t)f32_to_bf16(silu_mul(acc[mt][tt][1], acc[mt + 2][tt][1])) << 16);
-                uint32_t hi = (uint32_t)f32_to_bf16(silu_mul(acc[mt][tt][2], acc[mt + 2][tt][2])) |
-                              ((uint32_t)f32_to_bf16(silu_mul(acc[mt][tt][3], acc[mt + 2][tt][3])) << 16);
-                bf16_t *dst = act + ((size_t)g * T + sl) * gs + nt * 32 + mt * 16 + 4 * q;
+            for (int mt = 0; mt < HT; ++mt) {
+                uint32_t lo = (uint32_t)f32_to_bf16(silu_mul(acc[mt][tt][0], acc[mt + HT][tt][0])) |
+                              ((uint32_t)f32_to_bf16(silu_mul(acc[mt][tt][1], acc[mt + HT][tt][1])) << 16);
+                uint32_t hi = (uint32_t)f32_to_bf16(silu_mul(acc[mt][tt][2], acc[mt + HT][tt][2])) |
+                              ((uint32_t)f32_to_bf16(silu_mul(acc[mt][tt][3], acc[mt + HT][tt][3])) << 16);
+                bf16_t *dst = act + ((size_t)g * T + sl) * gs + nt * NB + mt * 16 + 4 * q;
                 *reinterpret_cast<uint2 *>(dst) = make_uint2(lo, hi);
             }
         }
@@ -183,49 +205,87 @@ __global__ __launch_bounds__(256) void gate_up_pf(
 }
 
 // ---------------------------------------------------------------------------
-// down: grid (d/64, ceil(T/128)), 256 threads; each wave 32 tokens x 64 outputs
+// down: grid (d/64, ceil(T/128)), 256 threads; each wave 32 tokens x 64 outputs; group size 128
 // ---------------------------------------------------------------------------
+struct DownFrags {
+    u32x4 a[4][4];      // [k step][output tile]
+    u32x4 b[4][2];      // [k step][token tile]
+};
+
 __global__ __launch_bounds__(256) void down_pf(
-    int T, int d, int G, int gs, const bf16_t *__restrict__ Wd, const int32_t *__restrict__ slot,
-    const int32_t *__restrict__ tok_cnt, const bf16_t *__restrict__ act, bf16_t *__restrict__ y)
+    int T, int d, int G, const bf16_t *__restrict__ Wd, const int32_t *__restrict__ slot,
+    const bf16_t *__restrict__ act, bf16_t *__restrict__ y)
 {
+    constexpr int gs = 128;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int i16 = lane & 15, q = lane >> 4;
     const int j0 = blockIdx.x * 64;
     const int t0 = blockIdx.y * 128 + wave * 32;
     if (t0 >= T) return;
-    int tok[2];
-#pragma unroll
-    for (int tt = 0; tt < 2; ++tt) {
-        const int t = t0 + tt * 16 + i16;
-        tok[tt] = t < T ? t : T - 1;                         // duplicate of a valid token, never stored
+    const int32_t *sl0, *sl1;
+    {
+        const int ta = t0 + i16, tb = t0 + 16 + i16;
+        sl0 = slot + (size_t)(ta < T ? ta : T - 1) * G;          // duplicates of a valid token, never stored
+        sl1 = slot + (size_t)(tb < T ? tb : T - 1) * G;
     }
     f32x4_t acc[4][2];
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt) acc[mt][tt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-    const int ksteps = gs / 32;
-    const u32x4 zero = {0u, 0u, 0u, 0u};
-    for (int g = 0; g < G; ++g) {
-        if (tok_cnt[g] == 0) continue;                       // uniform
-        const int s0 = slot[(size_t)tok[0] * G + g], s1 = slot[(size_t)tok[1] * G + g];
+    const bf16_t *wbase = Wd + (size_t)(j0 + i16) * gs + q * 8;
+    const size_t gstride = (size_t)d * gs;
+
+    // a token that does not keep the group gets a zero fragment: it contributes exactly nothing
+    auto fetch = [&](DownFrags &f, int g, int s0, int s1) {
+        const bf16_t *pa = wbase + g * gstride;
         const bf16_t *pb0 = act + ((size_t)g * T + (s0 < 0 ? 0 : s0)) * gs + q * 8;
         const bf16_t *pb1 = act + ((size_t)g * T + (s1 < 0 ? 0 : s1)) * gs + q * 8;
-        const bf16_t *pa = Wd + ((size_t)g * d + j0 + i16) * gs + q * 8;
-        for (int ks = 0; ks < ksteps; ++ks) {
-            u32x4 a[4];
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
 #pragma unroll
             for (int mt = 0; mt < 4; ++mt)
-                a[mt] = *reinterpret_cast<const u32x4 *>(pa + (size_t)mt * 16 * gs + ks * 32);
-            const u32x4 b0 = s0 < 0 ? zero : *reinterpret_cast<const u32x4 *>(pb0 + ks * 32);
-            const u32x4 b1 = s1 < 0 ? zero : *reinterpret_cast<const u32x4 *>(pb1 + ks * 32);
+                f.a[ks][mt] = *reinterpret_cast<const u32x4 *>(pa + (size_t)mt * 16 * gs + ks * 32);
+            const u32x4 v0 = *reinterpret_cast<const u32x4 *>(pb0 + ks * 32);
+            const u32x4 v1 = *reinterpret_cast<const u32x4 *>(pb1 + ks * 32);
+            f.b[ks][0] = s0 < 0 ? u32x4{0u, 0u, 0u, 0u} : v0;
+            f.b[ks][1] = s1 < 0 ? u32x4{0u, 0u, 0u, 0u} : v1;
+        }
+    };
+    auto multiply = [&](const DownFrags &f) {
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
             for (int mt = 0; mt < 4; ++mt) {
-                acc[mt][0] = mfma16p(a[mt], b0, acc[mt][0]);
-                acc[mt][1] = mfma16p(a[mt], b1, acc[mt][1]);
+                acc[mt][0] = mfma16p(f.a[ks][mt], f.b[ks][0], acc[mt][0]);
+                acc[mt][1] = mfma16p(f.a[ks][mt], f.b[ks][1], acc[mt][1]);
             }
-        }
+    };
+    // groups in pairs: the fragments of group g+1 are in flight while group g is multiplied,
+    // and the slots (which the fragment addresses depend on) are fetched one group further ahead
+    DownFrags F0, F1;
+    int s0 = sl0[0], s1 = sl1[0];
+    int n0 = G > 1 ? sl0[1] : -1, n1 = G > 1 ? sl1[1] : -1;
+    fetch(F0, 0, s0, s1);
+    int g = 0;
+    for (; g + 2 < G; g += 2) {
+        s0 = n0; s1 = n1;                       // slots of group g+1
+        n0 = sl0[g + 2]; n1 = sl1[g + 2];       // slots of group g+2
+        fetch(F1, g + 1, s0, s1);
+        multiply(F0);
+        s0 = n0; s1 = n1;
+        const int gn = g + 3 < G ? g + 3 : g + 2;
+        n0 = sl0[gn]; n1 = sl1[gn];             // slots of group g+3 (or a harmless repeat)
+        fetch(F0, g + 2, s0, s1);
+        multiply(F1);
+    }
+    // here F0 holds group g (g = G-1 or G-2) and (n0, n1) are the slots of group g+1 if it exists
+    if (g + 1 < G) {
+        fetch(F1, g + 1, n0, n1);
+        multiply(F0);
+        multiply(F1);
+    } else {
+        multiply(F0);
     }
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt) {
@@ -246,7 +306,7 @@ __global__ __launch_bounds__(256) void down_pf(
 // ---------------------------------------------------------------------------
 bool prefill_path_supported(int T, int d, int gs)
 {
-    return T > 1 && d % 128 == 0 && gs % 32 == 0;
+    return T > 1 && d % 128 == 0 && gs == 128;
 }
 
 hipError_t launch_ffn_prefill(const bf16_t *x, int T, int d, int G, int gs, const bf16_t *Wg,
@@ -255,9 +315,12 @@ hipError_t launch_ffn_prefill(const bf16_t *x, int T, int d, int G, int gs, cons
 {
     bf16_t *act = reinterpret_cast<bf16_t *>(ws.act);
     group_tokens_kernel<<<dim3(G), dim3(256), 0, s>>>(mask, T, G, ws.tok_list, ws.tok_cnt, ws.slot);
-    launch_timed("gate_up_pf", gate_up_pf, dim3(G * (gs / 32), (T + 255) / 256), dim3(256), s, x, T, d, gs, Wg,
-                 Wu, (const int32_t *)ws.tok_list, (const int32_t *)ws.tok_cnt, act);
-    down_pf<<<dim3(d / 64, (T + 127) / 128), dim3(256), 0, s>>>(T, d, G, gs, Wd, ws.slot, ws.tok_cnt, act, y);
+    // 128 tokens x 64 neurons per workgroup.  Measured on the 512-token LLaMA-7B shape: 32 neurons
+    // 169 us, 64 neurons 120 us, the whole group with 64 tokens 151 us.
+    constexpr int TT = 2, NB = 64;
+    launch_timed("gate_up_pf", gate_up_pf<TT, NB>, dim3(G * (gs / NB), (T + 64 * TT - 1) / (64 * TT)), dim3(256),
+                 s, x, T, d, gs, Wg, Wu, (const int32_t *)ws.tok_list, (const int32_t *)ws.tok_cnt, act);
+    down_pf<<<dim3(d / 64, (T + 127) / 128), dim3(256), 0, s>>>(T, d, G, Wd, ws.slot, act, y);
     return hipGetLastError();
 }
 

@@ -25,12 +25,88 @@ __global__ __launch_bounds__(256) void dot_rows_kernel(const XT *__restrict__ X,
     if (lane == 0) out[idx] = RELU ? (p > 0.0f ? p : 0.0f) : p;
 }
 
+// First layer for many tokens, bf16, d = NCH*512: a wave keeps JB rows of At in registers
+// (as floats) and sweeps a range of tokens, so At is read once per 64 tokens instead of once
+// per token.  Same arithmetic per (token, row) as dot_order64: lane l owns the 8-element
+// pieces l, l+64, ... in increasing order, one fused-multiply-add chain from +0, butterfly.
+constexpr int kPredTokens = 64;     // tokens per workgroup
+
+template <int NCH, int JB>
+__global__ __launch_bounds__(256) void hidden_rows_kernel(const bf16_t *__restrict__ X,
+                                                          const bf16_t *__restrict__ At,
+                                                          float *__restrict__ h, int T, int r)
+{
+    constexpr int d = NCH * 512;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int j0 = (blockIdx.x * 4 + wave) * JB;
+    if (j0 >= r) return;
+    float wr[JB][NCH][8];
+#pragma unroll
+    for (int b = 0; b < JB; ++b) {
+        const int j = j0 + b < r ? j0 + b : r - 1;
+#pragma unroll
+        for (int k = 0; k < NCH; ++k) load8(At + (size_t)j * d + (k * kWave + lane) * 8, wr[b][k]);
+    }
+    const int t0 = blockIdx.y * kPredTokens, t1 = min(T, t0 + kPredTokens);
+    for (int t = t0; t < t1; ++t) {
+        u32x4 xv[NCH];
+#pragma unroll
+        for (int k = 0; k < NCH; ++k)
+            xv[k] = *reinterpret_cast<const u32x4 *>(X + (size_t)t * d + (k * kWave + lane) * 8);
+        float p[JB];
+#pragma unroll
+        for (int b = 0; b < JB; ++b) p[b] = 0.0f;
+#pragma unroll
+        for (int k = 0; k < NCH; ++k) {
+            float xf[8];
+            unpack8(xv[k], xf);
+#pragma unroll
+            for (int b = 0; b < JB; ++b)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) p[b] = __builtin_fmaf(xf[e], wr[b][k][e], p[b]);
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            float qv[JB];
+#pragma unroll
+            for (int b = 0; b < JB; ++b) qv[b] = __shfl_xor(p[b], off, kWave);
+#pragma unroll
+            for (int b = 0; b < JB; ++b) p[b] = p[b] + qv[b];
+        }
+        if (lane == 0) {
+#pragma unroll
+            for (int b = 0; b < JB; ++b)
+                if (j0 + b < r) h[(size_t)t * r + j0 + b] = p[b] > 0.0f ? p[b] : 0.0f;
+        }
+    }
+}
+
+template <int NCH, int JB>
+static void launch_hidden_rows(const bf16_t *x, int T, int r, const bf16_t *At, float *h, hipStream_t s)
+{
+    hidden_rows_kernel<NCH, JB><<<dim3((r + 4 * JB - 1) / (4 * JB), (T + kPredTokens - 1) / kPredTokens),
+                                 dim3(256), 0, s>>>(x, At, h, T, r);
+}
+
+static bool hidden_rows_tiled(const bf16_t *x, int T, int d, int r, const bf16_t *At, float *h, hipStream_t s)
+{
+    if (T < 16) return false;
+    switch (d) {
+    case 4096: launch_hidden_rows<8, 2>(x, T, r, At, h, s); return true;
+    case 5120: launch_hidden_rows<10, 2>(x, T, r, At, h, s); return true;
+    case 8192: launch_hidden_rows<16, 1>(x, T, r, At, h, s); return true;
+    default: return false;
+    }
+}
+static bool hidden_rows_tiled(const float *, int, int, int, const float *, float *, hipStream_t) { return false; }
+
 template <typename WT>
 static hipError_t predict_t(const WT *x, int T, int d, int r, int G, const WT *At, const WT *Bt,
                             float *h, float *scores, hipStream_t s)
 {
     long long n1 = (long long)T * r, n2 = (long long)T * G;
-    dot_rows_kernel<WT, WT, true><<<dim3((unsigned)((n1 + 3) / 4)), dim3(256), 0, s>>>(x, At, h, T, r, d);
+    if (!hidden_rows_tiled(x, T, d, r, At, h, s))
+        dot_rows_kernel<WT, WT, true><<<dim3((unsigned)((n1 + 3) / 4)), dim3(256), 0, s>>>(x, At, h, T, r, d);
     if (scores)
         dot_rows_kernel<float, WT, false><<<dim3((unsigned)((n2 + 3) / 4)), dim3(256), 0, s>>>(h, Bt, scores, T, G, r);
     return hipGetLastError();

@@ -17,6 +17,8 @@ struct Timer {
     bool active = false;
     std::vector<hipEvent_t> start, stop;
     size_t used = 0;
+    int every = 1;          // time one launch in `every`
+    long long seen = 0;     // eligible launches since begin
     std::string name;
 } g_timer;
 }  // namespace
@@ -26,6 +28,7 @@ bool timer_acquire(hipEvent_t *start, hipEvent_t *stop)
     if (!g_timer.active) return false;
     std::lock_guard<std::mutex> lk(g_timer.mu);
     if (!g_timer.active || g_timer.used >= g_timer.start.size()) return false;
+    if (g_timer.seen++ % g_timer.every != 0) return false;
     *start = g_timer.start[g_timer.used];
     *stop = g_timer.stop[g_timer.used];
     return true;
@@ -43,10 +46,10 @@ void timer_commit(const char *kernel_name)
 
 extern "C" {
 
-int halo_profile_begin(int32_t max_launches)
+int halo_profile_begin(int32_t max_launches, int32_t every)
 {
     using namespace halo;
-    if (max_launches < 1 || max_launches > (1 << 20)) return HALO_ERR_ARG;
+    if (max_launches < 1 || max_launches > (1 << 20) || every < 1) return HALO_ERR_ARG;
     std::lock_guard<std::mutex> lk(g_timer.mu);
     if (g_timer.active) return HALO_ERR_ARG;
     g_timer.start.assign((size_t)max_launches, nullptr);
@@ -56,6 +59,8 @@ int halo_profile_begin(int32_t max_launches)
             return HALO_ERR_HIP;
     }
     g_timer.used = 0;
+    g_timer.every = every;
+    g_timer.seen = 0;
     g_timer.name.clear();
     g_timer.active = true;
     return HALO_OK;

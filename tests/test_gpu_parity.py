@@ -328,6 +328,10 @@ def test_llama7b_prefill_sampled_tokens():
     (40, 512, 7, 64, False),
     (300, 256, 6, 64, True),      # a group kept by more than 256 tokens: two token chunks
     (129, 384, 4, 40, False),     # ragged 128-token output tile; d multiple of 128 only
+    (20, 5120, 3, 256, False),    # register-tiled predictor, 13B row length
+    (18, 8192, 3, 512, False),    # register-tiled predictor, 70B row length
+    (33, 256, 1, 64, True),       # a single group
+    (70, 256, 2, 64, False),
 ])
 def test_many_tokens_matrix_core_path_all_tokens(T, d, G, r, keepall):
     w = dataclasses.replace(hs.LLAMA7B_PREFILL, name="case", d=d, ffn=G * 128, rank=r, T=T, seed=23)
