@@ -346,3 +346,75 @@ def test_many_tokens_matrix_core_path_all_tokens(T, d, G, r, keepall):
     g = hz.gpu_forward(w, L, x, K, pd, drop)
     c = hz.oracle_forward(w, L, x, K, pd, drop)
     hz.assert_parity(g, c, TOL["bf16"], "many tokens")
+
+
+def test_edge_cases_through_the_boundary():
+    _say("edge cases: T=0, K=0, K=G at the fast path's group limit, G=1024")
+    # T == 0 is a no-op that touches nothing
+    w = dataclasses.replace(hs.LLAMA7B_DECODE, name="case", ffn=4 * 128, seed=40)
+    s = hz.shape_of(w)
+    L = hz.Layer(w)
+    ws = torch.empty(H.halo_workspace_bytes(s, 1, 4), dtype=torch.uint8, device=hz.DEV)
+    x0 = torch.empty((0, w.d), dtype=torch.bfloat16, device=hz.DEV)
+    y0 = torch.empty((0, w.d), dtype=torch.bfloat16, device=hz.DEV)
+    m0 = torch.empty((0, 4), dtype=torch.uint8, device=hz.DEV)
+    H.halo_group_sparse_ffn(s, x0, L.Wg, L.Wu, L.Wd, m0, y0, ws)
+    # K == 0: nothing is executed, y is exactly zero
+    x = hs.hidden_states(w, 0, hz.DEV)
+    g = hz.gpu_forward(w, L, x, 0, np.zeros(0, np.int8), None)
+    assert not g["mask"].any() and not g["y"].any() and (g["n_surv"] == 0).all()
+    # one token, 256 groups (the fast path's limit), everything kept
+    w2 = dataclasses.replace(hs.LLAMA7B_DECODE, name="case", ffn=256 * 128, seed=41)
+    L2 = hz.Layer(w2)
+    x2 = hs.hidden_states(w2, 0, hz.DEV)
+    pd = H.halo_build_schedule(256, w2.device_plr())
+    g = hz.gpu_forward(w2, L2, x2, 256, pd, None)
+    c = hz.oracle_forward(w2, L2, x2, 256, pd, None)
+    hz.assert_parity(g, c, TOL["bf16"], "G=256 dense")
+    # 1024 groups (the interface's limit) at a small d: generic kernels, 3 tokens
+    w3 = dataclasses.replace(hs.TINY, name="case", d=64, ffn=1024 * 8, group_size=8, rank=16, T=3, seed=42)
+    L3 = hz.Layer(w3)
+    x3 = hs.hidden_states(w3, 0, hz.DEV)
+    pd = H.halo_build_schedule(300, w3.device_plr())
+    drop = hs.drop_outcomes(w3, T=3)
+    g = hz.gpu_forward(w3, L3, x3, 300, pd, drop)
+    c = hz.oracle_forward(w3, L3, x3, 300, pd, drop)
+    hz.assert_parity(g, c, TOL["f32"], "G=1024")
+
+
+def test_run_to_run_determinism_and_graph_replay_of_the_serial_pass():
+    w = hs.LLAMA7B_DECODE
+    _say("determinism + graph replay, 7B decode")
+    s = hz.shape_of(w)
+    L = hz.Layer(w)
+    K = w.k_keep()
+    pd = torch.from_numpy(H.halo_build_schedule(K, w.device_plr())).to(hz.DEV)
+    ws = torch.empty(H.halo_workspace_bytes(s, 1, K), dtype=torch.uint8, device=hz.DEV)
+    xs = [hs.hidden_states(w, i, hz.DEV) for i in range(4)]
+    dr = [torch.from_numpy(hs.drop_outcomes(w, 0, i)).to(hz.DEV) for i in range(4)]
+    ys = torch.zeros((4, 1, w.d), dtype=torch.bfloat16, device=hz.DEV)
+    ms = torch.zeros((4, 1, w.n_groups), dtype=torch.uint8, device=hz.DEV)
+
+    def run(out_y, out_m):
+        for i in range(4):
+            H.halo_ffn_forward(s, xs[i], L.At, L.Bt, L.Wg, L.Wu, L.Wd, K, pd, w.n_dev, dr[i], out_y[i], ws,
+                               mask=out_m[i])
+    run(ys, ms)
+    torch.cuda.synchronize()
+    y2, m2 = torch.zeros_like(ys), torch.zeros_like(ms)
+    run(y2, m2)
+    torch.cuda.synchronize()
+    assert torch.equal(ys, y2) and torch.equal(ms, m2)
+    st = torch.cuda.Stream()
+    y3, m3 = torch.zeros_like(ys), torch.zeros_like(ms)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=st):
+        with torch.cuda.stream(st):
+            run(y3, m3)
+    for _ in range(3):
+        y3.zero_()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(st):
+            g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(ys, y3) and torch.equal(ms, m3)
