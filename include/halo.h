@@ -81,6 +81,27 @@ int halo_build_schedule(int32_t n_prio, int32_t n_dev, const double *ratios,
                         const double *plr, int8_t *prio_dev);
 
 /*
+ * Workload ratios from device memory budgets and computing power: the first step of the
+ * paper's load-balancing scheduler, whose output feeds halo_build_schedule.  HOST
+ * pointers, no GPU work.  mem[i] >= 0 and comp[i] > 0 are device i's memory budget and
+ * computing power, demand > 0 is the model's total memory demand M_t (same unit as mem);
+ * ratios[n_dev] (out) is non-negative and sums to 1.
+ *   halo_ratios_comp_greedy  paper Alg. 1: devices in descending computing power (ties: lower
+ *                            index first) are filled to their budget until the demand is
+ *                            covered; the last one used takes only the remainder.
+ *   halo_ratios_min_max      paper Alg. 2: bisection, until the interval is no wider than eps
+ *                            (the paper uses 1e-3), on the threshold T over [0, max(mem)/min(comp)]
+ *                            for the smallest T with sum_i min(mem_i, T*comp_i) >= demand; device i
+ *                            gets min(mem_i, T*comp_i), normalised.
+ * Errors: HALO_ERR_NULL; HALO_ERR_ARG (n_dev outside 1..127, NaN, negative budget, non-positive
+ * computing power / demand / eps, or total budget below the demand -- the algorithms' assertion).
+ */
+int halo_ratios_comp_greedy(int32_t n_dev, const double *mem, const double *comp, double demand,
+                            double *ratios);
+int halo_ratios_min_max(int32_t n_dev, const double *mem, const double *comp, double demand, double eps,
+                        double *ratios);
+
+/*
  * Upper bound, in bytes, of the scratch any entry point below needs for T tokens
  * of this shape with k_keep groups kept per token.  Returns 0 for invalid arguments.
  */

@@ -14,6 +14,9 @@
  *
  *   halo_ref_schedule          Alg. 3 (PLR-aware ratio-guided scheduler) and the
  *                              worked example of Sec. III-B.4.
+ *   halo_ref_ratios_comp_greedy / halo_ref_ratios_min_max
+ *                              Alg. 1 and Alg. 2: workload ratios from memory budgets and
+ *                              computing power (the first step of the scheduler).
  *   halo_ref_predict_scores    Sec. III-B.2 (semantic-aware predictor): a
  *                              two-matrix network D -> hidden -> N_g, one
  *                              significance value per neuron group.
@@ -102,6 +105,82 @@ int halo_ref_schedule(int32_t n_prio, int32_t n_dev, const double *ratios,
         for (int64_t p = lo; p < hi; ++p) prio_dev[p] = (int8_t)q[k];
         lo = hi;
     }
+    return REF_OK;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Alg. 1: computation-greedy scheduler.  Devices are filled to their memory  */
+/* budget in descending order of computing power (ties: lower index first)    */
+/* until the model's demand M_t is covered; the last device used takes only   */
+/* the remainder; ratios are the allocations over their sum.                  */
+/* ------------------------------------------------------------------------- */
+int halo_ref_ratios_comp_greedy(int32_t n, const double *m, const double *c, double Mt, double *r)
+{
+    if (n < 1 || n > 127 || !m || !c || !r || !(Mt > 0.0)) return REF_ERR;
+    int sig[128];
+    double total = 0.0;
+    for (int i = 0; i < n; ++i) {
+        if (!(m[i] >= 0.0) || !(c[i] > 0.0)) return REF_ERR;
+        total += m[i];
+        sig[i] = i;
+    }
+    if (total < Mt) return REF_ERR;                      /* the assertion of the algorithm */
+    for (int i = 1; i < n; ++i) {                        /* stable insertion sort, c descending */
+        int v = sig[i], j = i - 1;
+        while (j >= 0 && c[sig[j]] < c[v]) { sig[j + 1] = sig[j]; --j; }
+        sig[j + 1] = v;
+    }
+    double u[128];
+    for (int i = 0; i < n; ++i) u[i] = 0.0;
+    double filled = 0.0;
+    for (int k = 0; k < n; ++k) {
+        int dev = sig[k];
+        if (filled + m[dev] >= Mt) {                     /* k is the minimum number of devices */
+            u[dev] = Mt - filled;
+            break;
+        }
+        u[dev] = m[dev];
+        filled += m[dev];
+    }
+    double sum = 0.0;
+    for (int i = 0; i < n; ++i) sum += u[i];
+    for (int i = 0; i < n; ++i) r[i] = u[i] / sum;
+    return REF_OK;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Alg. 2: min-max scheduler.  Bisection (until right - left <= eps) on the    */
+/* utilisation threshold T over [0, max(m)/min(c)]: the smallest T found with */
+/* sum_i min(m_i, T c_i) >= M_t; allocation u_i = min(m_i, T c_i), normalised.*/
+/* ------------------------------------------------------------------------- */
+int halo_ref_ratios_min_max(int32_t n, const double *m, const double *c, double Mt, double eps, double *r)
+{
+    if (n < 1 || n > 127 || !m || !c || !r || !(Mt > 0.0) || !(eps > 0.0)) return REF_ERR;
+    double total = 0.0, mmax = 0.0, cmin = 0.0;
+    for (int i = 0; i < n; ++i) {
+        if (!(m[i] >= 0.0) || !(c[i] > 0.0)) return REF_ERR;
+        total += m[i];
+        if (i == 0 || m[i] > mmax) mmax = m[i];
+        if (i == 0 || c[i] < cmin) cmin = c[i];
+    }
+    if (total < Mt) return REF_ERR;
+    double left = 0.0, right = mmax / cmin, topt = right;
+    while (right - left > eps) {
+        double mid = (left + right) / 2.0;
+        double used = 0.0;
+        for (int i = 0; i < n; ++i) {
+            double cap = mid * c[i];
+            used += m[i] < cap ? m[i] : cap;
+        }
+        if (used >= Mt) { topt = mid; right = mid; } else { left = mid; }
+    }
+    double sum = 0.0, u[128];
+    for (int i = 0; i < n; ++i) {
+        double cap = topt * c[i];
+        u[i] = m[i] < cap ? m[i] : cap;
+        sum += u[i];
+    }
+    for (int i = 0; i < n; ++i) r[i] = u[i] / sum;
     return REF_OK;
 }
 

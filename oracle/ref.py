@@ -50,6 +50,28 @@ def schedule(n_prio: int, plr, ratios=None) -> np.ndarray:
     return out
 
 
+def _ratios(fn_name, m, c, Mt, *extra):
+    m = np.ascontiguousarray(np.asarray(m, dtype=np.float64))
+    c = np.ascontiguousarray(np.asarray(c, dtype=np.float64))
+    assert m.shape == c.shape
+    r = np.full(m.shape, np.nan)
+    rc = getattr(lib(), fn_name)(C.c_int32(len(m)), _p(m, C.c_double), _p(c, C.c_double), C.c_double(Mt),
+                                 *[C.c_double(e) for e in extra], _p(r, C.c_double))
+    if rc != 0:
+        raise ValueError(fn_name + " rejected its arguments")
+    return r
+
+
+def ratios_comp_greedy(m, c, Mt) -> np.ndarray:
+    """Alg. 1: workload ratios, fastest devices filled first."""
+    return _ratios("halo_ref_ratios_comp_greedy", m, c, Mt)
+
+
+def ratios_min_max(m, c, Mt, eps: float = 1e-3) -> np.ndarray:
+    """Alg. 2: workload ratios minimising the largest per-device time."""
+    return _ratios("halo_ref_ratios_min_max", m, c, Mt, eps)
+
+
 def predict_scores(x, At, Bt, want64: bool = False):
     x, At, Bt = _f32(x), _f32(At), _f32(Bt)
     T, d = x.shape

@@ -62,6 +62,10 @@ def load_library():
     lib.halo_status_string.argtypes = [C.c_int]
     lib.halo_build_schedule.restype = C.c_int
     lib.halo_build_schedule.argtypes = [i32, i32, vp, vp, vp]
+    lib.halo_ratios_comp_greedy.restype = C.c_int
+    lib.halo_ratios_comp_greedy.argtypes = [i32, vp, vp, C.c_double, vp]
+    lib.halo_ratios_min_max.restype = C.c_int
+    lib.halo_ratios_min_max.argtypes = [i32, vp, vp, C.c_double, C.c_double, vp]
     lib.halo_workspace_bytes.restype = sz
     lib.halo_workspace_bytes.argtypes = [ps, i32, i32]
     lib.halo_predict_scores.restype = C.c_int
@@ -126,6 +130,29 @@ def halo_build_schedule(n_prio: int, plr: Sequence[float],
         plr_a.ctypes.data_as(C.c_void_p), out.ctypes.data_as(C.c_void_p))
     _check("halo_build_schedule", rc)
     return out
+
+
+def _host_ratios(name, mem, comp, demand, *extra) -> np.ndarray:
+    m = np.ascontiguousarray(np.asarray(mem, dtype=np.float64))
+    c = np.ascontiguousarray(np.asarray(comp, dtype=np.float64))
+    if m.shape != c.shape or m.ndim != 1:
+        raise ValueError("mem and comp must have one entry per device")
+    r = np.zeros_like(m)
+    rc = getattr(load_library(), name)(int(m.shape[0]), m.ctypes.data_as(C.c_void_p),
+                                       c.ctypes.data_as(C.c_void_p), float(demand), *extra,
+                                       r.ctypes.data_as(C.c_void_p))
+    _check(name, rc)
+    return r
+
+
+def halo_ratios_comp_greedy(mem, comp, demand: float) -> np.ndarray:
+    """Host-only (Alg. 1)."""
+    return _host_ratios("halo_ratios_comp_greedy", mem, comp, demand)
+
+
+def halo_ratios_min_max(mem, comp, demand: float, eps: float = 1e-3) -> np.ndarray:
+    """Host-only (Alg. 2)."""
+    return _host_ratios("halo_ratios_min_max", mem, comp, demand, float(eps))
 
 
 def halo_workspace_bytes(shape: Shape, T: int, k_keep: int) -> int:

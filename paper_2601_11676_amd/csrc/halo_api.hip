@@ -121,6 +121,79 @@ int halo_build_schedule(int32_t n_prio, int32_t n_dev, const double *ratios, con
     return HALO_OK;
 }
 
+int halo_ratios_comp_greedy(int32_t n_dev, const double *mem, const double *comp, double demand,
+                            double *ratios)
+{
+    if (!mem || !comp || !ratios) return HALO_ERR_NULL;
+    if (n_dev < 1 || n_dev > 127 || !(demand > 0.0)) return HALO_ERR_ARG;
+    double budget = 0.0;
+    for (int i = 0; i < n_dev; ++i) {
+        if (std::isnan(mem[i]) || mem[i] < 0.0 || std::isnan(comp[i]) || comp[i] <= 0.0) return HALO_ERR_ARG;
+        budget += mem[i];
+    }
+    if (budget < demand) return HALO_ERR_ARG;
+    // fastest first; equal computing power keeps the lower device index first
+    int by_speed[127];
+    for (int i = 0; i < n_dev; ++i) {
+        int pos = 0;
+        for (int j = 0; j < n_dev; ++j)
+            if (comp[j] > comp[i] || (comp[j] == comp[i] && j < i)) ++pos;
+        by_speed[pos] = i;
+    }
+    for (int i = 0; i < n_dev; ++i) ratios[i] = 0.0;
+    double placed = 0.0;
+    for (int k = 0; k < n_dev; ++k) {
+        const int dev = by_speed[k];
+        if (placed + mem[dev] >= demand) {      // this device completes the demand: it takes the rest
+            ratios[dev] = demand - placed;
+            break;
+        }
+        ratios[dev] = mem[dev];
+        placed += mem[dev];
+    }
+    double sum = 0.0;
+    for (int i = 0; i < n_dev; ++i) sum += ratios[i];
+    for (int i = 0; i < n_dev; ++i) ratios[i] /= sum;
+    return HALO_OK;
+}
+
+int halo_ratios_min_max(int32_t n_dev, const double *mem, const double *comp, double demand, double eps,
+                        double *ratios)
+{
+    if (!mem || !comp || !ratios) return HALO_ERR_NULL;
+    if (n_dev < 1 || n_dev > 127 || !(demand > 0.0) || !(eps > 0.0)) return HALO_ERR_ARG;
+    double budget = 0.0, mem_max = 0.0, comp_min = 0.0;
+    for (int i = 0; i < n_dev; ++i) {
+        if (std::isnan(mem[i]) || mem[i] < 0.0 || std::isnan(comp[i]) || comp[i] <= 0.0) return HALO_ERR_ARG;
+        budget += mem[i];
+        mem_max = i == 0 ? mem[i] : std::fmax(mem_max, mem[i]);
+        comp_min = i == 0 ? comp[i] : std::fmin(comp_min, comp[i]);
+    }
+    if (budget < demand) return HALO_ERR_ARG;
+    auto covered = [&](double threshold) {
+        double used = 0.0;
+        for (int i = 0; i < n_dev; ++i) used += std::fmin(mem[i], threshold * comp[i]);
+        return used;
+    };
+    double lo = 0.0, hi = mem_max / comp_min, best = hi;
+    while (hi - lo > eps) {
+        const double mid = (lo + hi) / 2.0;
+        if (covered(mid) >= demand) {
+            best = mid;
+            hi = mid;
+        } else {
+            lo = mid;
+        }
+    }
+    double sum = 0.0;
+    for (int i = 0; i < n_dev; ++i) {
+        ratios[i] = std::fmin(mem[i], best * comp[i]);
+        sum += ratios[i];
+    }
+    for (int i = 0; i < n_dev; ++i) ratios[i] /= sum;
+    return HALO_OK;
+}
+
 size_t halo_workspace_bytes(const halo_shape *shape, int32_t T, int32_t k_keep)
 {
     if (check_shape(shape) != HALO_OK || T < 0 || k_keep < 0 || k_keep > shape->n_groups) return 0;
