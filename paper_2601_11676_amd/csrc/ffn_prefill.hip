@@ -14,8 +14,9 @@
 //                  once more from cache per further 128 tokens.
 //                  act[g][slot][m] = SiLU(gate) * up in bf16.
 //   down_pf      : output-stationary: one workgroup = 128 tokens x 64 outputs, walking all
-//                  groups; a token that does not keep a group feeds zeros, so it contributes
-//                  exactly nothing, and every y element has exactly one writer (no atomics).
+//                  groups (Wd tiles through LDS, activation rows gathered into registers); a
+//                  token that does not keep a group feeds zeros, so it contributes exactly
+//                  nothing, and every y element has exactly one writer (no atomics).
 //
 // v_mfma_f32_16x16x32_bf16 operand layout as in ffn_mfma.hip: A lane l = row l%16, elements
 // 8*(l/16)..+7; B lane l = column l%16, same elements; D lane l = column l%16, rows 4*(l/16)..+3.
@@ -66,12 +67,13 @@ __global__ __launch_bounds__(256) void group_tokens_kernel(const uint8_t *__rest
 // ---------------------------------------------------------------------------
 // gate/up: grid (G * gs/NB, ceil(T/128)), 256 threads
 // ---------------------------------------------------------------------------
-constexpr int kKS = 64;             // K elements per LDS stage
-constexpr int kARow = kKS + 8;      // padded LDS row (elements): 144 bytes, conflict-free 16-byte reads
+constexpr int kKS = 64;             // K elements per LDS stage (32 and 128 measured slower)
+constexpr int kARow = kKS + 8;      // padded LDS row (elements): rows start 16 bytes apart in bank space
+constexpr int kKH = kKS / 32;       // matrix-instruction K steps per stage
 
 template <int TT>
 struct BFrags {
-    u32x4 v[2][TT];                 // [k half of the stage][token tile]
+    u32x4 v[kKH][TT];               // [k step of the stage][token tile]
 };
 
 // TT = 16-token tiles per wave (a workgroup covers 4 * TT * 16 tokens of the group's list);
@@ -85,7 +87,8 @@ __global__ __launch_bounds__(256) void gate_up_pf(
     const int32_t *__restrict__ tok_cnt, bf16_t *__restrict__ act)
 {
     constexpr int HT = NB / 16;                              // 16-row tiles per matrix
-    constexpr int NP = NB / 32;                              // staging passes per matrix
+    constexpr int RPP = 256 / (kKS / 8);                     // rows staged per pass (16 threads per row)
+    constexpr int NP = NB / RPP;                             // staging passes per matrix
     __shared__ __attribute__((aligned(16))) bf16_t sA[2][2 * NB * kARow];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int i16 = lane & 15, q = lane >> 4;
@@ -104,9 +107,9 @@ __global__ __launch_bounds__(256) void gate_up_pf(
         sl = sl < cnt ? sl : cnt - 1;                        // past the end: a valid duplicate, never stored
         xrow[tt] = x + (size_t)list[sl] * d + q * 8;
     }
-    // staging role of this thread: eight threads share a row's 128-byte segment; per pass the
-    // thread takes gate row sr + 32*p and up row sr + 32*p (LDS rows r and NB + r), piece sp
-    const int sr = tid >> 3, sp = tid & 7;
+    // staging role of this thread: sixteen threads share a row's 256-byte segment; per pass the
+    // thread takes gate row sr + RPP*p and up row sr + RPP*p (LDS rows r and NB + r), piece sp
+    const int sr = tid / (kKS / 8), sp = tid % (kKS / 8);
     const size_t neuron0 = (size_t)g * gs + nt * NB;
     const bf16_t *wsrc_g = Wg + (neuron0 + sr) * d + sp * 8;
     const bf16_t *wsrc_u = Wu + (neuron0 + sr) * d + sp * 8;
@@ -124,27 +127,27 @@ __global__ __launch_bounds__(256) void gate_up_pf(
     auto load_a = [&](int k0, AStage &r) {
 #pragma unroll
         for (int p = 0; p < NP; ++p) {
-            r.g[p] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(wsrc_g + (size_t)p * 32 * d + k0));
-            r.u[p] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(wsrc_u + (size_t)p * 32 * d + k0));
+            r.g[p] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(wsrc_g + (size_t)p * RPP * d + k0));
+            r.u[p] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(wsrc_u + (size_t)p * RPP * d + k0));
         }
     };
     auto store_a = [&](bf16_t *buf, const AStage &r) {
 #pragma unroll
         for (int p = 0; p < NP; ++p) {
-            *reinterpret_cast<u32x4 *>(buf + dst_off + p * 32 * kARow) = r.g[p];
-            *reinterpret_cast<u32x4 *>(buf + dst_off + (NB + p * 32) * kARow) = r.u[p];
+            *reinterpret_cast<u32x4 *>(buf + dst_off + p * RPP * kARow) = r.g[p];
+            *reinterpret_cast<u32x4 *>(buf + dst_off + (NB + p * RPP) * kARow) = r.u[p];
         }
     };
     auto load_b = [&](int k0, BFrags<TT> &b) {
 #pragma unroll
-        for (int kh = 0; kh < 2; ++kh)
+        for (int kh = 0; kh < kKH; ++kh)
 #pragma unroll
             for (int tt = 0; tt < TT; ++tt)
                 b.v[kh][tt] = *reinterpret_cast<const u32x4 *>(xrow[tt] + k0 + kh * 32);
     };
     auto compute = [&](const bf16_t *a_lds, const BFrags<TT> &b) {
 #pragma unroll
-        for (int kh = 0; kh < 2; ++kh) {
+        for (int kh = 0; kh < kKH; ++kh) {
             u32x4 a[2 * HT];
 #pragma unroll
             for (int mt = 0; mt < 2 * HT; ++mt)
@@ -158,7 +161,7 @@ __global__ __launch_bounds__(256) void gate_up_pf(
 
     // software pipeline over K: while stage s is multiplied, stage s+1's weights travel
     // global -> registers -> the other LDS buffer and its x fragments travel to registers
-    const int nstage = d / kKS;                 // even (d % 128 == 0)
+    const int nstage = d / kKS;                 // d % 128 == 0; any count >= 1
     AStage ra;
     BFrags<TT> b0, b1;
     bf16_t *wdst0 = sA[0], *wdst1 = sA[1];
@@ -179,12 +182,16 @@ __global__ __launch_bounds__(256) void gate_up_pf(
         store_a(wdst0, ra);
         __syncthreads();
     }
-    load_a((s + 1) * kKS, ra);
-    load_b((s + 1) * kKS, b1);
-    compute(sA[0], b0);
-    store_a(wdst1, ra);
-    __syncthreads();
-    compute(sA[1], b1);
+    if (s + 1 < nstage) {                       // two stages left
+        load_a((s + 1) * kKS, ra);
+        load_b((s + 1) * kKS, b1);
+        compute(sA[0], b0);
+        store_a(wdst1, ra);
+        __syncthreads();
+        compute(sA[1], b1);
+    } else {                                    // one stage left
+        compute(sA[0], b0);
+    }
 
     // D: column = token i16 of tile tt, rows 4q..4q+3 of a neuron tile (tiles 0..HT-1 gate, HT.. up)
 #pragma unroll
@@ -205,11 +212,18 @@ __global__ __launch_bounds__(256) void gate_up_pf(
 }
 
 // ---------------------------------------------------------------------------
-// down: grid (d/64, ceil(T/128)), 256 threads; each wave 32 tokens x 64 outputs; group size 128
+// down: grid (d/64, ceil(T/128)), 256 threads; group size 128
 // ---------------------------------------------------------------------------
-struct DownFrags {
-    u32x4 a[4][4];      // [k step][output tile]
-    u32x4 b[4][2];      // [k step][token tile]
+// A workgroup owns 128 tokens x 64 outputs and walks the groups.  The group's 64 x 128 tile of
+// Wd is 16 KiB of consecutive bytes: it is fetched once per workgroup with coalesced loads,
+// staged through LDS and shared by the four waves (each wave loading its own operand pieces
+// cost four times the L1 traffic and ran at 8 % of the matrix peak).  The activation rows are
+// private to a wave (its 32 tokens), gathered by slot straight into registers; a token that
+// does not keep the group gets a zero fragment and so contributes exactly nothing.
+constexpr int kWdRow = 128 + 8;     // padded LDS row of the Wd tile, elements
+
+struct ActFrags {
+    u32x4 b[4][2];                  // [k step][token tile]
 };
 
 __global__ __launch_bounds__(256) void down_pf(
@@ -217,11 +231,12 @@ __global__ __launch_bounds__(256) void down_pf(
     const bf16_t *__restrict__ act, bf16_t *__restrict__ y)
 {
     constexpr int gs = 128;
+    __shared__ __attribute__((aligned(16))) bf16_t sWd[2][64 * kWdRow];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int i16 = lane & 15, q = lane >> 4;
     const int j0 = blockIdx.x * 64;
-    const int t0 = blockIdx.y * 128 + wave * 32;
-    if (t0 >= T) return;
+    const int t0 = blockIdx.y * 128 + wave * 32;       // may be >= T for the last workgroup's upper waves:
+                                                        // those waves still stage Wd and meet the barriers
     const int32_t *sl0, *sl1;
     {
         const int ta = t0 + i16, tb = t0 + 16 + i16;
@@ -233,59 +248,88 @@ __global__ __launch_bounds__(256) void down_pf(
     for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt) acc[mt][tt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-    const bf16_t *wbase = Wd + (size_t)(j0 + i16) * gs + q * 8;
     const size_t gstride = (size_t)d * gs;
-
-    // a token that does not keep the group gets a zero fragment: it contributes exactly nothing
-    auto fetch = [&](DownFrags &f, int g, int s0, int s1) {
-        const bf16_t *pa = wbase + g * gstride;
+    // staging role: the tile is 1024 pieces of 16 bytes; this thread moves pieces tid + 256 n
+    const bf16_t *wsrc = Wd + (size_t)j0 * gs + tid * 8;
+    int wdst[4];
+#pragma unroll
+    for (int n = 0; n < 4; ++n) {
+        const int p = tid + 256 * n;
+        wdst[n] = (p >> 4) * kWdRow + (p & 15) * 8;
+    }
+    auto load_w = [&](u32x4 (&r)[4], int g) {
+#pragma unroll
+        for (int n = 0; n < 4; ++n)
+            r[n] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(wsrc + g * gstride + n * 2048));
+    };
+    auto store_w = [&](bf16_t *buf, const u32x4 (&r)[4]) {
+#pragma unroll
+        for (int n = 0; n < 4; ++n) *reinterpret_cast<u32x4 *>(buf + wdst[n]) = r[n];
+    };
+    auto load_act = [&](ActFrags &f, int g, int s0, int s1) {
         const bf16_t *pb0 = act + ((size_t)g * T + (s0 < 0 ? 0 : s0)) * gs + q * 8;
         const bf16_t *pb1 = act + ((size_t)g * T + (s1 < 0 ? 0 : s1)) * gs + q * 8;
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
-#pragma unroll
-            for (int mt = 0; mt < 4; ++mt)
-                f.a[ks][mt] = *reinterpret_cast<const u32x4 *>(pa + (size_t)mt * 16 * gs + ks * 32);
             const u32x4 v0 = *reinterpret_cast<const u32x4 *>(pb0 + ks * 32);
             const u32x4 v1 = *reinterpret_cast<const u32x4 *>(pb1 + ks * 32);
             f.b[ks][0] = s0 < 0 ? u32x4{0u, 0u, 0u, 0u} : v0;
             f.b[ks][1] = s1 < 0 ? u32x4{0u, 0u, 0u, 0u} : v1;
         }
     };
-    auto multiply = [&](const DownFrags &f) {
+    auto multiply = [&](const bf16_t *buf, const ActFrags &f) {
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks)
+        for (int ks = 0; ks < 4; ++ks) {
+            u32x4 a[4];
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt)
+                a[mt] = *reinterpret_cast<const u32x4 *>(buf + (mt * 16 + i16) * kWdRow + ks * 32 + q * 8);
 #pragma unroll
             for (int mt = 0; mt < 4; ++mt) {
-                acc[mt][0] = mfma16p(f.a[ks][mt], f.b[ks][0], acc[mt][0]);
-                acc[mt][1] = mfma16p(f.a[ks][mt], f.b[ks][1], acc[mt][1]);
+                acc[mt][0] = mfma16p(a[mt], f.b[ks][0], acc[mt][0]);
+                acc[mt][1] = mfma16p(a[mt], f.b[ks][1], acc[mt][1]);
             }
+        }
     };
-    // groups in pairs: the fragments of group g+1 are in flight while group g is multiplied,
-    // and the slots (which the fragment addresses depend on) are fetched one group further ahead
-    DownFrags F0, F1;
+    // groups in pairs: while group g is multiplied, group g+1's Wd tile travels global -> registers
+    // -> the other LDS buffer and its activation fragments travel to registers; the slots (which
+    // the fragment addresses depend on) are fetched one group further ahead
+    u32x4 rw[4];
+    ActFrags F0, F1;
     int s0 = sl0[0], s1 = sl1[0];
     int n0 = G > 1 ? sl0[1] : -1, n1 = G > 1 ? sl1[1] : -1;
-    fetch(F0, 0, s0, s1);
+    load_w(rw, 0);
+    load_act(F0, 0, s0, s1);
+    store_w(sWd[0], rw);
+    __syncthreads();
     int g = 0;
     for (; g + 2 < G; g += 2) {
         s0 = n0; s1 = n1;                       // slots of group g+1
         n0 = sl0[g + 2]; n1 = sl1[g + 2];       // slots of group g+2
-        fetch(F1, g + 1, s0, s1);
-        multiply(F0);
+        load_w(rw, g + 1);
+        load_act(F1, g + 1, s0, s1);
+        multiply(sWd[0], F0);
+        store_w(sWd[1], rw);
+        __syncthreads();
         s0 = n0; s1 = n1;
         const int gn = g + 3 < G ? g + 3 : g + 2;
         n0 = sl0[gn]; n1 = sl1[gn];             // slots of group g+3 (or a harmless repeat)
-        fetch(F0, g + 2, s0, s1);
-        multiply(F1);
+        load_w(rw, g + 2);
+        load_act(F0, g + 2, s0, s1);
+        multiply(sWd[1], F1);
+        store_w(sWd[0], rw);
+        __syncthreads();
     }
-    // here F0 holds group g (g = G-1 or G-2) and (n0, n1) are the slots of group g+1 if it exists
+    // here sWd[0] / F0 hold group g (G-1 or G-2) and (n0, n1) are the slots of group g+1 if it exists
     if (g + 1 < G) {
-        fetch(F1, g + 1, n0, n1);
-        multiply(F0);
-        multiply(F1);
+        load_w(rw, g + 1);
+        load_act(F1, g + 1, n0, n1);
+        multiply(sWd[0], F0);
+        store_w(sWd[1], rw);
+        __syncthreads();
+        multiply(sWd[1], F1);
     } else {
-        multiply(F0);
+        multiply(sWd[0], F0);
     }
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt) {

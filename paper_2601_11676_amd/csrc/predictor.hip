@@ -31,7 +31,7 @@ __global__ __launch_bounds__(256) void dot_rows_kernel(const XT *__restrict__ X,
 // pieces l, l+64, ... in increasing order, one fused-multiply-add chain from +0, butterfly.
 constexpr int kPredTokens = 64;     // tokens per workgroup
 
-template <int NCH, int JB>
+template <int NCH, int JB, int TB>
 __global__ __launch_bounds__(256) void hidden_rows_kernel(const bf16_t *__restrict__ X,
                                                           const bf16_t *__restrict__ At,
                                                           float *__restrict__ h, int T, int r)
@@ -48,53 +48,88 @@ __global__ __launch_bounds__(256) void hidden_rows_kernel(const bf16_t *__restri
         for (int k = 0; k < NCH; ++k) load8(At + (size_t)j * d + (k * kWave + lane) * 8, wr[b][k]);
     }
     const int t0 = blockIdx.y * kPredTokens, t1 = min(T, t0 + kPredTokens);
-    for (int t = t0; t < t1; ++t) {
-        u32x4 xv[NCH];
+    // TB tokens per iteration; the next iteration's x pieces are requested before the current
+    // ones are used, so the sweep is not one memory round trip per token
+    auto fetch = [&](u32x4 (&xv)[TB][NCH], int t) {
 #pragma unroll
-        for (int k = 0; k < NCH; ++k)
-            xv[k] = *reinterpret_cast<const u32x4 *>(X + (size_t)t * d + (k * kWave + lane) * 8);
-        float p[JB];
+        for (int c = 0; c < TB; ++c) {
+            const int tc = t + c < t1 ? t + c : t1 - 1;          // past the end: a duplicate, not stored
 #pragma unroll
-        for (int b = 0; b < JB; ++b) p[b] = 0.0f;
+            for (int k = 0; k < NCH; ++k)
+                xv[c][k] = *reinterpret_cast<const u32x4 *>(X + (size_t)tc * d + (k * kWave + lane) * 8);
+        }
+    };
+    auto finish = [&](const u32x4 (&xv)[TB][NCH], int t) {
+        float p[TB][JB];
+#pragma unroll
+        for (int c = 0; c < TB; ++c)
+#pragma unroll
+            for (int b = 0; b < JB; ++b) p[c][b] = 0.0f;
 #pragma unroll
         for (int k = 0; k < NCH; ++k) {
-            float xf[8];
-            unpack8(xv[k], xf);
 #pragma unroll
-            for (int b = 0; b < JB; ++b)
+            for (int c = 0; c < TB; ++c) {
+                float xf[8];
+                unpack8(xv[c][k], xf);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) p[b] = __builtin_fmaf(xf[e], wr[b][k][e], p[b]);
+                for (int b = 0; b < JB; ++b)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) p[c][b] = __builtin_fmaf(xf[e], wr[b][k][e], p[c][b]);
+            }
         }
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) {
-            float qv[JB];
+            float qv[TB][JB];
 #pragma unroll
-            for (int b = 0; b < JB; ++b) qv[b] = __shfl_xor(p[b], off, kWave);
+            for (int c = 0; c < TB; ++c)
 #pragma unroll
-            for (int b = 0; b < JB; ++b) p[b] = p[b] + qv[b];
+                for (int b = 0; b < JB; ++b) qv[c][b] = __shfl_xor(p[c][b], off, kWave);
+#pragma unroll
+            for (int c = 0; c < TB; ++c)
+#pragma unroll
+                for (int b = 0; b < JB; ++b) p[c][b] = p[c][b] + qv[c][b];
         }
         if (lane == 0) {
 #pragma unroll
-            for (int b = 0; b < JB; ++b)
-                if (j0 + b < r) h[(size_t)t * r + j0 + b] = p[b] > 0.0f ? p[b] : 0.0f;
+            for (int c = 0; c < TB; ++c)
+#pragma unroll
+                for (int b = 0; b < JB; ++b)
+                    if (t + c < t1 && j0 + b < r)
+                        h[(size_t)(t + c) * r + j0 + b] = p[c][b] > 0.0f ? p[c][b] : 0.0f;
         }
+    };
+    u32x4 xa[TB][NCH], xb[TB][NCH];
+    fetch(xa, t0);
+    int t = t0;
+    for (; t + 2 * TB < t1; t += 2 * TB) {      // two iterations per trip: the buffers swap by name
+        fetch(xb, t + TB);
+        finish(xa, t);
+        fetch(xa, t + 2 * TB);
+        finish(xb, t + TB);
+    }
+    if (t + TB < t1) {
+        fetch(xb, t + TB);
+        finish(xa, t);
+        finish(xb, t + TB);
+    } else {
+        finish(xa, t);
     }
 }
 
-template <int NCH, int JB>
+template <int NCH, int JB, int TB>
 static void launch_hidden_rows(const bf16_t *x, int T, int r, const bf16_t *At, float *h, hipStream_t s)
 {
-    hidden_rows_kernel<NCH, JB><<<dim3((r + 4 * JB - 1) / (4 * JB), (T + kPredTokens - 1) / kPredTokens),
-                                 dim3(256), 0, s>>>(x, At, h, T, r);
+    hidden_rows_kernel<NCH, JB, TB><<<dim3((r + 4 * JB - 1) / (4 * JB), (T + kPredTokens - 1) / kPredTokens),
+                                     dim3(256), 0, s>>>(x, At, h, T, r);
 }
 
 static bool hidden_rows_tiled(const bf16_t *x, int T, int d, int r, const bf16_t *At, float *h, hipStream_t s)
 {
     if (T < 16) return false;
     switch (d) {
-    case 4096: launch_hidden_rows<8, 2>(x, T, r, At, h, s); return true;
-    case 5120: launch_hidden_rows<10, 2>(x, T, r, At, h, s); return true;
-    case 8192: launch_hidden_rows<16, 1>(x, T, r, At, h, s); return true;
+    case 4096: launch_hidden_rows<8, 2, 1>(x, T, r, At, h, s); return true;
+    case 5120: launch_hidden_rows<10, 2, 1>(x, T, r, At, h, s); return true;
+    case 8192: launch_hidden_rows<16, 1, 1>(x, T, r, At, h, s); return true;
     default: return false;
     }
 }
