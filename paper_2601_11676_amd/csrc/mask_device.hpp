@@ -40,39 +40,53 @@ __device__ __forceinline__ void mask_scores_block(
     uint8_t *__restrict__ mask, int32_t *__restrict__ surv_idx, int32_t *__restrict__ n_surv)
 {
     constexpr int kWaves = NT / kWave;
+    constexpr int GB = NT >= 1024 ? 8 : 16;     // groups whose rows a wave fetches before reducing any
     const int wave = tid >> 6, lane = tid & 63;
-    // the schedule and this token's loss outcomes are fetched up front, off the critical path
-    for (int p = tid; p < K; p += NT) sh.prio[p] = prio_dev[p];
-    if (tid < n_dev) sh.drop[tid] = drop ? drop[tid] : 0;
-    for (int g = tid; g < 1024; g += NT) sh.pos[g] = 0;
-    if (FUSED) {
-        if (r <= 512) {
-            // one 8-element piece per lane: load the rows of a whole batch of groups before
-            // reducing any, so the wave pays the memory latency once (G <= 128 per 8 waves)
-            constexpr int GB = NT >= 1024 ? 8 : 16;
-            const bool on = lane * 8 < r;
-            float hx[8];
+    // Everything the head needs from memory -- schedule, loss outcomes, h, the first batch of
+    // Bt rows -- is requested in one straight line (clamped addresses and selects, no branches),
+    // so the workgroup pays one memory latency, not one per item.
+    const void *anywhere = FUSED ? static_cast<const void *>(Bt) : static_cast<const void *>(scores);
+    const int8_t *pp = K > 0 ? prio_dev + (tid < K ? tid : K - 1) : static_cast<const int8_t *>(anywhere);
+    const uint8_t *dp = drop ? drop + (tid < n_dev ? tid : n_dev - 1) : static_cast<const uint8_t *>(anywhere);
+    const int8_t pv = *pp;
+    const uint8_t dv = *dp;
+    const bool fast = FUSED && r <= 512;        // one 8-element piece of h and of every row per lane
+    const bool on = lane * 8 < r;
+    float hx[8];
+    Piece8<WT> w[GB];
+    auto load_batch = [&](int g0) {
+#pragma unroll
+        for (int b = 0; b < GB; ++b) {
+            const int g = g0 + kWaves * b;
+            const bool ok = on && g < G;
+            w[b].load(Bt + (size_t)(g < G ? g : G - 1) * r + (on ? lane * 8 : 0));
+            if (!ok) w[b].zero();
+        }
+    };
+    if (fast) {
+        load8(h + (on ? lane * 8 : 0), hx);
+        if (!on) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) hx[e] = 0.0f;
-            if (on) load8(h + lane * 8, hx);
+        }
+        load_batch(wave < G ? wave : 0);        // a wave beyond G loads (and later discards) batch 0
+    }
+    if (tid < K) sh.prio[tid] = pv;
+    for (int p = tid + NT; p < K; p += NT) sh.prio[p] = prio_dev[p];
+    if (tid < n_dev) sh.drop[tid] = drop ? dv : 0;
+    for (int g = tid; g < 1024; g += NT) sh.pos[g] = 0;
+    if (FUSED) {
+        if (fast) {
             for (int g0 = wave; g0 < G; g0 += kWaves * GB) {
-                Piece8<WT> w[GB];
-#pragma unroll
-                for (int b = 0; b < GB; ++b) {
-                    const int g = g0 + kWaves * b;
-                    w[b].zero();
-                    if (on && g < G) w[b].load(Bt + (size_t)g * r + lane * 8);
-                }
+                if (g0 != wave) load_batch(g0);
                 float p[GB];
 #pragma unroll
                 for (int b = 0; b < GB; ++b) {
                     p[b] = 0.0f;
-                    if (on) {
-                        float wf[8];
-                        w[b].get(wf);
+                    float wf[8];
+                    w[b].get(wf);
 #pragma unroll
-                        for (int e = 0; e < 8; ++e) p[b] = __builtin_fmaf(hx[e], wf[e], p[b]);
-                    }
+                    for (int e = 0; e < 8; ++e) p[b] = __builtin_fmaf(hx[e], wf[e], p[b]);
                 }
                 // the eight butterflies advance together: one exchange round trip per distance
 #pragma unroll
