@@ -48,6 +48,8 @@ TID_BT = 6
 TID_DROP = 7
 TID_PLR = 8
 TID_MISC = 9
+TID_Q4_CODES = 16     # + 0 gate, 1 up, 2 down
+TID_Q4_SCALES = 24    # + 0 gate, 1 up, 2 down
 
 
 def _mix_py(z: int) -> int:
@@ -208,6 +210,79 @@ def ffn_weights(w: Workload, layer: int = 0, device="cpu", copy: int = 0):
     lay = layer + 1000003 * copy
     mk = lambda tid: normal((w.ffn, w.d), W_SIGMA, dt, stream_key(w.seed, tid, lay), device)
     return mk(TID_WG), mk(TID_WU), mk(TID_WDT)
+
+
+# --------------------------------------------------------------------------
+# 4-bit block-quantised weights (the paper's models are 4-bit, section V-A)
+# --------------------------------------------------------------------------
+# Storage format (the library's, restated here because the generator writes it directly):
+# blocks of Q4_BLOCK consecutive elements along the reduction dimension share one bf16
+# scale s; an element is s * (c - 8) with a 4-bit code c.  Eight codes per 32-bit word:
+# element 2i of the word's eight sits in bits [4i, 4i+3], element 2i+1 in bits
+# [16+4i, 16+4i+3] (i = 0..3).
+# Values: the code is a fixed function of 16 hashed bits (a bell shape centred on 8,
+# like rounded normal weights), the scale is 2^-8 * (1 + k/128) with 7 hashed bits k, so
+# element values have a standard deviation of about 0.015 and only integer operations and a
+# table lookup are involved (bit-identical on CPU and GPU).
+
+Q4_BLOCK = 128
+
+
+@functools.lru_cache(maxsize=1)
+def _q4_code_table_np() -> np.ndarray:
+    z = _quantile_table_np().astype(np.float64)
+    return np.clip(np.floor(z * 2.5 + 8.5), 0, 15).astype(np.uint8)
+
+
+_code_table_cache = {}
+
+
+def _q4_code_table(device="cpu") -> torch.Tensor:
+    dev = torch.device(device)
+    key = (dev.type, dev.index)
+    if key not in _code_table_cache:
+        _code_table_cache[key] = torch.from_numpy(_q4_code_table_np().copy()).to(dev)
+    return _code_table_cache[key]
+
+
+def q4_codes(n_elements: int, key: int, device="cpu", chunk: int = 1 << 25) -> torch.Tensor:
+    """n_elements/8 int32 words holding the packed 4-bit codes of elements 0..n_elements-1."""
+    assert n_elements % 8 == 0 and chunk % 8 == 0
+    out = torch.empty(n_elements // 8, dtype=torch.int32, device=device)
+    tab = _q4_code_table(device)
+    shifts = torch.tensor([0, 16, 4, 20, 8, 24, 12, 28], dtype=torch.int64, device=device)
+    for s in range(0, n_elements, chunk):
+        c = min(chunk, n_elements - s)
+        code = tab[_lsr(raw_u64(key, s, c, device), 48)].to(torch.int64).reshape(-1, 8)
+        word = (code << shifts).sum(dim=1)                       # disjoint bit fields: sum == or
+        word = torch.where(word >= (1 << 31), word - (1 << 32), word)
+        out[s // 8:(s + c) // 8] = word.to(torch.int32)
+    return out
+
+
+def q4_scales(n_blocks: int, key: int, device="cpu") -> torch.Tensor:
+    """n_blocks bf16 scales in [2^-8, 2^-7)."""
+    k = _lsr(raw_u64(key, 0, n_blocks, device), 48) & 0x7F
+    return (k + 0x3B80).to(torch.int16).view(torch.bfloat16)
+
+
+def ffn_weights_q4(w: Workload, layer: int = 0, device="cpu", copy: int = 0):
+    """4-bit FFN weights of one layer, as the library stores them:
+    (Wg_codes int32 [ffn][d/8], Wg_scales bf16 [ffn][d/128], the same two for Wu,
+     Wd_codes int32 [G][d][gs/8], Wd_scales bf16 [G][d]).
+    Gate/up blocks run along d; the down projection is group-blocked and the block of
+    output j in group g is the group's gs = 128 neurons."""
+    assert w.d % Q4_BLOCK == 0 and w.group_size == Q4_BLOCK
+    lay = layer + 1000003 * copy
+    G, gs, d = w.n_groups, w.group_size, w.d
+    out = []
+    for i in range(2):
+        out.append(q4_codes(w.ffn * d, stream_key(w.seed, TID_Q4_CODES + i, lay), device).reshape(w.ffn, d // 8))
+        out.append(q4_scales(w.ffn * (d // Q4_BLOCK), stream_key(w.seed, TID_Q4_SCALES + i, lay),
+                             device).reshape(w.ffn, d // Q4_BLOCK))
+    out.append(q4_codes(G * d * gs, stream_key(w.seed, TID_Q4_CODES + 2, lay), device).reshape(G, d, gs // 8))
+    out.append(q4_scales(G * d, stream_key(w.seed, TID_Q4_SCALES + 2, lay), device).reshape(G, d))
+    return tuple(out)
 
 
 def predictor_weights(w: Workload, layer: int = 0, device="cpu", copy: int = 0):

@@ -30,6 +30,9 @@
  *                              down columns; the block output is the plain sum of
  *                              the groups' partial results (merge at the master).
  *
+ *   halo_ref_dequant_q4 /
+ *   halo_ref_dequant_down_q4   Sec. V-A: 4-bit integer weights (format: the library's).
+ *
  * Pins (see tests/test_oracle_*.py): Alg. 3's printed example; the 6144/256 = 24
  * group count; dense SwiGLU via a float64 library matmul; sum of partials = dense;
  * exact zeros for dropped / unselected groups; brute-force and library stable
@@ -375,6 +378,63 @@ int halo_ref_group_sparse_ffn(const float *x, int32_t T, int32_t d, int32_t G, i
     }
     free(act);
     free(part);
+    return REF_OK;
+}
+
+/* ------------------------------------------------------------------------- */
+/* 4-bit block-quantised weights.                                             */
+/*                                                                           */
+/* Sec. V-A: the evaluated models are quantised to 4-bit integers.  The paper */
+/* fixes no storage format; the one used here is the library's (stated in its */
+/* header): blocks of 128 consecutive elements along the reduction dimension  */
+/* share one scale s (a bf16 value, passed here widened to float), an element */
+/* is s * (c - 8) with a 4-bit code c; eight codes per 32-bit word, element   */
+/* 2i of the eight in bits [4i, 4i+3] and element 2i+1 in bits                */
+/* [16+4i, 16+4i+3].  The oracle's view of a quantised block is simply the    */
+/* dequantised matrix (every value is exact in float: 8 significant bits of   */
+/* scale times a 4-bit integer), fed to the same fp64 FFN as above.           */
+/* ------------------------------------------------------------------------- */
+#define Q4_BLOCK 128
+
+static int q4_code(const uint32_t *words, size_t element)
+{
+    const uint32_t w = words[element >> 3];
+    const unsigned k = (unsigned)(element & 7u);          /* position among the word's eight */
+    const unsigned shift = (k & 1u) ? 16u + 4u * (k >> 1) : 4u * (k >> 1);
+    return (int)((w >> shift) & 15u);
+}
+
+/* Row-major matrix [rows][cols], blocks along cols: out[r][c] = s[r][c/128] * (code - 8). */
+int halo_ref_dequant_q4(const uint32_t *codes /*[rows][cols/8]*/, const float *scales /*[rows][cols/128]*/,
+                        int64_t rows, int32_t cols, float *out /*[rows][cols]*/)
+{
+    if (!codes || !scales || !out || rows < 0 || cols < Q4_BLOCK || cols % Q4_BLOCK) return REF_ERR;
+    const int32_t nb = cols / Q4_BLOCK;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r)
+        for (int32_t c = 0; c < cols; ++c) {
+            const double s = (double)scales[(size_t)r * nb + c / Q4_BLOCK];
+            out[(size_t)r * cols + c] = (float)(s * (double)(q4_code(codes, (size_t)r * cols + c) - 8));
+        }
+    return REF_OK;
+}
+
+/* Down projection, group-blocked: codes [G][d][gs/8], scales [G][d]; the block of output j
+   in group g is the group's gs = 128 neurons.  Written out neuron-major like the other
+   matrices: WdT[g*gs + m][j] = s[g][j] * (code(g, j, m) - 8). */
+int halo_ref_dequant_down_q4(const uint32_t *codes, const float *scales, int32_t G, int32_t d, int32_t gs,
+                             float *WdT /*[G*gs][d]*/)
+{
+    if (!codes || !scales || !WdT || G < 1 || d < 1 || gs != Q4_BLOCK) return REF_ERR;
+#pragma omp parallel for schedule(static)
+    for (int32_t g = 0; g < G; ++g)
+        for (int32_t j = 0; j < d; ++j) {
+            const double s = (double)scales[(size_t)g * d + j];
+            for (int32_t m = 0; m < gs; ++m) {
+                const int c = q4_code(codes, ((size_t)g * d + j) * gs + m);
+                WdT[((size_t)g * gs + m) * d + j] = (float)(s * (double)(c - 8));
+            }
+        }
     return REF_OK;
 }
 

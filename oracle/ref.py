@@ -173,3 +173,40 @@ def ffn_forward(x, At, Bt, Wg, Wu, WdT, gs: int, K: int, prio_dev, n_dev: int, d
         raise ValueError("halo_ref_ffn_forward rejected its arguments")
     return dict(y=y, scores=scores, order=order, group_dev=group_dev, mask=mask,
                 surv_idx=surv_idx, n_surv=n_surv)
+
+
+def _u32(a) -> np.ndarray:
+    a = np.ascontiguousarray(np.asarray(a))
+    assert a.dtype in (np.int32, np.uint32)
+    return a.view(np.uint32)
+
+
+def dequant_q4(codes, scales) -> np.ndarray:
+    """Row-major 4-bit matrix -> float32 [rows][cols] (blocks of 128 along cols)."""
+    codes, scales = _u32(codes), _f32(scales)
+    rows, cols = codes.shape[0], codes.shape[1] * 8
+    assert scales.shape == (rows, cols // 128)
+    out = np.empty((rows, cols), dtype=np.float32)
+    rc = lib().halo_ref_dequant_q4(_p(codes, C.c_uint32), _p(scales, C.c_float), C.c_int64(rows),
+                                   C.c_int32(cols), _p(out, C.c_float))
+    if rc != 0:
+        raise ValueError("halo_ref_dequant_q4 rejected its arguments")
+    return out
+
+
+def dequant_down_q4(codes, scales) -> np.ndarray:
+    """Group-blocked 4-bit down projection [G][d][gs/8] -> float32 WdT [G*gs][d]."""
+    codes, scales = _u32(codes), _f32(scales)
+    G, d, gs = codes.shape[0], codes.shape[1], codes.shape[2] * 8
+    assert scales.shape == (G, d)
+    out = np.empty((G * gs, d), dtype=np.float32)
+    rc = lib().halo_ref_dequant_down_q4(_p(codes, C.c_uint32), _p(scales, C.c_float), C.c_int32(G),
+                                        C.c_int32(d), C.c_int32(gs), _p(out, C.c_float))
+    if rc != 0:
+        raise ValueError("halo_ref_dequant_down_q4 rejected its arguments")
+    return out
+
+
+def dequant_ffn_q4(q4):
+    """(Wg_codes, Wg_scales, Wu_codes, Wu_scales, Wd_codes, Wd_scales) -> (Wg, Wu, WdT) float32."""
+    return dequant_q4(q4[0], q4[1]), dequant_q4(q4[2], q4[3]), dequant_down_q4(q4[4], q4[5])
