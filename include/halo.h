@@ -207,6 +207,38 @@ int halo_ffn_forward_ahead(const halo_shape *shape, const void *x, int32_t T, co
                            int32_t *n_surv_next, void *workspace, size_t ws_bytes, void *stream);
 
 /*
+ * The FFN over 4-bit block-quantised weights (paper Sec. V-A: the evaluated models are
+ * quantised to 4-bit integers; the paper fixes no storage format, this one is the library's).
+ *
+ * Format: blocks of 128 consecutive elements along the reduction dimension share one bf16
+ * scale s; an element is s * (c - 8) with a 4-bit code c in 0..15.  Codes are packed eight per
+ * 32-bit little-endian word: of the word's eight consecutive elements, element 2i sits in
+ * bits [4i, 4i+3] and element 2i+1 in bits [16+4i, 16+4i+3] (i = 0..3).
+ *   Wg_codes, Wu_codes : [ffn][d/8] words       Wg_scales, Wu_scales : [ffn][d/128] bf16
+ *                        (row m = neuron m, blocks along d)
+ *   Wd_codes           : [n_groups][d][16] words Wd_scales           : [n_groups][d] bf16
+ *                        (group-blocked like Wd above: the block of output j in group g is
+ *                         the group's 128 neurons)
+ * Needs group_size == 128 and d % 128 == 0 (HALO_ERR_SHAPE otherwise); shape->dtype is the type
+ * of x, y and the predictor weights.  All pointers are device pointers, 16-byte aligned.
+ * Everything else -- mask semantics, workspace, stream, errors -- is as in
+ * halo_group_sparse_ffn / halo_ffn_forward.  One bf16 token with d in {4096, 8192} and
+ * n_groups <= 256 streams each surviving code byte once; other shapes take a plain path.
+ */
+int halo_group_sparse_ffn_q4(const halo_shape *shape, const void *x, int32_t T, const void *Wg_codes,
+                             const void *Wg_scales, const void *Wu_codes, const void *Wu_scales,
+                             const void *Wd_codes, const void *Wd_scales, const uint8_t *mask, void *y,
+                             void *workspace, size_t ws_bytes, void *stream);
+
+int halo_ffn_forward_q4(const halo_shape *shape, const void *x, const void *x_pred, int32_t T,
+                        const void *At, const void *Bt, const void *Wg_codes, const void *Wg_scales,
+                        const void *Wu_codes, const void *Wu_scales, const void *Wd_codes,
+                        const void *Wd_scales, int32_t k_keep, const int8_t *prio_dev, int32_t n_dev,
+                        const uint8_t *drop, void *y, float *scores, int32_t *order, int8_t *group_dev,
+                        uint8_t *mask, int32_t *surv_idx, int32_t *n_surv, void *workspace, size_t ws_bytes,
+                        void *stream);
+
+/*
  * Benchmark aid (not part of the paper's method).  Between halo_profile_begin and
  * halo_profile_end every call of halo_group_sparse_ffn / halo_ffn_forward brackets the
  * FFN's dominant kernel -- the gate/up projection, which streams two thirds of the

@@ -80,6 +80,11 @@ def load_library():
     lib.halo_ffn_forward_ahead.restype = C.c_int
     lib.halo_ffn_forward_ahead.argtypes = [ps, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, i32,
                                            vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.halo_group_sparse_ffn_q4.restype = C.c_int
+    lib.halo_group_sparse_ffn_q4.argtypes = [ps, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.halo_ffn_forward_q4.restype = C.c_int
+    lib.halo_ffn_forward_q4.argtypes = [ps, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, i32, vp,
+                                        vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.halo_profile_begin.restype = C.c_int
     lib.halo_profile_begin.argtypes = [i32, i32]
     lib.halo_profile_end.restype = C.c_int
@@ -210,6 +215,27 @@ def halo_ffn_forward_ahead(shape: Shape, x, Wg, Wu, Wd, mask_cur, y, x_pred_next
         _ptr(surv_idx_next), _ptr(n_surv_next), _ptr(workspace), workspace.numel(),
         _stream(stream))
     _check("halo_ffn_forward_ahead", rc)
+
+
+def halo_group_sparse_ffn_q4(shape: Shape, x, q4, mask, y, workspace, stream=None) -> None:
+    """q4 = (Wg_codes, Wg_scales, Wu_codes, Wu_scales, Wd_codes, Wd_scales), see include/halo.h."""
+    T = x.shape[0]
+    rc = load_library().halo_group_sparse_ffn_q4(
+        C.byref(shape.c), _ptr(x), T, *[_ptr(t) for t in q4], _ptr(mask), _ptr(y), _ptr(workspace),
+        workspace.numel(), _stream(stream))
+    _check("halo_group_sparse_ffn_q4", rc)
+
+
+def halo_ffn_forward_q4(shape: Shape, x, At, Bt, q4, k_keep: int, prio_dev, n_dev: int, drop, y, workspace,
+                        x_pred=None, scores=None, order=None, group_dev=None, mask=None, surv_idx=None,
+                        n_surv=None, stream=None) -> None:
+    T = x.shape[0]
+    xp = x if x_pred is None else x_pred
+    rc = load_library().halo_ffn_forward_q4(
+        C.byref(shape.c), _ptr(x), _ptr(xp), T, _ptr(At), _ptr(Bt), *[_ptr(t) for t in q4], int(k_keep),
+        _ptr(prio_dev), int(n_dev), _ptr(drop), _ptr(y), _ptr(scores), _ptr(order), _ptr(group_dev),
+        _ptr(mask), _ptr(surv_idx), _ptr(n_surv), _ptr(workspace), workspace.numel(), _stream(stream))
+    _check("halo_ffn_forward_q4", rc)
 
 
 def prepared(fn, *args, **kwargs):

@@ -1,0 +1,362 @@
+// Group-sparse SwiGLU FFN over 4-bit block-quantised weights (paper Sec. V-A: the evaluated
+// models are quantised to 4-bit integers; Sec. II-A neuron groups, merge = sum).
+//
+// Storage format (the library's own; the paper fixes none): blocks of 128 consecutive elements
+// along the reduction dimension share one bf16 scale s, an element is s * (c - 8) with a
+// 4-bit code c.  Eight codes per 32-bit word: element 2i of the eight in bits [4i, 4i+3],
+// element 2i+1 in bits [16+4i, 16+4i+3], so that (word >> 4i) & 0x000F000F holds the
+// pair (2i, 2i+1) in the two halves of a register -- the shape of a packed bf16 pair.
+//   gate/up : codes [ffn][d/8] words, scales [ffn][d/128]        (blocks along d)
+//   down    : codes [G][d][gs/8] words, scales [G][d], gs = 128  (block = the group's neurons)
+//
+// One token (the hot path): a quarter of the bf16 bytes per group, so the kernels are built
+// like the bf16 ones -- stream every surviving byte once with 16-byte loads -- and the
+// arithmetic stays far below the memory time: or-ing 0x4300 over a code gives the bf16 value
+// 128 + c exactly, the packed dot instruction multiplies two of those with two activations,
+// and the constant offset is taken out once per 32 elements: sum (c-8) x = sum (128+c) x -
+// 136 sum x.  Any other shape goes through plain kernels that dequantise element by element.
+#include "kernels.hpp"
+#include "mask_words.hpp"
+
+namespace halo {
+
+constexpr int kQ4Block = 128;
+
+__device__ __forceinline__ uint32_t q4_pair(uint32_t w, int i)
+{
+    return ((w >> (4 * i)) & 0x000F000Fu) | 0x43004300u;
+}
+
+// sum over the 32 elements of one 16-byte code piece of (128 + c) * x, x as 16 packed bf16 pairs
+__device__ __forceinline__ float q4_dot32(const u32x4 &c, const u32x4 (&x)[4])
+{
+    float a0 = 0.0f, a1 = 0.0f;
+    const uint32_t w[4] = {c.x, c.y, c.z, c.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        a0 = dot2_bf16(q4_pair(w[j], 0), x[j].x, a0);
+        a1 = dot2_bf16(q4_pair(w[j], 1), x[j].y, a1);
+        a0 = dot2_bf16(q4_pair(w[j], 2), x[j].z, a0);
+        a1 = dot2_bf16(q4_pair(w[j], 3), x[j].w, a1);
+    }
+    return a0 + a1;
+}
+
+// sum of 32 bf16 values held as 16 packed pairs
+__device__ __forceinline__ float sum32(const u32x4 (&x)[4])
+{
+    float a = 0.0f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        a = dot2_bf16(0x3F803F80u, x[j].x, a);
+        a = dot2_bf16(0x3F803F80u, x[j].y, a);
+        a = dot2_bf16(0x3F803F80u, x[j].z, a);
+        a = dot2_bf16(0x3F803F80u, x[j].w, a);
+    }
+    return a;
+}
+
+__device__ __forceinline__ float bf16_bits_to_float(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+
+// ---------------------------------------------------------------------------
+// one token, bf16 activations, d = NH * 2048, group size 128, G <= 256
+// ---------------------------------------------------------------------------
+// gate/up: one wave per neuron at a time, NB neurons requested together.  A lane owns the 32
+// elements 2048 h + 32 lane .. + 31 of every half h: one 16-byte code piece per matrix row and
+// half, one scale (block 16 h + lane / 4), and the matching 64 bytes of x kept in registers.
+template <int NH>
+__global__ __launch_bounds__(256) void gate_up_q4_t1(
+    const bf16_t *__restrict__ x, int G, const uint32_t *__restrict__ Gq, const bf16_t *__restrict__ Gs,
+    const uint32_t *__restrict__ Uq, const bf16_t *__restrict__ Us, const uint8_t *__restrict__ mask,
+    bf16_t *__restrict__ act)
+{
+    constexpr int d = NH * 2048, gs = 128, NB = 12 / NH;
+    constexpr int kWords = d / 8, kBlocks = d / kQ4Block;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const MaskWords mw = load_mask_words(mask, G, lane);
+    const long long total = (long long)mw.count * gs;
+    const int nw = gridDim.x * 4, w = blockIdx.x * 4 + wave;
+    const int n0 = (int)(total * w / nw), n1 = (int)(total * (w + 1) / nw);
+    if (n0 >= n1) return;
+    u32x4 xr[NH][4];
+    float xs[NH];
+#pragma unroll
+    for (int h = 0; h < NH; ++h) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            xr[h][j] = *reinterpret_cast<const u32x4 *>(x + h * 2048 + lane * 32 + j * 8);
+    }
+    for (int nb = n0; nb < n1; nb += NB) {
+        u32x4 cg[NB][NH], cu[NB][NH];
+        uint16_t sg[NB][NH], su[NB][NH];
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            const int n = nb + i < n1 ? nb + i : n1 - 1;            // past the end: an in-range duplicate
+            const int u = n / gs;
+            const size_t row = (size_t)nth_group(mw, u, lane) * gs + (n - u * gs);
+#pragma unroll
+            for (int h = 0; h < NH; ++h) {
+                cg[i][h] = __builtin_nontemporal_load(
+                    reinterpret_cast<const u32x4 *>(Gq + row * kWords + h * 256) + lane);
+                cu[i][h] = __builtin_nontemporal_load(
+                    reinterpret_cast<const u32x4 *>(Uq + row * kWords + h * 256) + lane);
+                sg[i][h] = Gs[row * kBlocks + h * 16 + (lane >> 2)];
+                su[i][h] = Us[row * kBlocks + h * 16 + (lane >> 2)];
+            }
+        }
+        if (nb == n0) {
+#pragma unroll
+            for (int h = 0; h < NH; ++h) xs[h] = 136.0f * sum32(xr[h]);
+        }
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            float ag = 0.0f, au = 0.0f;
+#pragma unroll
+            for (int h = 0; h < NH; ++h) {
+                ag = __builtin_fmaf(bf16_bits_to_float(sg[i][h]), q4_dot32(cg[i][h], xr[h]) - xs[h], ag);
+                au = __builtin_fmaf(bf16_bits_to_float(su[i][h]), q4_dot32(cu[i][h], xr[h]) - xs[h], au);
+            }
+            const float v = silu_mul(wave_sum_fast(ag), wave_sum_fast(au));
+            if (lane == 0 && nb + i < n1) act[nb + i] = f32_to_bf16(v);
+        }
+    }
+}
+
+// down: four lanes share an output row j (16 bytes each = 32 of the group's 128 neurons), a
+// wave covers 16 consecutive rows = 1 KiB of a group's codes, the workgroup's eight waves take
+// every eighth surviving group and meet in LDS.  The activation vector is staged in LDS once
+// per workgroup together with its 32-element sums (for the constant offset of the codes).
+constexpr int kDownQ4Batch = 8;
+
+struct DownQ4Shared {
+    int list[256];
+    __attribute__((aligned(16))) bf16_t act[256 * 128];
+    float asum[256 * 4];
+    float part[8][16];
+};
+
+__global__ __launch_bounds__(512) void down_q4_t1(int d, int G, const uint32_t *__restrict__ Dq,
+                                                   const bf16_t *__restrict__ Ds,
+                                                   const uint8_t *__restrict__ mask,
+                                                   const bf16_t *__restrict__ act, bf16_t *__restrict__ y)
+{
+    constexpr int gs = 128, kB = kDownQ4Batch;
+    __shared__ DownQ4Shared sh;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const MaskWords mw = load_mask_words(mask, G, lane);
+    const int count = mw.count;
+    const int j = blockIdx.x * 16 + (lane >> 2);                   // output row of this lane
+    const int p = lane & 3;                                        // which 32 neurons of the group
+    if (count == 0) {                                              // uniform
+        if (wave == 0 && p == 0) y[j] = 0;
+        return;
+    }
+    // stage the activation (count * 16 pieces of 16 bytes) and build the group list
+    {
+        const u32x4 *asrc = reinterpret_cast<const u32x4 *>(act);
+        u32x4 *adst = reinterpret_cast<u32x4 *>(sh.act);
+        for (int i = tid; i < count * 16; i += 512) adst[i] = asrc[i];
+    }
+    if (wave == 0) {
+        int base = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            if ((mw.w[k] >> lane) & 1ull)
+                sh.list[base + __popcll(mw.w[k] & ((1ull << lane) - 1ull))] = k * kWave + lane;
+            base += __popcll(mw.w[k]);
+        }
+    }
+    __syncthreads();
+    for (int i = tid; i < count * 4; i += 512) {
+        u32x4 a[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) a[k] = *reinterpret_cast<const u32x4 *>(sh.act + i * 32 + k * 8);
+        sh.asum[i] = 136.0f * sum32(a);
+    }
+    float acc = 0.0f;
+    const size_t gstride = (size_t)d * 16;                         // words per group
+    u32x4 c[kB];
+    uint16_t s[kB];
+    auto load_batch = [&](int u0) {
+#pragma unroll
+        for (int q = 0; q < kB; ++q) {
+            const int u = u0 + 8 * q < count ? u0 + 8 * q : count - 1;   // past the end: an in-range duplicate
+            const int g = sh.list[u];
+            c[q] = __builtin_nontemporal_load(
+                reinterpret_cast<const u32x4 *>(Dq + g * gstride + (size_t)j * 16) + p);
+            s[q] = Ds[(size_t)g * d + j];
+        }
+    };
+    load_batch(wave);                                              // every wave, also one with no group
+    __syncthreads();                                               // asum complete
+    for (int u0 = wave; u0 < count; u0 += 8 * kB) {
+        if (u0 != wave) load_batch(u0);
+#pragma unroll
+        for (int q = 0; q < kB; ++q) {
+            const int u = u0 + 8 * q;
+            if (u < count) {
+                u32x4 a[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+                    a[k] = *reinterpret_cast<const u32x4 *>(sh.act + u * gs + p * 32 + k * 8);
+                acc = __builtin_fmaf(bf16_bits_to_float(s[q]), q4_dot32(c[q], a) - sh.asum[u * 4 + p], acc);
+            }
+        }
+    }
+    // the four lanes of a row, then the eight waves
+    acc = dpp_add<0xB1>(acc);
+    acc = dpp_add<0x4E>(acc);
+    if (p == 0) sh.part[wave][lane >> 2] = acc;
+    __syncthreads();
+    if (wave == 0 && lane < 16) {
+        float v = 0.0f;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) v += sh.part[k][lane];
+        y[blockIdx.x * 16 + lane] = f32_to_bf16(v);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// generic (any T, f32 or bf16 activations): dequantise element by element
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void q4_unpack8(uint32_t w, float s, float (&o)[8])
+{
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        o[2 * i] = s * (float)((int)((w >> (4 * i)) & 15u) - 8);
+        o[2 * i + 1] = s * (float)((int)((w >> (16 + 4 * i)) & 15u) - 8);
+    }
+}
+
+template <typename XT, int TT>
+__global__ __launch_bounds__(256) void gate_up_q4_generic(
+    const XT *__restrict__ x, int T, int d, int G, int gs, const uint32_t *__restrict__ Gq,
+    const bf16_t *__restrict__ Gs, const uint32_t *__restrict__ Uq, const bf16_t *__restrict__ Us,
+    const uint8_t *__restrict__ mask, const int32_t *__restrict__ ulist, const int32_t *__restrict__ meta,
+    float *__restrict__ act, int act_stride)
+{
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int total = meta[0] * gs;
+    const int nwaves = gridDim.x * 4;
+    const int words = d / 8, blocks = d / kQ4Block;
+    for (int n = blockIdx.x * 4 + wave; n < total; n += nwaves) {
+        const int u = n / gs, m = n - u * gs;
+        const int g = ulist[u];
+        const size_t row = (size_t)g * gs + m;
+        for (int t0 = 0; t0 < T; t0 += TT) {
+            float ag[TT], au[TT];
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt) ag[tt] = au[tt] = 0.0f;
+            for (int c = lane; c < words; c += kWave) {
+                float a[8], b[8];
+                q4_unpack8(Gq[row * words + c], to_float(Gs[row * blocks + c / 16]), a);
+                q4_unpack8(Uq[row * words + c], to_float(Us[row * blocks + c / 16]), b);
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt) {
+                    if (t0 + tt < T) {
+                        float xv[8];
+                        load8(x + (size_t)(t0 + tt) * d + c * 8, xv);
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            ag[tt] = __builtin_fmaf(a[e], xv[e], ag[tt]);
+                            au[tt] = __builtin_fmaf(b[e], xv[e], au[tt]);
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt) {
+                const float vg = wave_sum(ag[tt]), vu = wave_sum(au[tt]);
+                const int t = t0 + tt;
+                if (lane == 0 && t < T)
+                    act[(size_t)t * act_stride + n] = mask[(size_t)t * G + g] ? silu_mul(vg, vu) : 0.0f;
+            }
+        }
+    }
+}
+
+// one wave per output row j; lanes take neurons lane and lane + 64 of every union group
+template <typename XT, int TT>
+__global__ __launch_bounds__(256) void down_q4_generic(
+    const float *__restrict__ act, int act_stride, int T, int d, const uint32_t *__restrict__ Dq,
+    const bf16_t *__restrict__ Ds, const int32_t *__restrict__ ulist, const int32_t *__restrict__ meta,
+    XT *__restrict__ y)
+{
+    constexpr int gs = 128;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int j = blockIdx.x * 4 + wave;
+    if (j >= d) return;
+    const int n_u = meta[0];
+    for (int t0 = 0; t0 < T; t0 += TT) {
+        float acc[TT];
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) acc[tt] = 0.0f;
+        for (int u = 0; u < n_u; ++u) {
+            const size_t blk = (size_t)ulist[u] * d + j;
+            const float s = to_float(Ds[blk]);
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                const int m = lane + half * kWave;
+                const uint32_t w = Dq[blk * (gs / 8) + m / 8];
+                const int k = m & 7;
+                const int shift = (k & 1) ? 16 + 4 * (k >> 1) : 4 * (k >> 1);
+                const float wv = s * (float)((int)((w >> shift) & 15u) - 8);
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt)
+                    if (t0 + tt < T)
+                        acc[tt] = __builtin_fmaf(wv, act[(size_t)(t0 + tt) * act_stride + u * gs + m], acc[tt]);
+            }
+        }
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) {
+            const float v = wave_sum(acc[tt]);
+            if (lane == 0 && t0 + tt < T) store_out(y + (size_t)(t0 + tt) * d + j, v);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------
+template <typename XT>
+static hipError_t q4_generic(const XT *x, int T, int d, int G, int gs, const Q4Weights &w,
+                             const uint8_t *mask, XT *y, const DecodeScratch &ws, hipStream_t s)
+{
+    constexpr int TT = 4;
+    const int ffn = G * gs;
+    hipError_t e = launch_union(mask, T, G, ws.ulist, ws.meta, s);
+    if (e != hipSuccess) return e;
+    int blocks = (ffn + 3) / 4;
+    if (blocks > 2048) blocks = 2048;
+    launch_timed("gate_up_q4_generic", gate_up_q4_generic<XT, TT>, dim3(blocks), dim3(256), s, x, T, d, G, gs,
+                 w.gate_codes, w.gate_scales, w.up_codes, w.up_scales, mask, (const int32_t *)ws.ulist,
+                 (const int32_t *)ws.meta, ws.act, ffn);
+    down_q4_generic<XT, TT><<<dim3((d + 3) / 4), dim3(256), 0, s>>>(ws.act, ffn, T, d, w.down_codes,
+                                                                  w.down_scales, ws.ulist, ws.meta, y);
+    return hipGetLastError();
+}
+
+bool q4_shape_supported(int d, int gs) { return gs == kQ4Block && d % kQ4Block == 0; }
+
+hipError_t launch_ffn_q4(int dtype, const void *x, int T, int d, int G, int gs, const Q4Weights &w,
+                         const uint8_t *mask, void *y, const DecodeScratch &ws, hipStream_t s)
+{
+    if (dtype == 0)
+        return q4_generic<float>((const float *)x, T, d, G, gs, w, mask, (float *)y, ws, s);
+    const bf16_t *bx = (const bf16_t *)x;
+    bf16_t *by = (bf16_t *)y;
+    if (T == 1 && G <= 256 && (d == 4096 || d == 8192)) {
+        bf16_t *act = reinterpret_cast<bf16_t *>(ws.act);
+        if (d == 4096)
+            launch_timed("gate_up_q4_t1", gate_up_q4_t1<2>, dim3(256), dim3(256), s, bx, G, w.gate_codes,
+                         w.gate_scales, w.up_codes, w.up_scales, mask, act);
+        else
+            launch_timed("gate_up_q4_t1", gate_up_q4_t1<4>, dim3(256), dim3(256), s, bx, G, w.gate_codes,
+                         w.gate_scales, w.up_codes, w.up_scales, mask, act);
+        down_q4_t1<<<dim3(d / 16), dim3(512), 0, s>>>(d, G, w.down_codes, w.down_scales, mask, act, by);
+        return hipGetLastError();
+    }
+    return q4_generic<bf16_t>(bx, T, d, G, gs, w, mask, by, ws, s);
+}
+
+}  // namespace halo

@@ -285,6 +285,69 @@ int halo_ffn_forward(const halo_shape *shape, const void *x, const void *x_pred,
     return e == hipSuccess ? HALO_OK : HALO_ERR_HIP;
 }
 
+int halo_group_sparse_ffn_q4(const halo_shape *shape, const void *x, int32_t T, const void *Wg_codes,
+                             const void *Wg_scales, const void *Wu_codes, const void *Wu_scales,
+                             const void *Wd_codes, const void *Wd_scales, const uint8_t *mask, void *y,
+                             void *workspace, size_t ws_bytes, void *stream)
+{
+    int rc = check_shape(shape);
+    if (rc) return rc;
+    if (!q4_shape_supported(shape->d, shape->group_size)) return HALO_ERR_SHAPE;
+    if (T < 0) return HALO_ERR_ARG;
+    if (T == 0) return HALO_OK;
+    if (!x || !Wg_codes || !Wg_scales || !Wu_codes || !Wu_scales || !Wd_codes || !Wd_scales || !mask || !y)
+        return HALO_ERR_NULL;
+    if (misaligned(x) || misaligned(Wg_codes) || misaligned(Wg_scales) || misaligned(Wu_codes) ||
+        misaligned(Wu_scales) || misaligned(Wd_codes) || misaligned(Wd_scales) || misaligned(y))
+        return HALO_ERR_ARG;
+    if (!workspace || misaligned(workspace)) return HALO_ERR_WORKSPACE;
+    Workspace ws(*shape, T, 0, workspace);
+    if (ws_bytes < ws.bytes) return HALO_ERR_WORKSPACE;
+    const Q4Weights w{(const uint32_t *)Wg_codes, (const bf16_t *)Wg_scales, (const uint32_t *)Wu_codes,
+                      (const bf16_t *)Wu_scales, (const uint32_t *)Wd_codes, (const bf16_t *)Wd_scales};
+    hipError_t e = launch_ffn_q4(shape->dtype, x, T, shape->d, shape->n_groups, shape->group_size, w, mask, y,
+                                 ws.dec, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? HALO_OK : HALO_ERR_HIP;
+}
+
+int halo_ffn_forward_q4(const halo_shape *shape, const void *x, const void *x_pred, int32_t T,
+                        const void *At, const void *Bt, const void *Wg_codes, const void *Wg_scales,
+                        const void *Wu_codes, const void *Wu_scales, const void *Wd_codes,
+                        const void *Wd_scales, int32_t k_keep, const int8_t *prio_dev, int32_t n_dev,
+                        const uint8_t *drop, void *y, float *scores, int32_t *order, int8_t *group_dev,
+                        uint8_t *mask, int32_t *surv_idx, int32_t *n_surv, void *workspace, size_t ws_bytes,
+                        void *stream)
+{
+    int rc = check_shape(shape);
+    if (rc) return rc;
+    if (!q4_shape_supported(shape->d, shape->group_size)) return HALO_ERR_SHAPE;
+    if (T < 0 || k_keep < 0 || k_keep > shape->n_groups || n_dev < 1 || n_dev > 127) return HALO_ERR_ARG;
+    if (T == 0) return HALO_OK;
+    if (!x || !x_pred || !At || !Bt || !Wg_codes || !Wg_scales || !Wu_codes || !Wu_scales || !Wd_codes ||
+        !Wd_scales || !y || (k_keep > 0 && !prio_dev))
+        return HALO_ERR_NULL;
+    if (misaligned(x) || misaligned(x_pred) || misaligned(At) || misaligned(Bt) || misaligned(Wg_codes) ||
+        misaligned(Wg_scales) || misaligned(Wu_codes) || misaligned(Wu_scales) || misaligned(Wd_codes) ||
+        misaligned(Wd_scales) || misaligned(y) || (scores && misaligned(scores)))
+        return HALO_ERR_ARG;
+    if (!workspace || misaligned(workspace)) return HALO_ERR_WORKSPACE;
+    Workspace ws(*shape, T, k_keep, workspace);
+    if (ws_bytes < ws.bytes) return HALO_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    float *sc = scores ? scores : ws.scores;
+    uint8_t *mk = mask ? mask : ws.mask;
+    hipError_t e = launch_predictor(shape->dtype, x_pred, T, shape->d, shape->rank, shape->n_groups, At, Bt,
+                                    ws.h, nullptr, s);
+    if (e != hipSuccess) return HALO_ERR_HIP;
+    e = launch_scores_and_mask(shape->dtype, ws.h, Bt, shape->rank, sc, T, shape->n_groups, k_keep, prio_dev,
+                               n_dev, drop, order, group_dev, mk, surv_idx, n_surv, s);
+    if (e != hipSuccess) return HALO_ERR_HIP;
+    const Q4Weights w{(const uint32_t *)Wg_codes, (const bf16_t *)Wg_scales, (const uint32_t *)Wu_codes,
+                      (const bf16_t *)Wu_scales, (const uint32_t *)Wd_codes, (const bf16_t *)Wd_scales};
+    e = launch_ffn_q4(shape->dtype, x, T, shape->d, shape->n_groups, shape->group_size, w, mk, y, ws.dec, s);
+    return e == hipSuccess ? HALO_OK : HALO_ERR_HIP;
+}
+
 int halo_ffn_forward_ahead(const halo_shape *shape, const void *x, int32_t T, const void *Wg,
                            const void *Wu, const void *Wd, const uint8_t *mask_cur, void *y,
                            const void *x_pred_next, const void *At_next, const void *Bt_next,

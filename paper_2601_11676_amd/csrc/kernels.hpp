@@ -61,6 +61,19 @@ hipError_t launch_ffn_prefill(const bf16_t *x, int T, int d, int G, int gs, cons
                               const bf16_t *Wu, const bf16_t *Wd, const uint8_t *mask, bf16_t *y,
                               const DecodeScratch &ws, hipStream_t s);
 
+// ffn_q4.hip : 4-bit block-quantised weights (blocks of 128 along the reduction dimension)
+struct Q4Weights {
+    const uint32_t *gate_codes;   // [ffn][d/8]
+    const bf16_t *gate_scales;    // [ffn][d/128]
+    const uint32_t *up_codes;
+    const bf16_t *up_scales;
+    const uint32_t *down_codes;   // [G][d][gs/8]
+    const bf16_t *down_scales;    // [G][d]
+};
+bool q4_shape_supported(int d, int gs);
+hipError_t launch_ffn_q4(int dtype, const void *x, int T, int d, int G, int gs, const Q4Weights &w,
+                         const uint8_t *mask, void *y, const DecodeScratch &ws, hipStream_t s);
+
 // profile.hip : optional HIP-event bracket around the dominant FFN kernel
 bool timer_acquire(hipEvent_t *start, hipEvent_t *stop);   // false: not profiling (or pool used up)
 void timer_commit(const char *kernel_name);

@@ -34,6 +34,45 @@ class Layer:
         return self._host
 
 
+class Q4Layer:
+    """One layer with 4-bit block-quantised FFN weights (device tensors in the library's storage
+    format); host() gives the oracle its view: the dequantised float32 matrices."""
+
+    def __init__(self, w: hs.Workload, layer: int = 0, copy: int = 0):
+        self.w = w
+        self.q4 = hs.ffn_weights_q4(w, layer, DEV, copy)
+        self.At, self.Bt = hs.predictor_weights(w, layer, DEV, copy)
+        self._host = None
+
+    def host(self):
+        if self._host is None:
+            q = [t.float().cpu().numpy() if t.dtype == torch.bfloat16 else t.cpu().numpy() for t in self.q4]
+            self._host = (to_np32(self.At), to_np32(self.Bt)) + tuple(ref.dequant_ffn_q4(q))
+        return self._host
+
+
+def gpu_forward_q4(w, layer: Q4Layer, x, K, prio_dev_np, drop_np):
+    """halo_ffn_forward_q4 through the C boundary; returns numpy outputs."""
+    s = shape_of(w)
+    T, G = x.shape[0], w.n_groups
+    ws = torch.empty(H.halo_workspace_bytes(s, T, K), dtype=torch.uint8, device=DEV)
+    pd = torch.from_numpy(np.ascontiguousarray(prio_dev_np)).to(DEV)
+    dr = None if drop_np is None else torch.from_numpy(np.ascontiguousarray(drop_np)).to(DEV)
+    y = torch.full((T, w.d), float("nan"), dtype=w.torch_dtype, device=DEV)
+    scores = torch.empty((T, G), dtype=torch.float32, device=DEV)
+    order = torch.empty((T, G), dtype=torch.int32, device=DEV)
+    group_dev = torch.empty((T, G), dtype=torch.int8, device=DEV)
+    mask = torch.empty((T, G), dtype=torch.uint8, device=DEV)
+    surv_idx = torch.empty((T, max(K, 1)), dtype=torch.int32, device=DEV)[:, :K].contiguous()
+    n_surv = torch.empty((T,), dtype=torch.int32, device=DEV)
+    H.halo_ffn_forward_q4(s, x, layer.At, layer.Bt, layer.q4, K, pd, w.n_dev, dr, y, ws, scores=scores,
+                          order=order, group_dev=group_dev, mask=mask, surv_idx=surv_idx, n_surv=n_surv)
+    torch.cuda.synchronize()
+    return dict(y=to_np32(y).astype(np.float64), scores=scores.cpu().numpy(),
+                order=order.cpu().numpy(), group_dev=group_dev.cpu().numpy(),
+                mask=mask.cpu().numpy(), surv_idx=surv_idx.cpu().numpy(), n_surv=n_surv.cpu().numpy())
+
+
 def gpu_forward(w, layer: Layer, x, K, prio_dev_np, drop_np, x_pred=None):
     """halo_ffn_forward through the C boundary; returns numpy outputs."""
     s = shape_of(w)

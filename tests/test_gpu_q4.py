@@ -1,0 +1,110 @@
+"""GPU parity of the FFN over 4-bit block-quantised weights (paper Sec. V-A) against the CPU
+oracle, whose view of such weights is the dequantised matrices.  Same bars as the other
+parity tests: bit-exact scores / ranking / masks, relative L2 <= 1e-5 (f32) or 2e-2 (bf16)."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+import halo_synth as hs
+import paper_2601_11676_amd as H
+from oracle import ref
+from tests import harness as hz
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+
+
+def _say(msg):
+    print("[case] " + msg, flush=True)
+
+
+def test_q4_generator_bits_identical_on_cpu_and_gpu():
+    _say("q4 generator cpu/gpu")
+    w = hs.small_variant(hs.LLAMA7B_DECODE, 384, 3, 64)
+    for a, b in zip(hs.ffn_weights_q4(w, 1, "cpu"), hs.ffn_weights_q4(w, 1, hz.DEV)):
+        b = b.cpu()
+        if a.dtype == torch.bfloat16:
+            a, b = a.view(torch.int16), b.view(torch.int16)
+        assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("dtype,T,d,G,r", [
+    ("f32", 16, 256, 8, 64),       # the tiny shape
+    ("f32", 5, 640, 7, 72),
+    ("bf16", 3, 384, 9, 40),
+    ("bf16", 1, 1024, 5, 264),     # one token, but not a row length of the streaming path
+    ("bf16", 7, 4096, 6, 256),
+    ("bf16", 40, 512, 70, 64),     # more groups than a wave, many tokens
+])
+def test_q4_plain_path_whole_pass(dtype, T, d, G, r):
+    w = dataclasses.replace(hs.TINY, name="case", d=d, ffn=G * 128, rank=r, T=T, dtype=dtype, seed=12)
+    _say(f"q4 plain {dtype} T={T} d={d} G={G} r={r}")
+    L = hz.Q4Layer(w)
+    x = hs.hidden_states(w, 0, hz.DEV)
+    K = max(1, G // 2)
+    pd = H.halo_build_schedule(K, w.device_plr())
+    drop = hs.drop_outcomes(w, T=T)
+    g = hz.gpu_forward_q4(w, L, x, K, pd, drop)
+    c = hz.oracle_forward(w, L, x, K, pd, drop)
+    hz.assert_parity(g, c, TOL[dtype], "q4 plain")
+
+
+@pytest.mark.parametrize("d,G,K", [(4096, 7, 4), (8192, 6, 6), (4096, 200, 150), (4096, 9, 1)])
+def test_q4_one_token_streaming_path(d, G, K):
+    w = dataclasses.replace(hs.LLAMA7B_DECODE, name="case", d=d, ffn=G * 128, rank=256, seed=22)
+    _say(f"q4 one-token path d={d} G={G} K={K}")
+    L = hz.Q4Layer(w)
+    pd = H.halo_build_schedule(K, w.device_plr())
+    for step in range(3):
+        x = hs.hidden_states(w, step, hz.DEV)
+        drop = hs.drop_outcomes(w, 0, step)
+        g = hz.gpu_forward_q4(w, L, x, K, pd, drop)
+        c = hz.oracle_forward(w, L, x, K, pd, drop)
+        hz.assert_parity(g, c, TOL["bf16"], f"q4 t1 d={d} step {step}")
+
+
+def test_q4_llama7b_decode_full_size_steps():
+    w = hs.LLAMA7B_DECODE
+    _say("q4 llama7b decode full size")
+    L = hz.Q4Layer(w)
+    K = w.k_keep()
+    pd = H.halo_build_schedule(K, w.device_plr())
+    for step in (0, 1, 7, 1023):
+        x = hs.hidden_states(w, step, hz.DEV)
+        drop = hs.drop_outcomes(w, 0, step)
+        g = hz.gpu_forward_q4(w, L, x, K, pd, drop)
+        c = hz.oracle_forward(w, L, x, K, pd, drop)
+        hz.assert_parity(g, c, TOL["bf16"], f"q4 7b step {step}")
+
+
+def test_q4_ffn_entry_point_with_handmade_masks_and_errors():
+    w = dataclasses.replace(hs.LLAMA7B_DECODE, name="case", ffn=10 * 128, rank=64, seed=23)
+    _say("q4 ffn entry point, handmade masks")
+    L = hz.Q4Layer(w)
+    s = hz.shape_of(w)
+    _, _, Wg, Wu, WdT = L.host()
+    ws = torch.empty(H.halo_workspace_bytes(s, 1, 0), dtype=torch.uint8, device=hz.DEV)
+    x = hs.hidden_states(w, 3, hz.DEV)
+    xn = hz.to_np32(x)
+    for bits in ([0] * 10, [1] * 10, [1, 0, 0, 0, 0, 0, 0, 0, 0, 1], [0, 0, 0, 0, 1, 0, 0, 0, 0, 0]):
+        mask_np = np.array([bits], np.uint8)
+        y = torch.full((1, w.d), float("nan"), dtype=torch.bfloat16, device=hz.DEV)
+        H.halo_group_sparse_ffn_q4(s, x, L.q4, torch.from_numpy(mask_np).to(hz.DEV), y, ws)
+        torch.cuda.synchronize()
+        yg = hz.to_np32(y).astype(np.float64)
+        yc = ref.group_sparse_ffn(xn, Wg, Wu, WdT, 128, mask_np)
+        if not any(bits):
+            assert not yg.any()
+        else:
+            assert np.linalg.norm(yg - yc) / np.linalg.norm(yc) <= TOL["bf16"]
+    # a group size other than the quantisation block is refused before anything is enqueued
+    bad = H.Shape(w.d, 20 * 64, 64, w.rank, "bf16")
+    y = torch.zeros((1, w.d), dtype=torch.bfloat16, device=hz.DEV)
+    with pytest.raises(H.HaloError):
+        H.halo_group_sparse_ffn_q4(bad, x, L.q4, torch.zeros((1, 20), dtype=torch.uint8, device=hz.DEV), y, ws)
+    # no tokens: nothing to do
+    H.halo_group_sparse_ffn_q4(s, x[:0], L.q4, torch.zeros((0, 10), dtype=torch.uint8, device=hz.DEV), y[:0], ws)
+    torch.cuda.synchronize()
