@@ -71,6 +71,8 @@ def main():
     ap.add_argument("--serial", action="store_true",
                     help="predictor, mask and FFN back to back on one stream (halo_ffn_forward) instead "
                          "of the predictor running one step ahead beside the FFN (halo_ffn_forward_ahead)")
+    ap.add_argument("--q4", action="store_true",
+                    help="4-bit block-quantised FFN weights (halo_ffn_forward_q4 / _ahead_q4) instead of bf16")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
     ap.add_argument("--cpu-steps", type=int, default=64)
     ap.add_argument("--time-every", type=int, default=4,
@@ -116,8 +118,11 @@ def main():
     # ---- resident inputs -------------------------------------------------------------
     copies = []
     for c in range(NC):
-        Wg, Wu, WdT = hs.ffn_weights(w, 0, dev, copy=c)
         At, Bt = hs.predictor_weights(w, 0, dev, copy=c)
+        if args.q4:
+            copies.append((At, Bt, hs.ffn_weights_q4(w, 0, dev, copy=c)))
+            continue
+        Wg, Wu, WdT = hs.ffn_weights(w, 0, dev, copy=c)
         copies.append((At, Bt, Wg, Wu, H.pack_down_proj(WdT, w.group_size)))   # library layout
         if c == 0:
             WdT0 = WdT                  # neuron-major original of copy 0, for the oracle leg
@@ -134,6 +139,17 @@ def main():
     torch.cuda.synchronize()
 
     st = torch.cuda.Stream()               # every library call below goes to this stream (default priority)
+
+    def step_serial_q4(s):
+        At, Bt, q4 = copies[s % NC]
+        H.halo_ffn_forward_q4(shape, xs[s], At, Bt, q4, k_keep, prio_dev, w.n_dev, drops[s], ys[s], ws,
+                              mask=masks[s], stream=st)
+
+    def step_ahead_q4(s):
+        q4 = copies[s % NC][2]
+        At, Bt = copies[(s + 1) % NC][:2]
+        H.halo_ffn_forward_ahead_q4(shape, xs[s], q4, masks[s], ys[s], xs[s + 1], At, Bt, k_keep, prio_dev,
+                                    w.n_dev, drops[s + 1], masks[s + 1], ws, stream=st)
 
     def step_serial(s):
         At, Bt, Wg, Wu, Wd = copies[s % NC]
@@ -153,6 +169,8 @@ def main():
     # marshal every step's call once: the timed and the profiled loops then cost a few
     # microseconds of host time per step, so the GPU is never left waiting for Python
     make = step_serial if args.serial else step_ahead
+    if args.q4:
+        make = step_serial_q4 if args.serial else step_ahead_q4
     calls = [H.prepared(make, s) for s in range(W + K)]
 
     def step(s):
@@ -160,7 +178,7 @@ def main():
 
     # ---- warm-up -----------------------------------------------------------------------
     torch.cuda.synchronize()
-    step_serial(0)                          # also provides masks[0] for the overlapped form
+    (step_serial_q4 if args.q4 else step_serial)(0)   # also provides masks[0] for the overlapped form
     for s in range(W):
         step(s)
     torch.cuda.synchronize()
@@ -219,6 +237,8 @@ def main():
     n_surv = mask_np.sum(axis=2)                          # [K][T]
     union = mask_np.any(axis=1).sum(axis=1)               # [K] groups read per step
     group_bytes = w.group_size * d * esz                  # one projection of one group
+    if args.q4:                                           # codes + one bf16 scale per 128 elements
+        group_bytes = w.group_size * d // 2 + w.group_size * d // hs.Q4_BLOCK * 2
     gate_up_bytes = float(union.sum()) * 2 * group_bytes  # over the K launches
     ffn_bytes = float(union.sum()) * 3 * group_bytes
     pred_bytes = K * (w.rank * d + G * w.rank) * esz
@@ -226,7 +246,7 @@ def main():
     timed_union = union[::args.time_every][:kern_n]
     gate_up_bytes = float(timed_union.sum()) * 2 * group_bytes
     achieved = gate_up_bytes / (kern_ms * 1e-3) / 1e9 if kern_ms > 0 else 0.0
-    traffic = read_traffic(kern_name, w.name)
+    traffic = read_traffic(kern_name, w.name + ("_q4" if args.q4 else ""))
     if kern_name.endswith("_pf"):
         # many tokens: the dominant kernel is a dense contraction on the matrix cores
         flops = float(n_surv[::args.time_every][:kern_n].sum()) * w.group_size * d * 2 * 2   # gate and up, 2 flop per MAC
@@ -242,8 +262,8 @@ def main():
                 "bytes_per_launch": gate_up_bytes / max(kern_n, 1)}
 
     out = {
-        "metric": "FFN tokens/s (decode), LLaMA-7B shape, 50% groups kept" if w.name == "llama7b_decode"
-                  else f"FFN tokens/s, {w.name}, keep {w.keep[0]}",
+        "metric": ("FFN tokens/s (decode), LLaMA-7B shape, 50% groups kept" if w.name == "llama7b_decode"
+                   else f"FFN tokens/s, {w.name}, keep {w.keep[0]}") + (", 4-bit weights" if args.q4 else ""),
         "value": K * T / elapsed,
         "unit": "tokens/s",
         "n_gpus": 1,
@@ -253,9 +273,9 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": w.dtype,
+        "dtype": w.dtype + (" activations, 4-bit block-quantised FFN weights" if args.q4 else ""),
         "data": "synthetic",
-        "config": {"workload": w.name, "d": d, "ffn": w.ffn, "n_groups": G, "group_size": w.group_size,
+        "config": {"workload": w.name + ("_q4" if args.q4 else ""), "d": d, "ffn": w.ffn, "n_groups": G, "group_size": w.group_size,
                    "rank": w.rank, "tokens_per_step": T, "k_keep": k_keep, "n_dev": w.n_dev,
                    "plr": [float(v) for v in w.device_plr()], "seed": w.seed, "weight_copies": NC,
                    "graph": use_graph, "predictor": "serial" if args.serial else "one step ahead, beside the FFN"},
@@ -273,7 +293,12 @@ def main():
     # ---- CPU oracle on a bounded sample of the same steps (rank 0, N=1) -----------------
     if not args.no_cpu:
         from oracle import ref
-        At, Bt, Wg, Wu, WdT = (t.float().cpu().numpy() for t in (*copies[0][:4], WdT0))
+        if args.q4:
+            At, Bt = (t.float().cpu().numpy() for t in copies[0][:2])
+            Wg, Wu, WdT = ref.dequant_ffn_q4([t.float().cpu().numpy() if t.dtype == torch.bfloat16
+                                              else t.cpu().numpy() for t in copies[0][2]])
+        else:
+            At, Bt, Wg, Wu, WdT = (t.float().cpu().numpy() for t in (*copies[0][:4], WdT0))
         sample = [s for s in range(W, W + K) if s % NC == 0][: max(1, min(args.cpu_steps, 64 // T))]
         if not sample:
             sample = [W]

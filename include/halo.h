@@ -238,6 +238,18 @@ int halo_ffn_forward_q4(const halo_shape *shape, const void *x, const void *x_pr
                         uint8_t *mask, int32_t *surv_idx, int32_t *n_surv, void *workspace, size_t ws_bytes,
                         void *stream);
 
+/* halo_ffn_forward_ahead over 4-bit weights: same contract, same weight arguments as
+ * halo_group_sparse_ffn_q4.  The prediction rides in spare workgroups for one bf16 token with
+ * d in {4096, 8192} and n_groups <= 256; otherwise it is enqueued after the FFN. */
+int halo_ffn_forward_ahead_q4(const halo_shape *shape, const void *x, int32_t T, const void *Wg_codes,
+                              const void *Wg_scales, const void *Wu_codes, const void *Wu_scales,
+                              const void *Wd_codes, const void *Wd_scales, const uint8_t *mask_cur, void *y,
+                              const void *x_pred_next, const void *At_next, const void *Bt_next,
+                              int32_t k_keep, const int8_t *prio_dev, int32_t n_dev,
+                              const uint8_t *drop_next, float *scores_next, int32_t *order_next,
+                              int8_t *group_dev_next, uint8_t *mask_next, int32_t *surv_idx_next,
+                              int32_t *n_surv_next, void *workspace, size_t ws_bytes, void *stream);
+
 /*
  * Benchmark aid (not part of the paper's method).  Between halo_profile_begin and
  * halo_profile_end every call of halo_group_sparse_ffn / halo_ffn_forward brackets the

@@ -85,6 +85,9 @@ def load_library():
     lib.halo_ffn_forward_q4.restype = C.c_int
     lib.halo_ffn_forward_q4.argtypes = [ps, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, i32, vp,
                                         vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.halo_ffn_forward_ahead_q4.restype = C.c_int
+    lib.halo_ffn_forward_ahead_q4.argtypes = [ps, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp,
+                                              i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.halo_profile_begin.restype = C.c_int
     lib.halo_profile_begin.argtypes = [i32, i32]
     lib.halo_profile_end.restype = C.c_int
@@ -236,6 +239,19 @@ def halo_ffn_forward_q4(shape: Shape, x, At, Bt, q4, k_keep: int, prio_dev, n_de
         _ptr(prio_dev), int(n_dev), _ptr(drop), _ptr(y), _ptr(scores), _ptr(order), _ptr(group_dev),
         _ptr(mask), _ptr(surv_idx), _ptr(n_surv), _ptr(workspace), workspace.numel(), _stream(stream))
     _check("halo_ffn_forward_q4", rc)
+
+
+def halo_ffn_forward_ahead_q4(shape: Shape, x, q4, mask_cur, y, x_pred_next, At_next, Bt_next, k_keep: int,
+                              prio_dev, n_dev: int, drop_next, mask_next, workspace, scores_next=None,
+                              order_next=None, group_dev_next=None, surv_idx_next=None, n_surv_next=None,
+                              stream=None) -> None:
+    T = x.shape[0]
+    rc = load_library().halo_ffn_forward_ahead_q4(
+        C.byref(shape.c), _ptr(x), T, *[_ptr(t) for t in q4], _ptr(mask_cur), _ptr(y), _ptr(x_pred_next),
+        _ptr(At_next), _ptr(Bt_next), int(k_keep), _ptr(prio_dev), int(n_dev), _ptr(drop_next),
+        _ptr(scores_next), _ptr(order_next), _ptr(group_dev_next), _ptr(mask_next), _ptr(surv_idx_next),
+        _ptr(n_surv_next), _ptr(workspace), workspace.numel(), _stream(stream))
+    _check("halo_ffn_forward_ahead_q4", rc)
 
 
 def prepared(fn, *args, **kwargs):

@@ -117,6 +117,33 @@ __device__ __forceinline__ float dot_order64(const XT *__restrict__ xp, const WT
     return wave_sum(p);
 }
 
+// The same dot product (same element-to-lane map, same order, same result bits) for bf16
+// operands of a length known at compile time: every piece of both operands is requested before
+// the first multiply, so the wave pays one memory latency instead of one per 512 elements.
+template <int N>
+__device__ __forceinline__ float dot_order64_fixed(const bf16_t *__restrict__ xp, const bf16_t *__restrict__ wp,
+                                                   int lane)
+{
+    static_assert(N % 512 == 0, "whole 16-byte pieces for all 64 lanes");
+    constexpr int NC = N / 512;
+    u32x4 xv[NC], wv[NC];
+#pragma unroll
+    for (int k = 0; k < NC; ++k) {
+        xv[k] = *reinterpret_cast<const u32x4 *>(xp + (k * kWave + lane) * 8);
+        wv[k] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(wp + (k * kWave + lane) * 8));
+    }
+    float p = 0.0f;
+#pragma unroll
+    for (int k = 0; k < NC; ++k) {
+        float a[8], b[8];
+        unpack8(xv[k], a);
+        unpack8(wv[k], b);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) p = __builtin_fmaf(a[e], b[e], p);
+    }
+    return wave_sum(p);
+}
+
 // Wave-wide sum through the DPP cross-lane paths (no LDS traffic); result is uniform.
 // Used where the summation order is free (FFN dot products), not by the predictor.
 template <int CTRL>
@@ -151,6 +178,14 @@ __device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float acc)
 __device__ __forceinline__ float silu_mul(float gate, float up)
 {
     return gate / (1.0f + expf(-gate)) * up;
+}
+
+// The same with the hardware exponential and reciprocal (each within about one unit in the
+// last place of float): for results that are rounded to bf16 right afterwards.
+__device__ __forceinline__ float silu_mul_fast(float gate, float up)
+{
+    const float e = __builtin_amdgcn_exp2f(gate * -1.44269504088896341f);
+    return gate * __builtin_amdgcn_rcpf(1.0f + e) * up;
 }
 
 }  // namespace halo

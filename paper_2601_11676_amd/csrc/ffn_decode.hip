@@ -254,7 +254,7 @@ __global__ __launch_bounds__(256) void gate_up_pred_t1(
         const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
         const int j = blockIdx.x * 4 + wave;
         if (j < r) {
-            const float p = dot_order64(x_next, At_next + (size_t)j * (NCH * 512), NCH * 512, lane);
+            const float p = dot_order64_fixed<NCH * 512>(x_next, At_next + (size_t)j * (NCH * 512), lane);
             if (lane == 0) h_next[j] = p > 0.0f ? p : 0.0f;
         }
         return;
@@ -342,21 +342,6 @@ __global__ __launch_bounds__(RQ * 128) void down_t1(int d, int G, const bf16_t *
     down_t1_body<RQ>(sh, d, G, Wd, mask, act, y, blockIdx.x);
 }
 
-// Arguments of the prediction for the next block that rides along with this block's kernels.
-struct AheadDev {
-    const float *h;          // [r] first-layer output, written by gate_up_pred_t1
-    const bf16_t *Bt;        // [G][r]
-    int r, K, n_dev;
-    const int8_t *prio_dev;
-    const uint8_t *drop;     // [n_dev] or nullptr
-    float *scores;           // [G]
-    int32_t *order;
-    int8_t *group_dev;
-    uint8_t *mask;
-    int32_t *surv_idx;
-    int32_t *n_surv;
-};
-
 // The down projection, with the second predictor layer + ranking + mask of the NEXT block in
 // workgroup 0 (it is the longest dependent chain, so it is dispatched first).
 template <int RQ>
@@ -418,8 +403,7 @@ static hipError_t decode_t1(const bf16_t *x, int G, int gs, const bf16_t *Wg, co
     launch_timed("gate_up_pred_t1", gate_up_pred_t1<NCH>, dim3(kGateUpBlocks + n_pred), dim3(256), s, x, G,
                  gs, Wg, Wu, mask, act, (const bf16_t *)ah->x_next, (const bf16_t *)ah->At, ah->r, ah->h,
                  n_pred);
-    AheadDev nx{ah->h, (const bf16_t *)ah->Bt, ah->r, ah->K, ah->n_dev, ah->prio_dev, ah->drop,
-                ah->scores, ah->order, ah->group_dev, ah->mask, ah->surv_idx, ah->n_surv};
+    const AheadDev nx = ahead_dev(*ah);
     down_mask_t1<RQ><<<dim3(257), dim3(RQ * 128), 0, s>>>(d, G, Wd, mask, act, y, nx);
     return hipGetLastError();
 }

@@ -16,15 +16,23 @@
 // and the constant offset is taken out once per 32 elements: sum (c-8) x = sum (128+c) x -
 // 136 sum x.  Any other shape goes through plain kernels that dequantise element by element.
 #include "kernels.hpp"
+#include "mask_device.hpp"
 #include "mask_words.hpp"
 
 namespace halo {
 
 constexpr int kQ4Block = 128;
 
+// codes 2i and 2i+1 of a word as the packed bf16 pair (128 + c, 128 + c): a shift and one
+// and-or.  The three-operand form is written out because the compiler otherwise emits the
+// "and" and the "or" separately (its two constants cannot both be literals of one instruction;
+// here they sit in registers).
 __device__ __forceinline__ uint32_t q4_pair(uint32_t w, int i)
 {
-    return ((w >> (4 * i)) & 0x000F000Fu) | 0x43004300u;
+    uint32_t r;
+    const uint32_t sh = i ? w >> (4 * i) : w;
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(sh), "v"(0x000F000Fu), "v"(0x43004300u));
+    return r;
 }
 
 // sum over the 32 elements of one 16-byte code piece of (128 + c) * x, x as 16 packed bf16 pairs
@@ -64,20 +72,42 @@ __device__ __forceinline__ float bf16_bits_to_float(uint16_t b) { return __uint_
 // gate/up: one wave per neuron at a time, NB neurons requested together.  A lane owns the 32
 // elements 2048 h + 32 lane .. + 31 of every half h: one 16-byte code piece per matrix row and
 // half, one scale (block 16 h + lane / 4), and the matching 64 bytes of x kept in registers.
+// Eight waves per workgroup, two per SIMD: unpacking the codes costs about three vector
+// instructions per two weights, which is not negligible beside the memory time of a quarter
+// of the bf16 bytes, so one wave's arithmetic has to overlap another's memory wait.
+constexpr int kQ4GateUpThreads = 512;
+constexpr int kQ4GateUpBlocks = 256;      // workgroups that do gate/up work (one per compute unit)
+
 template <int NH>
-__global__ __launch_bounds__(256) void gate_up_q4_t1(
+__global__ __launch_bounds__(kQ4GateUpThreads, (NH == 2 ? 4 : 2)) void gate_up_q4_t1(
     const bf16_t *__restrict__ x, int G, const uint32_t *__restrict__ Gq, const bf16_t *__restrict__ Gs,
     const uint32_t *__restrict__ Uq, const bf16_t *__restrict__ Us, const uint8_t *__restrict__ mask,
-    bf16_t *__restrict__ act)
+    bf16_t *__restrict__ act, const bf16_t *__restrict__ x_next, const bf16_t *__restrict__ At_next, int r,
+    float *__restrict__ h_next, int n_pred)
 {
-    constexpr int d = NH * 2048, gs = 128, NB = 12 / NH;
+    constexpr int d = NH * 2048, gs = 128, NB = NH == 2 ? 3 : 2, WPB = kQ4GateUpThreads / 64;
     constexpr int kWords = d / 8, kBlocks = d / kQ4Block;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    if ((int)blockIdx.x < n_pred) {
+        // the first predictor layer of the NEXT block rides along (paper Sec. III-B.3, Pred beside
+        // Load/Comp, one layer ahead): one row of At per wave, h_next = ReLU(x_next A)
+        const int j = blockIdx.x * WPB + wave;
+        if (j < r) {
+            const float p = dot_order64_fixed<d>(x_next, At_next + (size_t)j * d, lane);
+            if (lane == 0) h_next[j] = p > 0.0f ? p : 0.0f;
+        }
+        return;
+    }
     const MaskWords mw = load_mask_words(mask, G, lane);
-    const long long total = (long long)mw.count * gs;
-    const int nw = gridDim.x * 4, w = blockIdx.x * 4 + wave;
-    const int n0 = (int)(total * w / nw), n1 = (int)(total * (w + 1) / nw);
+    // contiguous runs of the surviving neurons, wave by wave (lengths differ by at most one);
+    // kQ4GateUpBlocks * WPB is a power of two, and a run is far shorter than a group, so it
+    // touches at most two groups: the group ids are looked up twice, not once per neuron
+    constexpr int nw = kQ4GateUpBlocks * WPB;
+    const int total = mw.count * gs, w = (blockIdx.x - n_pred) * WPB + wave;
+    const int n0 = (int)((unsigned)total * (unsigned)w / nw), n1 = (int)((unsigned)total * (unsigned)(w + 1) / nw);
     if (n0 >= n1) return;
+    const int u_first = n0 / gs, u_last = (n1 - 1) / gs;
+    const int g_first = nth_group(mw, u_first, lane), g_last = nth_group(mw, u_last, lane);
     u32x4 xr[NH][4];
     float xs[NH];
 #pragma unroll
@@ -93,7 +123,7 @@ __global__ __launch_bounds__(256) void gate_up_q4_t1(
         for (int i = 0; i < NB; ++i) {
             const int n = nb + i < n1 ? nb + i : n1 - 1;            // past the end: an in-range duplicate
             const int u = n / gs;
-            const size_t row = (size_t)nth_group(mw, u, lane) * gs + (n - u * gs);
+            const size_t row = (size_t)(u == u_first ? g_first : g_last) * gs + (n - u * gs);
 #pragma unroll
             for (int h = 0; h < NH; ++h) {
                 cg[i][h] = __builtin_nontemporal_load(
@@ -110,14 +140,15 @@ __global__ __launch_bounds__(256) void gate_up_q4_t1(
         }
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
+            if (nb + i >= n1) break;                                // uniform: duplicates cost no arithmetic
             float ag = 0.0f, au = 0.0f;
 #pragma unroll
             for (int h = 0; h < NH; ++h) {
                 ag = __builtin_fmaf(bf16_bits_to_float(sg[i][h]), q4_dot32(cg[i][h], xr[h]) - xs[h], ag);
                 au = __builtin_fmaf(bf16_bits_to_float(su[i][h]), q4_dot32(cu[i][h], xr[h]) - xs[h], au);
             }
-            const float v = silu_mul(wave_sum_fast(ag), wave_sum_fast(au));
-            if (lane == 0 && nb + i < n1) act[nb + i] = f32_to_bf16(v);
+            const float v = silu_mul_fast(wave_sum_fast(ag), wave_sum_fast(au));
+            if (lane == 0) act[nb + i] = f32_to_bf16(v);
         }
     }
 }
@@ -135,17 +166,31 @@ struct DownQ4Shared {
     float part[8][16];
 };
 
-__global__ __launch_bounds__(512) void down_q4_t1(int d, int G, const uint32_t *__restrict__ Dq,
-                                                   const bf16_t *__restrict__ Ds,
-                                                   const uint8_t *__restrict__ mask,
-                                                   const bf16_t *__restrict__ act, bf16_t *__restrict__ y)
+// With ahead != 0 workgroup 0 is the mask workgroup of the NEXT block (second predictor layer,
+// ranking, mask); it is dispatched first because it is the longest dependent chain.  A
+// workgroup is one or the other, so the two LDS layouts share their bytes and two workgroups
+// fit a compute unit (the mask workgroup must run beside a down-projection one, not after).
+__global__ __launch_bounds__(512, 4) void down_q4_t1(int d, int G, const uint32_t *__restrict__ Dq,
+                                                      const bf16_t *__restrict__ Ds,
+                                                      const uint8_t *__restrict__ mask,
+                                                      const bf16_t *__restrict__ act, bf16_t *__restrict__ y,
+                                                      int ahead, AheadDev nx)
 {
     constexpr int gs = 128, kB = kDownQ4Batch;
-    __shared__ DownQ4Shared sh;
+    constexpr size_t kLds = sizeof(DownQ4Shared) > sizeof(MaskShared) ? sizeof(DownQ4Shared) : sizeof(MaskShared);
+    __shared__ __attribute__((aligned(16))) unsigned char lds[kLds];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    if (ahead && blockIdx.x == 0) {
+        mask_scores_block<512, bf16_t, true>(*reinterpret_cast<MaskShared *>(lds), tid, nx.h, nx.Bt, nx.r,
+                                             nx.scores, G, nx.K, nx.prio_dev, nx.n_dev, nx.drop, nx.order,
+                                             nx.group_dev, nx.mask, nx.surv_idx, nx.n_surv);
+        return;
+    }
+    DownQ4Shared &sh = *reinterpret_cast<DownQ4Shared *>(lds);
+    const int vblock = blockIdx.x - (ahead ? 1 : 0);
     const MaskWords mw = load_mask_words(mask, G, lane);
     const int count = mw.count;
-    const int j = blockIdx.x * 16 + (lane >> 2);                   // output row of this lane
+    const int j = vblock * 16 + (lane >> 2);                       // output row of this lane
     const int p = lane & 3;                                        // which 32 neurons of the group
     if (count == 0) {                                              // uniform
         if (wave == 0 && p == 0) y[j] = 0;
@@ -212,7 +257,7 @@ __global__ __launch_bounds__(512) void down_q4_t1(int d, int G, const uint32_t *
         float v = 0.0f;
 #pragma unroll
         for (int k = 0; k < 8; ++k) v += sh.part[k][lane];
-        y[blockIdx.x * 16 + lane] = f32_to_bf16(v);
+        y[vblock * 16 + lane] = f32_to_bf16(v);
     }
 }
 
@@ -339,21 +384,32 @@ static hipError_t q4_generic(const XT *x, int T, int d, int G, int gs, const Q4W
 bool q4_shape_supported(int d, int gs) { return gs == kQ4Block && d % kQ4Block == 0; }
 
 hipError_t launch_ffn_q4(int dtype, const void *x, int T, int d, int G, int gs, const Q4Weights &w,
-                         const uint8_t *mask, void *y, const DecodeScratch &ws, hipStream_t s)
+                         const uint8_t *mask, void *y, const DecodeScratch &ws, hipStream_t s,
+                         const AheadArgs *ahead, bool *ahead_fused)
 {
+    if (ahead_fused) *ahead_fused = false;
     if (dtype == 0)
         return q4_generic<float>((const float *)x, T, d, G, gs, w, mask, (float *)y, ws, s);
     const bf16_t *bx = (const bf16_t *)x;
     bf16_t *by = (bf16_t *)y;
     if (T == 1 && G <= 256 && (d == 4096 || d == 8192)) {
         bf16_t *act = reinterpret_cast<bf16_t *>(ws.act);
+        const AheadArgs *ah = (ahead && ahead_fused) ? ahead : nullptr;
+        if (ah) *ahead_fused = true;
+        const int n_pred = ah ? (ah->r + 7) / 8 : 0;
+        const bf16_t *xn = ah ? (const bf16_t *)ah->x_next : nullptr, *an = ah ? (const bf16_t *)ah->At : nullptr;
+        float *hn = ah ? ah->h : nullptr;
+        const int r = ah ? ah->r : 0;
         if (d == 4096)
-            launch_timed("gate_up_q4_t1", gate_up_q4_t1<2>, dim3(256), dim3(256), s, bx, G, w.gate_codes,
-                         w.gate_scales, w.up_codes, w.up_scales, mask, act);
+            launch_timed("gate_up_q4_t1", gate_up_q4_t1<2>, dim3(kQ4GateUpBlocks + n_pred), dim3(kQ4GateUpThreads), s, bx, G, w.gate_codes,
+                         w.gate_scales, w.up_codes, w.up_scales, mask, act, xn, an, r, hn, n_pred);
         else
-            launch_timed("gate_up_q4_t1", gate_up_q4_t1<4>, dim3(256), dim3(256), s, bx, G, w.gate_codes,
-                         w.gate_scales, w.up_codes, w.up_scales, mask, act);
-        down_q4_t1<<<dim3(d / 16), dim3(512), 0, s>>>(d, G, w.down_codes, w.down_scales, mask, act, by);
+            launch_timed("gate_up_q4_t1", gate_up_q4_t1<4>, dim3(kQ4GateUpBlocks + n_pred), dim3(kQ4GateUpThreads), s, bx, G, w.gate_codes,
+                         w.gate_scales, w.up_codes, w.up_scales, mask, act, xn, an, r, hn, n_pred);
+        AheadDev nx{};
+        if (ah) nx = ahead_dev(*ah);
+        down_q4_t1<<<dim3(d / 16 + (ah ? 1 : 0)), dim3(512), 0, s>>>(d, G, w.down_codes, w.down_scales, mask, act,
+                                                                     by, ah ? 1 : 0, nx);
         return hipGetLastError();
     }
     return q4_generic<bf16_t>(bx, T, d, G, gs, w, mask, by, ws, s);

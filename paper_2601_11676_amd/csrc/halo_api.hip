@@ -348,6 +348,54 @@ int halo_ffn_forward_q4(const halo_shape *shape, const void *x, const void *x_pr
     return e == hipSuccess ? HALO_OK : HALO_ERR_HIP;
 }
 
+int halo_ffn_forward_ahead_q4(const halo_shape *shape, const void *x, int32_t T, const void *Wg_codes,
+                              const void *Wg_scales, const void *Wu_codes, const void *Wu_scales,
+                              const void *Wd_codes, const void *Wd_scales, const uint8_t *mask_cur, void *y,
+                              const void *x_pred_next, const void *At_next, const void *Bt_next,
+                              int32_t k_keep, const int8_t *prio_dev, int32_t n_dev,
+                              const uint8_t *drop_next, float *scores_next, int32_t *order_next,
+                              int8_t *group_dev_next, uint8_t *mask_next, int32_t *surv_idx_next,
+                              int32_t *n_surv_next, void *workspace, size_t ws_bytes, void *stream)
+{
+    int rc = check_shape(shape);
+    if (rc) return rc;
+    if (!q4_shape_supported(shape->d, shape->group_size)) return HALO_ERR_SHAPE;
+    if (T < 0 || k_keep < 0 || k_keep > shape->n_groups || n_dev < 1 || n_dev > 127) return HALO_ERR_ARG;
+    if (T == 0) return HALO_OK;
+    if (!x || !Wg_codes || !Wg_scales || !Wu_codes || !Wu_scales || !Wd_codes || !Wd_scales || !mask_cur ||
+        !y || !x_pred_next || !At_next || !Bt_next || !mask_next || (k_keep > 0 && !prio_dev))
+        return HALO_ERR_NULL;
+    if (mask_next == mask_cur || y == x_pred_next) return HALO_ERR_ARG;
+    if (misaligned(x) || misaligned(Wg_codes) || misaligned(Wg_scales) || misaligned(Wu_codes) ||
+        misaligned(Wu_scales) || misaligned(Wd_codes) || misaligned(Wd_scales) || misaligned(y) ||
+        misaligned(x_pred_next) || misaligned(At_next) || misaligned(Bt_next) ||
+        (scores_next && misaligned(scores_next)))
+        return HALO_ERR_ARG;
+    if (!workspace || misaligned(workspace)) return HALO_ERR_WORKSPACE;
+    Workspace ws(*shape, T, k_keep, workspace);
+    if (ws_bytes < ws.bytes) return HALO_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    float *sc = scores_next ? scores_next : ws.scores;
+    AheadArgs ah{x_pred_next, At_next, Bt_next, shape->rank, k_keep, n_dev, prio_dev, drop_next, ws.h, sc,
+                 order_next, group_dev_next, mask_next, surv_idx_next, n_surv_next};
+    const Q4Weights w{(const uint32_t *)Wg_codes, (const bf16_t *)Wg_scales, (const uint32_t *)Wu_codes,
+                      (const bf16_t *)Wu_scales, (const uint32_t *)Wd_codes, (const bf16_t *)Wd_scales};
+    bool fused = false;
+    hipError_t e = launch_ffn_q4(shape->dtype, x, T, shape->d, shape->n_groups, shape->group_size, w, mask_cur,
+                                 y, ws.dec, s, &ah, &fused);
+    if (e != hipSuccess) return HALO_ERR_HIP;
+    if (!fused) {
+        e = launch_predictor(shape->dtype, x_pred_next, T, shape->d, shape->rank, shape->n_groups, At_next,
+                             Bt_next, ws.h, nullptr, s);
+        if (e != hipSuccess) return HALO_ERR_HIP;
+        e = launch_scores_and_mask(shape->dtype, ws.h, Bt_next, shape->rank, sc, T, shape->n_groups, k_keep,
+                                   prio_dev, n_dev, drop_next, order_next, group_dev_next, mask_next,
+                                   surv_idx_next, n_surv_next, s);
+        if (e != hipSuccess) return HALO_ERR_HIP;
+    }
+    return HALO_OK;
+}
+
 int halo_ffn_forward_ahead(const halo_shape *shape, const void *x, int32_t T, const void *Wg,
                            const void *Wu, const void *Wd, const uint8_t *mask_cur, void *y,
                            const void *x_pred_next, const void *At_next, const void *Bt_next,

@@ -42,6 +42,25 @@ struct AheadArgs {
     uint8_t *mask;
     int32_t *surv_idx, *n_surv;
 };
+// Arguments of the prediction for the next block that rides along with this block's kernels.
+struct AheadDev {
+    const float *h;          // [r] first-layer output, written by the gate/up launch
+    const bf16_t *Bt;        // [G][r]
+    int r, K, n_dev;
+    const int8_t *prio_dev;
+    const uint8_t *drop;     // [n_dev] or nullptr
+    float *scores;           // [G]
+    int32_t *order;
+    int8_t *group_dev;
+    uint8_t *mask;
+    int32_t *surv_idx;
+    int32_t *n_surv;
+};
+inline AheadDev ahead_dev(const AheadArgs &a)
+{
+    return AheadDev{a.h, (const bf16_t *)a.Bt, a.r, a.K, a.n_dev, a.prio_dev, a.drop, a.scores, a.order,
+                    a.group_dev, a.mask, a.surv_idx, a.n_surv};
+}
 hipError_t launch_ffn_decode(int dtype, const void *x, int T, int d, int G, int gs, const void *Wg,
                              const void *Wu, const void *Wd, const uint8_t *mask, void *y,
                              const DecodeScratch &ws, hipStream_t s, const AheadArgs *ahead = nullptr,
@@ -72,7 +91,8 @@ struct Q4Weights {
 };
 bool q4_shape_supported(int d, int gs);
 hipError_t launch_ffn_q4(int dtype, const void *x, int T, int d, int G, int gs, const Q4Weights &w,
-                         const uint8_t *mask, void *y, const DecodeScratch &ws, hipStream_t s);
+                         const uint8_t *mask, void *y, const DecodeScratch &ws, hipStream_t s,
+                         const AheadArgs *ahead = nullptr, bool *ahead_fused = nullptr);
 
 // profile.hip : optional HIP-event bracket around the dominant FFN kernel
 bool timer_acquire(hipEvent_t *start, hipEvent_t *stop);   // false: not profiling (or pool used up)

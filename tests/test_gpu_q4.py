@@ -108,3 +108,47 @@ def test_q4_ffn_entry_point_with_handmade_masks_and_errors():
     # no tokens: nothing to do
     H.halo_group_sparse_ffn_q4(s, x[:0], L.q4, torch.zeros((0, 10), dtype=torch.uint8, device=hz.DEV), y[:0], ws)
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("d,T", [(4096, 1), (8192, 1), (512, 3)])
+def test_q4_one_step_ahead_overlap_equals_the_serial_pass(d, T):
+    # predictor + mask of step s+1 beside (or, for shapes without spare workgroups, after) the FFN of step s
+    w = dataclasses.replace(hs.LLAMA7B_DECODE, name="case", d=d, ffn=20 * 128, T=T, seed=9)
+    _say(f"halo_ffn_forward_ahead_q4 vs halo_ffn_forward_q4 d={d} T={T}")
+    s = hz.shape_of(w)
+    L = hz.Q4Layer(w)
+    G, K, n = w.n_groups, 10, 5
+    pd = H.halo_build_schedule(K, w.device_plr())
+    xs = [hs.hidden_states(w, i, hz.DEV) for i in range(n + 1)]
+    drops = [hs.drop_outcomes(w, 0, i) for i in range(n + 1)]
+    serial = [hz.gpu_forward_q4(w, L, xs[i], K, pd, drops[i]) for i in range(n)]
+    ws = torch.empty(H.halo_workspace_bytes(s, T, K), dtype=torch.uint8, device=hz.DEV)
+    pdd = torch.from_numpy(pd).to(hz.DEV)
+    dd = [torch.from_numpy(x).to(hz.DEV) for x in drops]
+    masks = torch.zeros((n + 1, T, G), dtype=torch.uint8, device=hz.DEV)
+    ys = torch.zeros((n, T, w.d), dtype=torch.bfloat16, device=hz.DEV)
+    sc = torch.empty((T, G), dtype=torch.float32, device=hz.DEV)
+    H.halo_predict_scores(s, xs[0], L.At, L.Bt, sc, ws)
+    H.halo_build_group_mask(sc, K, pdd, w.n_dev, dd[0], masks[0])
+
+    def run(ys_, masks_):
+        for i in range(n):
+            H.halo_ffn_forward_ahead_q4(s, xs[i], L.q4, masks_[i], ys_[i], xs[i + 1], L.At, L.Bt, K, pdd,
+                                        w.n_dev, dd[i + 1], masks_[i + 1], ws)
+
+    run(ys, masks)
+    torch.cuda.synchronize()
+    for i in range(n):
+        assert np.array_equal(masks[i].cpu().numpy(), serial[i]["mask"]), i
+        assert np.array_equal(hz.to_np32(ys[i]).astype(np.float64), serial[i]["y"]), i
+    g = torch.cuda.CUDAGraph()
+    ys2 = torch.zeros_like(ys)
+    masks2 = masks.clone()
+    with torch.cuda.graph(g):
+        run(ys2, masks2)
+    for _ in range(2):
+        ys2.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(ys2, ys) and torch.equal(masks2, masks)
