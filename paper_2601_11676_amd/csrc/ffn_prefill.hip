@@ -71,15 +71,13 @@ constexpr int kKS = 64;             // K elements per LDS stage (32 and 128 meas
 constexpr int kARow = kKS + 8;      // padded LDS row (elements): rows start 16 bytes apart in bank space
 constexpr int kKH = kKS / 32;       // matrix-instruction K steps per stage
 
-template <int TT>
-struct BFrags {
-    u32x4 v[kKH][TT];               // [k step of the stage][token tile]
-};
-
 // TT = 16-token tiles per wave (a workgroup covers 4 * TT * 16 tokens of the group's list);
-// NB = neurons per workgroup (32 or 64).  More neurons per workgroup means each gathered x
-// row is fetched fewer times: x does not stay in the 4 MB L2 next to the weight stream, and
-// its re-fetches were what bounded the 32-neuron form.
+// NB = neurons per workgroup (32 or 64).  Both operands go through LDS: the 2*NB weight rows and
+// the workgroup's gathered x rows are fetched with coalesced 128-byte row segments (eight lanes
+// per row), parked in registers for a stage and written to the other LDS buffer, so both are
+// requested two stages before the matrix instructions read them.  (Letting each lane fetch
+// its own x operand piece straight from memory touched 16 rows per instruction and could only
+// be requested one stage ahead; waves spent more than half their time waiting.)
 template <int TT, int NB>
 __global__ __launch_bounds__(256) void gate_up_pf(
     const bf16_t *__restrict__ x, int T, int d, int gs, const bf16_t *__restrict__ Wg,
@@ -87,33 +85,35 @@ __global__ __launch_bounds__(256) void gate_up_pf(
     const int32_t *__restrict__ tok_cnt, bf16_t *__restrict__ act)
 {
     constexpr int HT = NB / 16;                              // 16-row tiles per matrix
-    constexpr int RPP = 256 / (kKS / 8);                     // rows staged per pass (16 threads per row)
-    constexpr int NP = NB / RPP;                             // staging passes per matrix
+    constexpr int RPP = 256 / (kKS / 8);                     // rows staged per pass (kKS/8 threads per row)
+    constexpr int NP = NB / RPP;                             // staging passes per weight matrix
+    constexpr int kTok = 4 * TT * 16;                        // tokens per workgroup
+    constexpr int NPX = kTok / RPP;                          // staging passes for the x tile
     __shared__ __attribute__((aligned(16))) bf16_t sA[2][2 * NB * kARow];
+    __shared__ __attribute__((aligned(16))) bf16_t sX[2][kTok * kARow];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int i16 = lane & 15, q = lane >> 4;
     const int per_group = gs / NB;
     const int g = blockIdx.x / per_group, nt = blockIdx.x - g * per_group;
     const int cnt = tok_cnt[g];
-    constexpr int kTok = 4 * TT * 16;                        // tokens per workgroup
     const int c0 = blockIdx.y * kTok;
     if (c0 >= cnt) return;                                   // uniform for the workgroup
     const int32_t *list = tok_list + (size_t)g * T;
-    // this wave's tokens: slots c0 + (wave*TT + tt)*16 + i16
-    const bf16_t *xrow[TT];
-#pragma unroll
-    for (int tt = 0; tt < TT; ++tt) {
-        int sl = c0 + (wave * TT + tt) * 16 + i16;
-        sl = sl < cnt ? sl : cnt - 1;                        // past the end: a valid duplicate, never stored
-        xrow[tt] = x + (size_t)list[sl] * d + q * 8;
-    }
-    // staging role of this thread: sixteen threads share a row's 256-byte segment; per pass the
-    // thread takes gate row sr + RPP*p and up row sr + RPP*p (LDS rows r and NB + r), piece sp
+    // staging role of this thread: kKS/8 threads share a row's segment of a stage; per pass the
+    // thread takes gate row sr + RPP*p and up row sr + RPP*p (LDS rows r and NB + r), piece sp,
+    // and x row (= token slot) sr + RPP*p of the workgroup's tile
     const int sr = tid / (kKS / 8), sp = tid % (kKS / 8);
     const size_t neuron0 = (size_t)g * gs + nt * NB;
     const bf16_t *wsrc_g = Wg + (neuron0 + sr) * d + sp * 8;
     const bf16_t *wsrc_u = Wu + (neuron0 + sr) * d + sp * 8;
     const int dst_off = sr * kARow + sp * 8;
+    const bf16_t *xsrc[NPX];
+#pragma unroll
+    for (int p = 0; p < NPX; ++p) {
+        int sl = c0 + sr + RPP * p;
+        sl = sl < cnt ? sl : cnt - 1;                        // past the end: a valid duplicate, never stored
+        xsrc[p] = x + (size_t)list[sl] * d + sp * 8;
+    }
 
     f32x4_t acc[2 * HT][TT];
 #pragma unroll
@@ -121,77 +121,68 @@ __global__ __launch_bounds__(256) void gate_up_pf(
 #pragma unroll
         for (int tt = 0; tt < TT; ++tt) acc[mt][tt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-    struct AStage {
-        u32x4 g[NP], u[NP];
+    struct Stage {
+        u32x4 g[NP], u[NP], x[NPX];
     };
-    auto load_a = [&](int k0, AStage &r) {
+    auto load_stage = [&](int k0, Stage &r) {
+#pragma unroll
+        for (int p = 0; p < NPX; ++p) r.x[p] = *reinterpret_cast<const u32x4 *>(xsrc[p] + k0);
 #pragma unroll
         for (int p = 0; p < NP; ++p) {
             r.g[p] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(wsrc_g + (size_t)p * RPP * d + k0));
             r.u[p] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(wsrc_u + (size_t)p * RPP * d + k0));
         }
     };
-    auto store_a = [&](bf16_t *buf, const AStage &r) {
+    auto store_stage = [&](int buf, const Stage &r) {
+#pragma unroll
+        for (int p = 0; p < NPX; ++p) *reinterpret_cast<u32x4 *>(sX[buf] + dst_off + p * RPP * kARow) = r.x[p];
 #pragma unroll
         for (int p = 0; p < NP; ++p) {
-            *reinterpret_cast<u32x4 *>(buf + dst_off + p * RPP * kARow) = r.g[p];
-            *reinterpret_cast<u32x4 *>(buf + dst_off + (NB + p * RPP) * kARow) = r.u[p];
+            *reinterpret_cast<u32x4 *>(sA[buf] + dst_off + p * RPP * kARow) = r.g[p];
+            *reinterpret_cast<u32x4 *>(sA[buf] + dst_off + (NB + p * RPP) * kARow) = r.u[p];
         }
     };
-    auto load_b = [&](int k0, BFrags<TT> &b) {
-#pragma unroll
-        for (int kh = 0; kh < kKH; ++kh)
-#pragma unroll
-            for (int tt = 0; tt < TT; ++tt)
-                b.v[kh][tt] = *reinterpret_cast<const u32x4 *>(xrow[tt] + k0 + kh * 32);
-    };
-    auto compute = [&](const bf16_t *a_lds, const BFrags<TT> &b) {
+    auto compute = [&](int buf) {
+        const bf16_t *a_lds = sA[buf], *x_lds = sX[buf];
 #pragma unroll
         for (int kh = 0; kh < kKH; ++kh) {
-            u32x4 a[2 * HT];
+            u32x4 a[2 * HT], b[TT];
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt)
+                b[tt] = *reinterpret_cast<const u32x4 *>(x_lds + ((wave * TT + tt) * 16 + i16) * kARow + kh * 32 + q * 8);
 #pragma unroll
             for (int mt = 0; mt < 2 * HT; ++mt)
                 a[mt] = *reinterpret_cast<const u32x4 *>(a_lds + (mt * 16 + i16) * kARow + kh * 32 + q * 8);
 #pragma unroll
             for (int mt = 0; mt < 2 * HT; ++mt)
 #pragma unroll
-                for (int tt = 0; tt < TT; ++tt) acc[mt][tt] = mfma16p(a[mt], b.v[kh][tt], acc[mt][tt]);
+                for (int tt = 0; tt < TT; ++tt) acc[mt][tt] = mfma16p(a[mt], b[tt], acc[mt][tt]);
         }
     };
 
-    // software pipeline over K: while stage s is multiplied, stage s+1's weights travel
-    // global -> registers -> the other LDS buffer and its x fragments travel to registers
-    const int nstage = d / kKS;                 // d % 128 == 0; any count >= 1
-    AStage ra;
-    BFrags<TT> b0, b1;
-    bf16_t *wdst0 = sA[0], *wdst1 = sA[1];
-    load_a(0, ra);
-    load_b(0, b0);
-    store_a(wdst0, ra);
+    // software pipeline over K (an even number of stages, d % 128 == 0).  Top of an even stage s:
+    // LDS buffer 0 holds stage s; r1 = stage s+1 is in flight.
+    const int nstage = d / kKS;
+    Stage r0, r1;
+    load_stage(0, r0);
+    load_stage(kKS, r1);
+    store_stage(0, r0);
     __syncthreads();
     int s = 0;
     for (; s + 2 < nstage; s += 2) {
-        load_a((s + 1) * kKS, ra);
-        load_b((s + 1) * kKS, b1);
-        compute(sA[0], b0);
-        store_a(wdst1, ra);
+        load_stage((s + 2) * kKS, r0);
+        compute(0);
+        store_stage(1, r1);
         __syncthreads();
-        load_a((s + 2) * kKS, ra);
-        load_b((s + 2) * kKS, b0);
-        compute(sA[1], b1);
-        store_a(wdst0, ra);
+        load_stage((s + 3) * kKS, r1);
+        compute(1);
+        store_stage(0, r0);
         __syncthreads();
     }
-    if (s + 1 < nstage) {                       // two stages left
-        load_a((s + 1) * kKS, ra);
-        load_b((s + 1) * kKS, b1);
-        compute(sA[0], b0);
-        store_a(wdst1, ra);
-        __syncthreads();
-        compute(sA[1], b1);
-    } else {                                    // one stage left
-        compute(sA[0], b0);
-    }
+    compute(0);
+    store_stage(1, r1);
+    __syncthreads();
+    compute(1);
 
     // D: column = token i16 of tile tt, rows 4q..4q+3 of a neuron tile (tiles 0..HT-1 gate, HT.. up)
 #pragma unroll
