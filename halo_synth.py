@@ -48,6 +48,12 @@ TID_BT = 6
 TID_DROP = 7
 TID_PLR = 8
 TID_MISC = 9
+TID_WQ = 10
+TID_WK = 11
+TID_WV = 12
+TID_WOT = 13
+TID_KCACHE = 14
+TID_VCACHE = 15
 TID_Q4_CODES = 16     # + 0 gate, 1 up, 2 down
 TID_Q4_SCALES = 24    # + 0 gate, 1 up, 2 down
 
@@ -283,6 +289,79 @@ def ffn_weights_q4(w: Workload, layer: int = 0, device="cpu", copy: int = 0):
     out.append(q4_codes(G * d * gs, stream_key(w.seed, TID_Q4_CODES + 2, lay), device).reshape(G, d, gs // 8))
     out.append(q4_scales(G * d, stream_key(w.seed, TID_Q4_SCALES + 2, lay), device).reshape(G, d))
     return tuple(out)
+
+
+# --------------------------------------------------------------------------
+# Attention block (one head + its output-projection slice = one neuron group, section II-A)
+# --------------------------------------------------------------------------
+@dataclasses.dataclass(frozen=True)
+class MhaWorkload:
+    name: str
+    d: int
+    n_heads: int
+    head_dim: int
+    rank: int
+    ctx: int                   # positions already in the KV cache when the timed step runs
+    max_len: int
+    dtype: str
+    keep: float
+    n_dev: int
+    plr: Tuple[float, ...]
+    seed: int
+
+    @property
+    def torch_dtype(self) -> torch.dtype:
+        return torch.float32 if self.dtype == "f32" else torch.bfloat16
+
+    def k_keep(self, keep: Optional[float] = None) -> int:
+        from fractions import Fraction
+        import math
+        keep = self.keep if keep is None else keep
+        return max(1, min(self.n_heads, math.floor(Fraction(str(keep)) * self.n_heads + Fraction(1, 2))))
+
+    def device_plr(self) -> np.ndarray:
+        return np.asarray(self.plr, dtype=np.float64)
+
+
+# LLaMA-7B attention shape: 32 heads of 128, 2048 cached positions, half the heads kept
+LLAMA7B_MHA_DECODE = MhaWorkload("llama7b_mha_decode", 4096, 32, 128, 256, 2048, 2304, "bf16", 0.5, 4,
+                                 (0.0, 0.05, 0.1, 0.2), 5)
+MHA_BY_NAME = {LLAMA7B_MHA_DECODE.name: LLAMA7B_MHA_DECODE}
+
+
+def mha_weights(w: MhaWorkload, layer: int = 0, device="cpu", copy: int = 0):
+    """(Wq, Wk, Wv, WoT), each [n_heads*head_dim][d]; rows h*head_dim.. belong to head h; WoT is the
+    output projection stored head-dimension-major (row n = the weights leaving dimension n)."""
+    lay = layer + 1000003 * copy
+    hd = w.n_heads * w.head_dim
+    mk = lambda tid: normal((hd, w.d), W_SIGMA, w.torch_dtype, stream_key(w.seed, tid, lay), device)
+    return mk(TID_WQ), mk(TID_WK), mk(TID_WV), mk(TID_WOT)
+
+
+def mha_predictor_weights(w: MhaWorkload, layer: int = 0, device="cpu", copy: int = 0):
+    lay = layer + 1000003 * copy
+    At = normal((w.rank, w.d), W_SIGMA, w.torch_dtype, stream_key(w.seed, TID_AT, lay), device)
+    Bt = normal((w.n_heads, w.rank), W_SIGMA, w.torch_dtype, stream_key(w.seed, TID_BT, lay), device)
+    return At, Bt
+
+
+def kv_cache(w: MhaWorkload, layer: int = 0, device="cpu", copy: int = 0):
+    """(k_cache, v_cache), each [n_heads][max_len][head_dim] ~ N(0,1) in the workload dtype: stands in
+    for the keys / values of the positions decoded so far (all max_len rows are filled; a step at
+    position pos reads rows 0..pos-1 and writes row pos)."""
+    lay = layer + 1000003 * copy
+    shape = (w.n_heads, w.max_len, w.head_dim)
+    return (normal(shape, 1.0, w.torch_dtype, stream_key(w.seed, TID_KCACHE, lay), device),
+            normal(shape, 1.0, w.torch_dtype, stream_key(w.seed, TID_VCACHE, lay), device))
+
+
+def mha_hidden(w: MhaWorkload, step: int = 0, device="cpu"):
+    return normal((1, w.d), X_SIGMA, w.torch_dtype, stream_key(w.seed, TID_X, 0, step), device)
+
+
+def mha_drop_outcomes(w: MhaWorkload, layer: int = 0, step: int = 0) -> np.ndarray:
+    u = uniform01(w.n_dev, stream_key(w.seed, TID_DROP, layer, step)).reshape(1, w.n_dev)
+    return (u < w.device_plr()[None, :]).astype(np.uint8)
 
 
 def predictor_weights(w: Workload, layer: int = 0, device="cpu", copy: int = 0):

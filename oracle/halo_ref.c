@@ -30,6 +30,9 @@
  *                              down columns; the block output is the plain sum of
  *                              the groups' partial results (merge at the master).
  *
+ *   halo_ref_mha_decode        Sec. II-A: one attention head + its output-projection
+ *                              slice = one neuron group; Sec. III-B.3: full KV cache.
+ *
  *   halo_ref_dequant_q4 /
  *   halo_ref_dequant_down_q4   Sec. V-A: 4-bit integer weights (format: the library's).
  *
@@ -435,6 +438,99 @@ int halo_ref_dequant_down_q4(const uint32_t *codes, const float *scales, int32_t
                 WdT[((size_t)g * gs + m) * d + j] = (float)(s * (double)(c - 8));
             }
         }
+    return REF_OK;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Head-sparse multi-head attention for one new token (decode).               */
+/*                                                                           */
+/* Sec. II-A "Neuron group": in the MHA, one head and its slice of the output */
+/* projection are an independent neuron group; the block output is the sum of */
+/* the groups' partial results.  Sec. III-B.3: every device keeps the full KV  */
+/* cache, so keys and values are produced for every head at every position,    */
+/* whether or not the head's output takes part in the merge.                   */
+/*                                                                           */
+/* For head h with rows h*dh .. h*dh+dh-1 of Wq, Wk, Wv ([H*dh][d]) and of WoT  */
+/* ([H*dh][d], row n = the output-projection weights leaving head-dimension n): */
+/*   k_h = Wk_h x, v_h = Wv_h x, stored at position pos of the caches after    */
+/*         rounding to the storage type (the caches hold storage-type values); */
+/*   for a surviving head: q_h = Wq_h x,                                        */
+/*         s_j = q_h . K_h[j] / sqrt(dh)  for j = 0..pos,  p = softmax(s),      */
+/*         o_h = sum_j p_j V_h[j],   y += WoT_h^T o_h.                          */
+/* Scaled dot-product attention as usually defined; no positional rotation and  */
+/* no biases (the paper discusses neither).  Everything in double except the    */
+/* rounding of the new cache entries.                                           */
+/* ------------------------------------------------------------------------- */
+static float round_to_bf16(double v)
+{
+    float f = (float)v;
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    if ((u & 0x7f800000u) == 0x7f800000u) return f;          /* inf / nan unchanged */
+    u += 0x7fffu + ((u >> 16) & 1u);                          /* round to nearest, ties to even */
+    u &= 0xffff0000u;
+    memcpy(&f, &u, 4);
+    return f;
+}
+
+int halo_ref_mha_decode(const float *x /*[d]*/, int32_t d, int32_t H, int32_t dh, const float *Wq,
+                        const float *Wk, const float *Wv, const float *WoT, float *k_cache /*[H][max_len][dh]*/,
+                        float *v_cache, int32_t max_len, int32_t pos, const uint8_t *mask /*[H] or NULL*/,
+                        int32_t cache_is_bf16, double *y /*[d]*/)
+{
+    if (!x || !Wq || !Wk || !Wv || !WoT || !k_cache || !v_cache || !y) return REF_ERR;
+    if (d < 1 || H < 1 || dh < 1 || max_len < 1 || pos < 0 || pos >= max_len) return REF_ERR;
+    /* keys and values of the new token, every head */
+#pragma omp parallel for schedule(static)
+    for (int32_t n = 0; n < H * dh; ++n) {
+        double k = 0.0, v = 0.0;
+        for (int32_t i = 0; i < d; ++i) {
+            k += (double)Wk[(size_t)n * d + i] * (double)x[i];
+            v += (double)Wv[(size_t)n * d + i] * (double)x[i];
+        }
+        const int32_t h = n / dh, e = n - h * dh;
+        const size_t at = ((size_t)h * max_len + pos) * dh + e;
+        k_cache[at] = cache_is_bf16 ? round_to_bf16(k) : (float)k;
+        v_cache[at] = cache_is_bf16 ? round_to_bf16(v) : (float)v;
+    }
+    for (int32_t j = 0; j < d; ++j) y[j] = 0.0;
+    double *q = (double *)malloc(sizeof(double) * (size_t)dh);
+    double *o = (double *)malloc(sizeof(double) * (size_t)dh);
+    double *p = (double *)malloc(sizeof(double) * (size_t)(pos + 1));
+    for (int32_t h = 0; h < H; ++h) {
+        if (mask && !mask[h]) continue;
+        for (int32_t e = 0; e < dh; ++e) {
+            double acc = 0.0;
+            for (int32_t i = 0; i < d; ++i) acc += (double)Wq[((size_t)h * dh + e) * d + i] * (double)x[i];
+            q[e] = acc;
+        }
+        const float *K = k_cache + (size_t)h * max_len * dh, *V = v_cache + (size_t)h * max_len * dh;
+        double smax = -INFINITY;
+        for (int32_t j = 0; j <= pos; ++j) {
+            double sj = 0.0;
+            for (int32_t e = 0; e < dh; ++e) sj += q[e] * (double)K[(size_t)j * dh + e];
+            p[j] = sj / sqrt((double)dh);
+            if (p[j] > smax) smax = p[j];
+        }
+        double denom = 0.0;
+        for (int32_t j = 0; j <= pos; ++j) {
+            p[j] = exp(p[j] - smax);
+            denom += p[j];
+        }
+        for (int32_t e = 0; e < dh; ++e) {
+            double acc = 0.0;
+            for (int32_t j = 0; j <= pos; ++j) acc += p[j] * (double)V[(size_t)j * dh + e];
+            o[e] = acc / denom;
+        }
+        for (int32_t j = 0; j < d; ++j) {
+            double acc = 0.0;
+            for (int32_t e = 0; e < dh; ++e) acc += o[e] * (double)WoT[((size_t)h * dh + e) * d + j];
+            y[j] += acc;
+        }
+    }
+    free(q);
+    free(o);
+    free(p);
     return REF_OK;
 }
 

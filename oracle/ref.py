@@ -210,3 +210,27 @@ def dequant_down_q4(codes, scales) -> np.ndarray:
 def dequant_ffn_q4(q4):
     """(Wg_codes, Wg_scales, Wu_codes, Wu_scales, Wd_codes, Wd_scales) -> (Wg, Wu, WdT) float32."""
     return dequant_q4(q4[0], q4[1]), dequant_q4(q4[2], q4[3]), dequant_down_q4(q4[4], q4[5])
+
+
+def mha_decode(x, Wq, Wk, Wv, WoT, k_cache, v_cache, pos: int, mask=None, cache_is_bf16: bool = True):
+    """One decode step of head-sparse attention.  k_cache / v_cache: float32 [H][max_len][dh] holding
+    storage-type values; they are updated in place at position pos.  Returns y [d] float64."""
+    x = _f32(x).reshape(-1)
+    Wq, Wk, Wv, WoT = _f32(Wq), _f32(Wk), _f32(Wv), _f32(WoT)
+    d = x.shape[0]
+    assert k_cache.dtype == np.float32 and v_cache.dtype == np.float32
+    assert k_cache.flags["C_CONTIGUOUS"] and v_cache.flags["C_CONTIGUOUS"] and k_cache.shape == v_cache.shape
+    H, max_len, dh = k_cache.shape
+    assert Wq.shape == (H * dh, d) and Wk.shape == Wq.shape and Wv.shape == Wq.shape and WoT.shape == Wq.shape
+    m = None if mask is None else np.ascontiguousarray(np.asarray(mask, dtype=np.uint8).reshape(-1))
+    if m is not None:
+        assert m.shape == (H,)
+    y = np.empty((d,), dtype=np.float64)
+    rc = lib().halo_ref_mha_decode(_p(x, C.c_float), C.c_int32(d), C.c_int32(H), C.c_int32(dh),
+                                   _p(Wq, C.c_float), _p(Wk, C.c_float), _p(Wv, C.c_float), _p(WoT, C.c_float),
+                                   _p(k_cache, C.c_float), _p(v_cache, C.c_float), C.c_int32(max_len),
+                                   C.c_int32(pos), _p(m, C.c_uint8), C.c_int32(1 if cache_is_bf16 else 0),
+                                   _p(y, C.c_double))
+    if rc != 0:
+        raise ValueError("halo_ref_mha_decode rejected its arguments")
+    return y
