@@ -251,6 +251,48 @@ int halo_ffn_forward_ahead_q4(const halo_shape *shape, const void *x, int32_t T,
                               int32_t *n_surv_next, void *workspace, size_t ws_bytes, void *stream);
 
 /*
+ * The attention block as neuron groups (paper Sec. II-A: "one head and its output projection
+ * weight are an independent neuron group"; the block output is the sum of the groups' partial
+ * results).  One new token of one sequence (decode) at position pos, 0-based:
+ *   every head h    : k_h = Wk_h x, v_h = Wv_h x are written to row pos of the caches -- every
+ *                     device keeps the full KV cache (Sec. III-B.3), so keys and values exist
+ *                     for every head whether or not its output takes part in the merge;
+ *   surviving heads : q_h = Wq_h x,  p = softmax(q_h K_h^T / sqrt(head_dim)) over rows 0..pos,
+ *                     o_h = p V_h,  y = sum over surviving h of Wo_h o_h.
+ * Plain scaled dot-product attention: no positional rotation, no biases (the paper discusses
+ * neither).  Only surviving heads' query rows, cache rows and output-projection blocks are read.
+ *
+ * halo_mha_shape: d, n_heads (<= 256), head_dim (must be 128), rank of the head predictor,
+ * dtype (HALO_BF16 only).  Layouts (device pointers, 16-byte aligned, dense):
+ *   x [d], y [d];  Wq, Wk, Wv [n_heads*head_dim][d] (rows of head h contiguous);
+ *   Wo head-blocked [n_heads][d][head_dim] (the layout of Wd with heads as groups);
+ *   k_cache, v_cache [n_heads][max_len][head_dim], rows 0..pos-1 valid on entry, row pos written;
+ *   mask [n_heads] as produced by halo_build_group_mask with G = n_heads.
+ * halo_mha_forward runs predictor -> mask -> attention on one stream; the predictor is the same
+ * two-matrix network with one output per head (At [rank][d], Bt [n_heads][rank]) and the optional
+ * outputs have the meaning they have in halo_ffn_forward.
+ * Errors: as halo_group_sparse_ffn, plus HALO_ERR_ARG for pos outside [0, max_len).
+ */
+typedef struct {
+    int32_t d, n_heads, head_dim, rank;
+    int32_t dtype;
+} halo_mha_shape;
+
+size_t halo_mha_workspace_bytes(const halo_mha_shape *shape, int32_t max_len);
+
+int halo_head_sparse_mha(const halo_mha_shape *shape, const void *x, const void *Wq, const void *Wk,
+                         const void *Wv, const void *Wo, void *k_cache, void *v_cache, int32_t max_len,
+                         int32_t pos, const uint8_t *mask, void *y, void *workspace, size_t ws_bytes,
+                         void *stream);
+
+int halo_mha_forward(const halo_mha_shape *shape, const void *x, const void *x_pred, const void *At,
+                     const void *Bt, const void *Wq, const void *Wk, const void *Wv, const void *Wo,
+                     void *k_cache, void *v_cache, int32_t max_len, int32_t pos, int32_t k_keep,
+                     const int8_t *prio_dev, int32_t n_dev, const uint8_t *drop, void *y, float *scores,
+                     int32_t *order, int8_t *group_dev, uint8_t *mask, int32_t *surv_idx, int32_t *n_surv,
+                     void *workspace, size_t ws_bytes, void *stream);
+
+/*
  * Benchmark aid (not part of the paper's method).  Between halo_profile_begin and
  * halo_profile_end every call of halo_group_sparse_ffn / halo_ffn_forward brackets the
  * FFN's dominant kernel -- the gate/up projection, which streams two thirds of the

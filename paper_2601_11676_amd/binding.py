@@ -27,6 +27,20 @@ class _CShape(C.Structure):
                 ("n_groups", C.c_int32), ("rank", C.c_int32), ("dtype", C.c_int32)]
 
 
+class _CMhaShape(C.Structure):
+    _fields_ = [("d", C.c_int32), ("n_heads", C.c_int32), ("head_dim", C.c_int32), ("rank", C.c_int32),
+                ("dtype", C.c_int32)]
+
+
+class MhaShape:
+    """halo_mha_shape: d, n_heads, head_dim, rank, dtype ('bf16')."""
+
+    def __init__(self, d: int, n_heads: int, head_dim: int, rank: int, dtype: str = "bf16"):
+        self.d, self.n_heads, self.head_dim, self.rank, self.dtype = d, n_heads, head_dim, rank, dtype
+        code = {"f32": HALO_F32, "bf16": HALO_BF16}.get(dtype, -1)
+        self.c = _CMhaShape(d, n_heads, head_dim, rank, code)
+
+
 class Shape:
     """halo_shape: d, ffn, group_size, n_groups, rank, dtype ('f32' | 'bf16')."""
 
@@ -88,6 +102,14 @@ def load_library():
     lib.halo_ffn_forward_ahead_q4.restype = C.c_int
     lib.halo_ffn_forward_ahead_q4.argtypes = [ps, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp,
                                               i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    pm = C.POINTER(_CMhaShape)
+    lib.halo_mha_workspace_bytes.restype = sz
+    lib.halo_mha_workspace_bytes.argtypes = [pm, i32]
+    lib.halo_head_sparse_mha.restype = C.c_int
+    lib.halo_head_sparse_mha.argtypes = [pm, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, sz, vp]
+    lib.halo_mha_forward.restype = C.c_int
+    lib.halo_mha_forward.argtypes = [pm, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, vp, i32, vp, vp,
+                                     vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.halo_profile_begin.restype = C.c_int
     lib.halo_profile_begin.argtypes = [i32, i32]
     lib.halo_profile_end.restype = C.c_int
@@ -252,6 +274,31 @@ def halo_ffn_forward_ahead_q4(shape: Shape, x, q4, mask_cur, y, x_pred_next, At_
         _ptr(scores_next), _ptr(order_next), _ptr(group_dev_next), _ptr(mask_next), _ptr(surv_idx_next),
         _ptr(n_surv_next), _ptr(workspace), workspace.numel(), _stream(stream))
     _check("halo_ffn_forward_ahead_q4", rc)
+
+
+def halo_mha_workspace_bytes(shape: MhaShape, max_len: int) -> int:
+    return int(load_library().halo_mha_workspace_bytes(C.byref(shape.c), int(max_len)))
+
+
+def halo_head_sparse_mha(shape: MhaShape, x, Wq, Wk, Wv, Wo, k_cache, v_cache, pos: int, mask, y, workspace,
+                         stream=None) -> None:
+    """k_cache / v_cache: [n_heads][max_len][head_dim]; Wo head-blocked (pack_down_proj(WoT, head_dim))."""
+    rc = load_library().halo_head_sparse_mha(
+        C.byref(shape.c), _ptr(x), _ptr(Wq), _ptr(Wk), _ptr(Wv), _ptr(Wo), _ptr(k_cache), _ptr(v_cache),
+        int(k_cache.shape[1]), int(pos), _ptr(mask), _ptr(y), _ptr(workspace), workspace.numel(), _stream(stream))
+    _check("halo_head_sparse_mha", rc)
+
+
+def halo_mha_forward(shape: MhaShape, x, At, Bt, Wq, Wk, Wv, Wo, k_cache, v_cache, pos: int, k_keep: int,
+                     prio_dev, n_dev: int, drop, y, workspace, x_pred=None, scores=None, order=None,
+                     group_dev=None, mask=None, surv_idx=None, n_surv=None, stream=None) -> None:
+    xp = x if x_pred is None else x_pred
+    rc = load_library().halo_mha_forward(
+        C.byref(shape.c), _ptr(x), _ptr(xp), _ptr(At), _ptr(Bt), _ptr(Wq), _ptr(Wk), _ptr(Wv), _ptr(Wo),
+        _ptr(k_cache), _ptr(v_cache), int(k_cache.shape[1]), int(pos), int(k_keep), _ptr(prio_dev), int(n_dev),
+        _ptr(drop), _ptr(y), _ptr(scores), _ptr(order), _ptr(group_dev), _ptr(mask), _ptr(surv_idx),
+        _ptr(n_surv), _ptr(workspace), workspace.numel(), _stream(stream))
+    _check("halo_mha_forward", rc)
 
 
 def prepared(fn, *args, **kwargs):

@@ -408,6 +408,25 @@ static hipError_t decode_t1(const bf16_t *x, int G, int gs, const bf16_t *Wg, co
     return hipGetLastError();
 }
 
+hipError_t launch_down_t1(const bf16_t *Wd, int d, int G, const uint8_t *mask, const bf16_t *act, bf16_t *y,
+                          hipStream_t s)
+{
+    switch (d) {
+    case 4096: down_t1<4><<<dim3(256), dim3(512), 0, s>>>(d, G, Wd, mask, act, y); break;
+    case 5120: down_t1<5><<<dim3(256), dim3(640), 0, s>>>(d, G, Wd, mask, act, y); break;
+    case 8192: down_t1<8><<<dim3(256), dim3(1024), 0, s>>>(d, G, Wd, mask, act, y); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_down_generic_bf16(const float *act, int act_stride, int d, int gs, const bf16_t *Wd,
+                                    const int32_t *ulist, const int32_t *meta, bf16_t *y, hipStream_t s)
+{
+    down_generic<bf16_t, 4><<<dim3((d + 3) / 4), dim3(256), 0, s>>>(act, act_stride, 1, d, gs, Wd, ulist, meta, y);
+    return hipGetLastError();
+}
+
 // ahead != nullptr asks for the next block's prediction to ride along with this block's
 // kernels.  Only the one-token path can do that; *ahead_fused tells the caller whether it did
 // (if not, the caller enqueues the prediction itself).

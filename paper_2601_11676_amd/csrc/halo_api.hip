@@ -64,6 +64,53 @@ struct Workspace {
     }
 };
 
+int check_mha_shape(const halo_mha_shape *s)
+{
+    if (!s) return HALO_ERR_NULL;
+    if (s->dtype != HALO_BF16) return HALO_ERR_DTYPE;
+    if (s->d < 8 || s->d % 8 || s->rank < 8 || s->rank % 8) return HALO_ERR_SHAPE;
+    if (s->n_heads < 1 || s->n_heads > 256 || !mha_shape_supported(s->d, s->head_dim)) return HALO_ERR_SHAPE;
+    return HALO_OK;
+}
+
+// The attention block's workspace: the FFN's carving with heads as groups, plus queries and
+// partial softmaxes.
+struct MhaWorkspace {
+    halo_shape as_ffn{};
+    Workspace base;
+    MhaScratch mha{};
+    size_t bytes = 0;
+
+    static halo_shape ffn_view(const halo_mha_shape &s)
+    {
+        halo_shape f{};
+        f.d = s.d;
+        f.ffn = s.n_heads * s.head_dim;
+        f.group_size = s.head_dim;
+        f.n_groups = s.n_heads;
+        f.rank = s.rank;
+        f.dtype = (halo_dtype)s.dtype;
+        return f;
+    }
+
+    MhaWorkspace(const halo_mha_shape &s, int max_len, void *p)
+        : as_ffn(ffn_view(s)), base(as_ffn, 1, s.n_heads, p)
+    {
+        size_t off = base.bytes;
+        char *b = static_cast<char *>(p);
+        auto take = [&](size_t n) -> char * {
+            char *r = b ? b + off : nullptr;
+            off += align_up(n);
+            return r;
+        };
+        const size_t chunks = (size_t)(max_len + kMhaChunk - 1) / kMhaChunk;
+        mha.q = reinterpret_cast<float *>(take((size_t)s.n_heads * s.head_dim * sizeof(float)));
+        mha.part = reinterpret_cast<float *>(take((size_t)s.n_heads * chunks * (s.head_dim + 2) * sizeof(float)));
+        mha.dec = base.dec;
+        bytes = off;
+    }
+};
+
 }  // namespace
 
 extern "C" {
@@ -345,6 +392,69 @@ int halo_ffn_forward_q4(const halo_shape *shape, const void *x, const void *x_pr
     const Q4Weights w{(const uint32_t *)Wg_codes, (const bf16_t *)Wg_scales, (const uint32_t *)Wu_codes,
                       (const bf16_t *)Wu_scales, (const uint32_t *)Wd_codes, (const bf16_t *)Wd_scales};
     e = launch_ffn_q4(shape->dtype, x, T, shape->d, shape->n_groups, shape->group_size, w, mk, y, ws.dec, s);
+    return e == hipSuccess ? HALO_OK : HALO_ERR_HIP;
+}
+
+size_t halo_mha_workspace_bytes(const halo_mha_shape *shape, int32_t max_len)
+{
+    if (check_mha_shape(shape) != HALO_OK || max_len < 1) return 0;
+    return MhaWorkspace(*shape, max_len, nullptr).bytes;
+}
+
+int halo_head_sparse_mha(const halo_mha_shape *shape, const void *x, const void *Wq, const void *Wk,
+                         const void *Wv, const void *Wo, void *k_cache, void *v_cache, int32_t max_len,
+                         int32_t pos, const uint8_t *mask, void *y, void *workspace, size_t ws_bytes,
+                         void *stream)
+{
+    int rc = check_mha_shape(shape);
+    if (rc) return rc;
+    if (max_len < 1 || pos < 0 || pos >= max_len) return HALO_ERR_ARG;
+    if (!x || !Wq || !Wk || !Wv || !Wo || !k_cache || !v_cache || !mask || !y) return HALO_ERR_NULL;
+    if (misaligned(x) || misaligned(Wq) || misaligned(Wk) || misaligned(Wv) || misaligned(Wo) ||
+        misaligned(k_cache) || misaligned(v_cache) || misaligned(y))
+        return HALO_ERR_ARG;
+    if (!workspace || misaligned(workspace)) return HALO_ERR_WORKSPACE;
+    MhaWorkspace ws(*shape, max_len, workspace);
+    if (ws_bytes < ws.bytes) return HALO_ERR_WORKSPACE;
+    hipError_t e = launch_mha_decode(x, shape->d, shape->n_heads, Wq, Wk, Wv, Wo, k_cache, v_cache, max_len, pos,
+                                     mask, y, ws.mha, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? HALO_OK : HALO_ERR_HIP;
+}
+
+int halo_mha_forward(const halo_mha_shape *shape, const void *x, const void *x_pred, const void *At,
+                     const void *Bt, const void *Wq, const void *Wk, const void *Wv, const void *Wo,
+                     void *k_cache, void *v_cache, int32_t max_len, int32_t pos, int32_t k_keep,
+                     const int8_t *prio_dev, int32_t n_dev, const uint8_t *drop, void *y, float *scores,
+                     int32_t *order, int8_t *group_dev, uint8_t *mask, int32_t *surv_idx, int32_t *n_surv,
+                     void *workspace, size_t ws_bytes, void *stream)
+{
+    int rc = check_mha_shape(shape);
+    if (rc) return rc;
+    if (max_len < 1 || pos < 0 || pos >= max_len || k_keep < 0 || k_keep > shape->n_heads || n_dev < 1 ||
+        n_dev > 127)
+        return HALO_ERR_ARG;
+    if (!x || !x_pred || !At || !Bt || !Wq || !Wk || !Wv || !Wo || !k_cache || !v_cache || !y ||
+        (k_keep > 0 && !prio_dev))
+        return HALO_ERR_NULL;
+    if (misaligned(x) || misaligned(x_pred) || misaligned(At) || misaligned(Bt) || misaligned(Wq) ||
+        misaligned(Wk) || misaligned(Wv) || misaligned(Wo) || misaligned(k_cache) || misaligned(v_cache) ||
+        misaligned(y) || (scores && misaligned(scores)))
+        return HALO_ERR_ARG;
+    if (!workspace || misaligned(workspace)) return HALO_ERR_WORKSPACE;
+    MhaWorkspace ws(*shape, max_len, workspace);
+    if (ws_bytes < ws.bytes) return HALO_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    float *sc = scores ? scores : ws.base.scores;
+    uint8_t *mk = mask ? mask : ws.base.mask;
+    // the predictor and the mask builder are the FFN's: one significance value per head
+    hipError_t e = launch_predictor(shape->dtype, x_pred, 1, shape->d, shape->rank, shape->n_heads, At, Bt,
+                                    ws.base.h, nullptr, s);
+    if (e != hipSuccess) return HALO_ERR_HIP;
+    e = launch_scores_and_mask(shape->dtype, ws.base.h, Bt, shape->rank, sc, 1, shape->n_heads, k_keep, prio_dev,
+                               n_dev, drop, order, group_dev, mk, surv_idx, n_surv, s);
+    if (e != hipSuccess) return HALO_ERR_HIP;
+    e = launch_mha_decode(x, shape->d, shape->n_heads, Wq, Wk, Wv, Wo, k_cache, v_cache, max_len, pos, mk, y,
+                          ws.mha, s);
     return e == hipSuccess ? HALO_OK : HALO_ERR_HIP;
 }
 
