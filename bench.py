@@ -60,6 +60,154 @@ def read_traffic(kernel: str, workload: str):
     return None
 
 
+def main_mha(args, w):
+    """Head-sparse attention decode (one head + its output-projection slice = one neuron group).
+    One step = predictor -> head mask -> q/k/v rows, attention over the KV cache, output
+    projection, for one new token; weights and caches rotate over --copies replicas."""
+    import torch
+
+    import halo_synth as hs
+    import paper_2601_11676_amd as H
+
+    dev = "cuda:0"
+    K, W, NC = args.steps, args.warmup, min(args.copies, 8)
+    Hh, d, dh = w.n_heads, w.d, w.head_dim
+    k_keep = w.k_keep()
+    shape = H.MhaShape(d, Hh, dh, w.rank, w.dtype)
+    copies = []
+    for c in range(NC):
+        Wq, Wk, Wv, WoT = hs.mha_weights(w, 0, dev, copy=c)
+        At, Bt = hs.mha_predictor_weights(w, 0, dev, copy=c)
+        kc, vc = hs.kv_cache(w, 0, dev, copy=c)
+        copies.append((At, Bt, Wq, Wk, Wv, H.pack_down_proj(WoT, dh), kc, vc))
+        if c == 0:
+            host0 = tuple(t.float().cpu().numpy() for t in (Wq, Wk, Wv, WoT, At, Bt))
+            k0, v0 = kc.float().cpu().numpy(), vc.float().cpu().numpy()   # cache of copy 0 before any step
+        del WoT
+    n_all = W + K
+    xs = torch.stack([hs.mha_hidden(w, s, dev) for s in range(n_all + 1)])
+    drops_np = np.stack([hs.mha_drop_outcomes(w, 0, s) for s in range(n_all + 1)])
+    drops = torch.from_numpy(drops_np).to(dev)
+    prio_dev_np = H.halo_build_schedule(k_keep, w.device_plr())
+    prio_dev = torch.from_numpy(prio_dev_np).to(dev)
+    ys = torch.zeros((n_all, 1, d), dtype=w.torch_dtype, device=dev)
+    masks = torch.zeros((n_all + 1, 1, Hh), dtype=torch.uint8, device=dev)
+    ws = torch.empty(H.halo_mha_workspace_bytes(shape, w.max_len), dtype=torch.uint8, device=dev)
+    span = w.max_len - w.ctx                       # positions a copy's cache can still take
+    pos_of = lambda s: w.ctx + (s // NC) % span    # each copy's cache grows by one row per visit
+    st = torch.cuda.Stream()
+
+    def make_serial(s):
+        At, Bt, Wq, Wk, Wv, Wo, kc, vc = copies[s % NC]
+        H.halo_mha_forward(shape, xs[s], At, Bt, Wq, Wk, Wv, Wo, kc, vc, pos_of(s), k_keep, prio_dev, w.n_dev,
+                           drops[s], ys[s], ws, mask=masks[s], stream=st)
+
+    def make_ahead(s):
+        # attention of step s with the mask predicted one step earlier; beside it, in spare workgroups
+        # of the q/k/v and output-projection launches, predictor + head mask of step s+1
+        _, _, Wq, Wk, Wv, Wo, kc, vc = copies[s % NC]
+        At, Bt = copies[(s + 1) % NC][:2]
+        H.halo_mha_forward_ahead(shape, xs[s], Wq, Wk, Wv, Wo, kc, vc, pos_of(s), masks[s], ys[s], xs[s + 1],
+                                 At, Bt, k_keep, prio_dev, w.n_dev, drops[s + 1], masks[s + 1], ws, stream=st)
+
+    calls = [H.prepared(make_serial if args.serial else make_ahead, s) for s in range(n_all)]
+    torch.cuda.synchronize()
+    make_serial(0)                          # also provides masks[0] for the overlapped form (row pos_of(0)
+    for s in range(W):                      # of copy 0 is simply written again by step 0)
+        calls[s]()
+    torch.cuda.synchronize()
+    use_graph = not args.no_graph
+    if use_graph:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=st):
+            for s in range(W, W + K):
+                calls[s]()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(st):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        with torch.cuda.stream(st):
+            graph.replay()
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+    else:
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for s in range(W, W + K):
+            calls[s]()
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+    y_timed = ys[W:W + K].clone()
+    H.halo_profile_begin(K, args.time_every)
+    torch.cuda.synchronize()
+    for s in range(W, W + K):
+        calls[s]()
+    torch.cuda.synchronize()
+    kern_ms, kern_n, kern_name = H.halo_profile_end()
+    same = bool(torch.equal(y_timed, ys[W:W + K]))
+
+    n_surv = masks[W:W + K].cpu().numpy().sum(axis=2)[:, 0]                 # [K]
+    esz = 2
+    row_bytes = d * esz
+    qkv_bytes = (2 * Hh * dh + n_surv * dh) * row_bytes                     # per launch
+    cache_bytes = np.array([n_surv[i] * 2 * (pos_of(W + i) + 1) * dh * esz for i in range(K)])
+    out_bytes = n_surv * dh * row_bytes
+    total_bytes = float((qkv_bytes + cache_bytes + out_bytes).sum())
+    timed = qkv_bytes[::args.time_every][:kern_n]
+    achieved = float(timed.sum()) / (kern_ms * 1e-3) / 1e9 if kern_ms > 0 else 0.0
+    out = {
+        "metric": f"MHA tokens/s (decode), {w.name}, {w.keep} of the heads kept, {w.ctx} cached positions",
+        "value": K / elapsed, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": elapsed / K * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "d": d, "n_heads": Hh, "head_dim": dh, "rank": w.rank, "ctx": w.ctx,
+                   "max_len": w.max_len, "k_keep": k_keep, "n_dev": w.n_dev,
+                   "plr": [float(v) for v in w.device_plr()], "seed": w.seed, "weight_copies": NC, "graph": use_graph,
+                   "predictor": "serial" if args.serial else "one step ahead, beside the attention block"},
+        "whole_pass": {"mean_n_surv": float(n_surv.mean()), "bytes_per_step": total_bytes / K,
+                       "GBps": total_bytes / elapsed / 1e9,
+                       "frac_of_hbm_peak": total_bytes / elapsed / 1e9 / HBM_PEAK_GBPS, "graph_equals_eager": same},
+        "roofline": {"bound": "hbm", "kernel": kern_name, "achieved": achieved, "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": read_traffic(kern_name, w.name),
+                     "launches": int(kern_n), "avg_us": kern_ms / max(kern_n, 1) * 1e3,
+                     "bytes_per_launch": float(timed.mean()) if len(timed) else 0.0},
+    }
+    if not args.no_cpu:
+        from oracle import ref
+        Wq, Wk, Wv, WoT, At, Bt = host0
+        # copy 0's first visit after the caches were last in their generated state is step 0; replay the
+        # oracle over copy 0's visits from the start so that its cache matches the GPU's at every step
+        visits = [s for s in range(W + K) if s % NC == 0]
+        sample = visits[: max(1, min(args.cpu_steps, 16))]
+        kc, vc = k0.copy(), v0.copy()
+        x_np = xs.float().cpu().numpy()
+        y_np = ys.float().cpu().numpy()
+        worst, masks_ok = 0.0, True
+        t0 = time.perf_counter()
+        outs = []
+        for s in sample:
+            sc = ref.predict_scores(x_np[s], At, Bt)
+            m = ref.build_group_mask(sc, k_keep, prio_dev_np, w.n_dev, drops_np[s])
+            outs.append((m["mask"], ref.mha_decode(x_np[s], Wq, Wk, Wv, WoT, kc, vc, pos_of(s), m["mask"][0])))
+        cpu_t = time.perf_counter() - t0
+        # the eager and graph passes re-ran the timed steps on the same cache rows, so only steps before
+        # the timed region (warm-up visits) are compared value by value with the GPU's stored outputs
+        for s, (mk, yc) in zip(sample, outs):
+            if s >= W:
+                break
+            masks_ok &= bool(np.array_equal(mk, masks[s].cpu().numpy()))
+            den = np.linalg.norm(yc)
+            if den > 0:
+                worst = max(worst, float(np.linalg.norm(y_np[s, 0] - yc) / den))
+        out["cpu_baseline"] = {"value": len(sample) / cpu_t, "unit": "tokens/s", "cores": ref.num_threads(),
+                               "kind": "oracle",
+                               "sample": f"{len(sample)} steps on weight copy 0 (whole pass each)",
+                               "ms_per_step": cpu_t / len(sample) * 1e3,
+                               "gpu_vs_oracle_max_rel_l2": worst, "masks_bit_exact": masks_ok}
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -107,6 +255,9 @@ def main():
             dst.copy_(src)          # one elementwise copy kernel: reads n bytes, writes n bytes
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration": {"bytes_read": n, "bytes_written": n, "launches": 8}}))
+        return
+    if args.workload in hs.MHA_BY_NAME:
+        main_mha(args, hs.MHA_BY_NAME[args.workload])
         return
     w = hs.BY_NAME[args.workload]
     K, W, NC = args.steps, args.warmup, args.copies

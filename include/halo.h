@@ -271,7 +271,12 @@ int halo_ffn_forward_ahead_q4(const halo_shape *shape, const void *x, int32_t T,
  * halo_mha_forward runs predictor -> mask -> attention on one stream; the predictor is the same
  * two-matrix network with one output per head (At [rank][d], Bt [n_heads][rank]) and the optional
  * outputs have the meaning they have in halo_ffn_forward.
- * Errors: as halo_group_sparse_ffn, plus HALO_ERR_ARG for pos outside [0, max_len).
+ * halo_mha_forward_ahead is the overlapped form (same contract as halo_ffn_forward_ahead):
+ * attention of the current block with mask_cur, and beside it predictor + head mask of the next
+ * block from x_pred_next; for d in {4096, 5120, 8192} the prediction rides in spare workgroups of
+ * the q/k/v launch and of the output-projection launch, otherwise it is enqueued afterwards.
+ * Errors: as halo_group_sparse_ffn, plus HALO_ERR_ARG for pos outside [0, max_len) or
+ * max_len > 131072.
  */
 typedef struct {
     int32_t d, n_heads, head_dim, rank;
@@ -291,6 +296,14 @@ int halo_mha_forward(const halo_mha_shape *shape, const void *x, const void *x_p
                      const int8_t *prio_dev, int32_t n_dev, const uint8_t *drop, void *y, float *scores,
                      int32_t *order, int8_t *group_dev, uint8_t *mask, int32_t *surv_idx, int32_t *n_surv,
                      void *workspace, size_t ws_bytes, void *stream);
+
+int halo_mha_forward_ahead(const halo_mha_shape *shape, const void *x, const void *Wq, const void *Wk,
+                           const void *Wv, const void *Wo, void *k_cache, void *v_cache, int32_t max_len,
+                           int32_t pos, const uint8_t *mask_cur, void *y, const void *x_pred_next,
+                           const void *At_next, const void *Bt_next, int32_t k_keep, const int8_t *prio_dev,
+                           int32_t n_dev, const uint8_t *drop_next, float *scores_next, int32_t *order_next,
+                           int8_t *group_dev_next, uint8_t *mask_next, int32_t *surv_idx_next,
+                           int32_t *n_surv_next, void *workspace, size_t ws_bytes, void *stream);
 
 /*
  * Benchmark aid (not part of the paper's method).  Between halo_profile_begin and

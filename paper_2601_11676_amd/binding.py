@@ -110,6 +110,9 @@ def load_library():
     lib.halo_mha_forward.restype = C.c_int
     lib.halo_mha_forward.argtypes = [pm, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, vp, i32, vp, vp,
                                      vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.halo_mha_forward_ahead.restype = C.c_int
+    lib.halo_mha_forward_ahead.argtypes = [pm, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, i32, vp,
+                                           i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.halo_profile_begin.restype = C.c_int
     lib.halo_profile_begin.argtypes = [i32, i32]
     lib.halo_profile_end.restype = C.c_int
@@ -299,6 +302,19 @@ def halo_mha_forward(shape: MhaShape, x, At, Bt, Wq, Wk, Wv, Wo, k_cache, v_cach
         _ptr(drop), _ptr(y), _ptr(scores), _ptr(order), _ptr(group_dev), _ptr(mask), _ptr(surv_idx),
         _ptr(n_surv), _ptr(workspace), workspace.numel(), _stream(stream))
     _check("halo_mha_forward", rc)
+
+
+def halo_mha_forward_ahead(shape: MhaShape, x, Wq, Wk, Wv, Wo, k_cache, v_cache, pos: int, mask_cur, y,
+                           x_pred_next, At_next, Bt_next, k_keep: int, prio_dev, n_dev: int, drop_next, mask_next,
+                           workspace, scores_next=None, order_next=None, group_dev_next=None, surv_idx_next=None,
+                           n_surv_next=None, stream=None) -> None:
+    rc = load_library().halo_mha_forward_ahead(
+        C.byref(shape.c), _ptr(x), _ptr(Wq), _ptr(Wk), _ptr(Wv), _ptr(Wo), _ptr(k_cache), _ptr(v_cache),
+        int(k_cache.shape[1]), int(pos), _ptr(mask_cur), _ptr(y), _ptr(x_pred_next), _ptr(At_next), _ptr(Bt_next),
+        int(k_keep), _ptr(prio_dev), int(n_dev), _ptr(drop_next), _ptr(scores_next), _ptr(order_next),
+        _ptr(group_dev_next), _ptr(mask_next), _ptr(surv_idx_next), _ptr(n_surv_next), _ptr(workspace),
+        workspace.numel(), _stream(stream))
+    _check("halo_mha_forward_ahead", rc)
 
 
 def prepared(fn, *args, **kwargs):

@@ -409,8 +409,18 @@ static hipError_t decode_t1(const bf16_t *x, int G, int gs, const bf16_t *Wg, co
 }
 
 hipError_t launch_down_t1(const bf16_t *Wd, int d, int G, const uint8_t *mask, const bf16_t *act, bf16_t *y,
-                          hipStream_t s)
+                          hipStream_t s, const AheadArgs *ahead)
 {
+    if (ahead) {
+        const AheadDev nx = ahead_dev(*ahead);
+        switch (d) {
+        case 4096: down_mask_t1<4><<<dim3(257), dim3(512), 0, s>>>(d, G, Wd, mask, act, y, nx); break;
+        case 5120: down_mask_t1<5><<<dim3(257), dim3(640), 0, s>>>(d, G, Wd, mask, act, y, nx); break;
+        case 8192: down_mask_t1<8><<<dim3(257), dim3(1024), 0, s>>>(d, G, Wd, mask, act, y, nx); break;
+        default: return hipErrorInvalidValue;
+        }
+        return hipGetLastError();
+    }
     switch (d) {
     case 4096: down_t1<4><<<dim3(256), dim3(512), 0, s>>>(d, G, Wd, mask, act, y); break;
     case 5120: down_t1<5><<<dim3(256), dim3(640), 0, s>>>(d, G, Wd, mask, act, y); break;

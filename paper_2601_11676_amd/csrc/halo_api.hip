@@ -397,7 +397,7 @@ int halo_ffn_forward_q4(const halo_shape *shape, const void *x, const void *x_pr
 
 size_t halo_mha_workspace_bytes(const halo_mha_shape *shape, int32_t max_len)
 {
-    if (check_mha_shape(shape) != HALO_OK || max_len < 1) return 0;
+    if (check_mha_shape(shape) != HALO_OK || max_len < 1 || max_len > kMhaMaxLen) return 0;
     return MhaWorkspace(*shape, max_len, nullptr).bytes;
 }
 
@@ -408,7 +408,7 @@ int halo_head_sparse_mha(const halo_mha_shape *shape, const void *x, const void 
 {
     int rc = check_mha_shape(shape);
     if (rc) return rc;
-    if (max_len < 1 || pos < 0 || pos >= max_len) return HALO_ERR_ARG;
+    if (max_len < 1 || max_len > kMhaMaxLen || pos < 0 || pos >= max_len) return HALO_ERR_ARG;
     if (!x || !Wq || !Wk || !Wv || !Wo || !k_cache || !v_cache || !mask || !y) return HALO_ERR_NULL;
     if (misaligned(x) || misaligned(Wq) || misaligned(Wk) || misaligned(Wv) || misaligned(Wo) ||
         misaligned(k_cache) || misaligned(v_cache) || misaligned(y))
@@ -430,8 +430,8 @@ int halo_mha_forward(const halo_mha_shape *shape, const void *x, const void *x_p
 {
     int rc = check_mha_shape(shape);
     if (rc) return rc;
-    if (max_len < 1 || pos < 0 || pos >= max_len || k_keep < 0 || k_keep > shape->n_heads || n_dev < 1 ||
-        n_dev > 127)
+    if (max_len < 1 || max_len > kMhaMaxLen || pos < 0 || pos >= max_len || k_keep < 0 ||
+        k_keep > shape->n_heads || n_dev < 1 || n_dev > 127)
         return HALO_ERR_ARG;
     if (!x || !x_pred || !At || !Bt || !Wq || !Wk || !Wv || !Wo || !k_cache || !v_cache || !y ||
         (k_keep > 0 && !prio_dev))
@@ -456,6 +456,50 @@ int halo_mha_forward(const halo_mha_shape *shape, const void *x, const void *x_p
     e = launch_mha_decode(x, shape->d, shape->n_heads, Wq, Wk, Wv, Wo, k_cache, v_cache, max_len, pos, mk, y,
                           ws.mha, s);
     return e == hipSuccess ? HALO_OK : HALO_ERR_HIP;
+}
+
+int halo_mha_forward_ahead(const halo_mha_shape *shape, const void *x, const void *Wq, const void *Wk,
+                           const void *Wv, const void *Wo, void *k_cache, void *v_cache, int32_t max_len,
+                           int32_t pos, const uint8_t *mask_cur, void *y, const void *x_pred_next,
+                           const void *At_next, const void *Bt_next, int32_t k_keep, const int8_t *prio_dev,
+                           int32_t n_dev, const uint8_t *drop_next, float *scores_next, int32_t *order_next,
+                           int8_t *group_dev_next, uint8_t *mask_next, int32_t *surv_idx_next,
+                           int32_t *n_surv_next, void *workspace, size_t ws_bytes, void *stream)
+{
+    int rc = check_mha_shape(shape);
+    if (rc) return rc;
+    if (max_len < 1 || max_len > kMhaMaxLen || pos < 0 || pos >= max_len || k_keep < 0 ||
+        k_keep > shape->n_heads || n_dev < 1 || n_dev > 127)
+        return HALO_ERR_ARG;
+    if (!x || !Wq || !Wk || !Wv || !Wo || !k_cache || !v_cache || !mask_cur || !y || !x_pred_next || !At_next ||
+        !Bt_next || !mask_next || (k_keep > 0 && !prio_dev))
+        return HALO_ERR_NULL;
+    if (mask_next == mask_cur || y == x_pred_next) return HALO_ERR_ARG;
+    if (misaligned(x) || misaligned(Wq) || misaligned(Wk) || misaligned(Wv) || misaligned(Wo) ||
+        misaligned(k_cache) || misaligned(v_cache) || misaligned(y) || misaligned(x_pred_next) ||
+        misaligned(At_next) || misaligned(Bt_next) || (scores_next && misaligned(scores_next)))
+        return HALO_ERR_ARG;
+    if (!workspace || misaligned(workspace)) return HALO_ERR_WORKSPACE;
+    MhaWorkspace ws(*shape, max_len, workspace);
+    if (ws_bytes < ws.bytes) return HALO_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    float *sc = scores_next ? scores_next : ws.base.scores;
+    AheadArgs ah{x_pred_next, At_next, Bt_next, shape->rank, k_keep, n_dev, prio_dev, drop_next, ws.base.h, sc,
+                 order_next, group_dev_next, mask_next, surv_idx_next, n_surv_next};
+    bool fused = false;
+    hipError_t e = launch_mha_decode(x, shape->d, shape->n_heads, Wq, Wk, Wv, Wo, k_cache, v_cache, max_len, pos,
+                                     mask_cur, y, ws.mha, s, &ah, &fused);
+    if (e != hipSuccess) return HALO_ERR_HIP;
+    if (!fused) {
+        e = launch_predictor(shape->dtype, x_pred_next, 1, shape->d, shape->rank, shape->n_heads, At_next, Bt_next,
+                             ws.base.h, nullptr, s);
+        if (e != hipSuccess) return HALO_ERR_HIP;
+        e = launch_scores_and_mask(shape->dtype, ws.base.h, Bt_next, shape->rank, sc, 1, shape->n_heads, k_keep,
+                                   prio_dev, n_dev, drop_next, order_next, group_dev_next, mask_next,
+                                   surv_idx_next, n_surv_next, s);
+        if (e != hipSuccess) return HALO_ERR_HIP;
+    }
+    return HALO_OK;
 }
 
 int halo_ffn_forward_ahead_q4(const halo_shape *shape, const void *x, int32_t T, const void *Wg_codes,

@@ -61,16 +61,16 @@ inline AheadDev ahead_dev(const AheadArgs &a)
     return AheadDev{a.h, (const bf16_t *)a.Bt, a.r, a.K, a.n_dev, a.prio_dev, a.drop, a.scores, a.order,
                     a.group_dev, a.mask, a.surv_idx, a.n_surv};
 }
+// the one-token down projection on its own (also the attention block's output projection)
+hipError_t launch_down_t1(const bf16_t *Wd, int d, int G, const uint8_t *mask, const bf16_t *act, bf16_t *y,
+                          hipStream_t s, const AheadArgs *ahead = nullptr);
+hipError_t launch_down_generic_bf16(const float *act, int act_stride, int d, int gs, const bf16_t *Wd,
+                                    const int32_t *ulist, const int32_t *meta, bf16_t *y, hipStream_t s);
+
 hipError_t launch_ffn_decode(int dtype, const void *x, int T, int d, int G, int gs, const void *Wg,
                              const void *Wu, const void *Wd, const uint8_t *mask, void *y,
                              const DecodeScratch &ws, hipStream_t s, const AheadArgs *ahead = nullptr,
                              bool *ahead_fused = nullptr);
-
-// the one-token down projection on its own (also the attention block's output projection)
-hipError_t launch_down_t1(const bf16_t *Wd, int d, int G, const uint8_t *mask, const bf16_t *act, bf16_t *y,
-                          hipStream_t s);
-hipError_t launch_down_generic_bf16(const float *act, int act_stride, int d, int gs, const bf16_t *Wd,
-                                    const int32_t *ulist, const int32_t *meta, bf16_t *y, hipStream_t s);
 
 hipError_t launch_union(const uint8_t *mask, int T, int G, int32_t *ulist, int32_t *meta, hipStream_t s);
 
@@ -107,10 +107,12 @@ struct MhaScratch {
     DecodeScratch dec;   // ulist / meta / act as in the FFN
 };
 constexpr int kMhaChunk = 128;
+constexpr int kMhaMaxLen = 131072;   // cache rows: 1024 chunks
 bool mha_shape_supported(int d, int head_dim);
 hipError_t launch_mha_decode(const void *x, int d, int H, const void *Wq, const void *Wk, const void *Wv,
                              const void *Wo, void *k_cache, void *v_cache, int max_len, int pos,
-                             const uint8_t *mask, void *y, const MhaScratch &ws, hipStream_t s);
+                             const uint8_t *mask, void *y, const MhaScratch &ws, hipStream_t s,
+                             const AheadArgs *ahead = nullptr, bool *ahead_fused = nullptr);
 
 // profile.hip : optional HIP-event bracket around the dominant FFN kernel
 bool timer_acquire(hipEvent_t *start, hipEvent_t *stop);   // false: not profiling (or pool used up)

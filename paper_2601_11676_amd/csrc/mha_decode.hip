@@ -72,6 +72,10 @@ struct QkvArgs {
     float *q;                        // [n_surv][128], compact by surviving-head slot
     const uint8_t *mask;             // [H]
     int H, max_len, pos;
+    // the next block's first predictor layer, in the first n_pred workgroups (0 = none)
+    const bf16_t *x_next, *At_next;
+    float *h_next;
+    int r, n_pred;
 };
 
 // pairs of rows [p0, p1) of a job list whose row v comes from src(v) and goes to put(v, value)
@@ -116,7 +120,16 @@ __global__ __launch_bounds__(256) void qkv_rows(QkvArgs a)
 {
     constexpr int d = NCH * 512, dh = kHeadDim;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int nw = gridDim.x * 4, w = blockIdx.x * 4 + wave;
+    if ((int)blockIdx.x < a.n_pred) {
+        // paper Sec. III-B.3, Pred beside Load/Comp, one layer ahead: h_next = ReLU(x_next A)
+        const int j = blockIdx.x * 4 + wave;
+        if (j < a.r) {
+            const float p = dot_order64_fixed<d>(a.x_next, a.At_next + (size_t)j * d, lane);
+            if (lane == 0) a.h_next[j] = p > 0.0f ? p : 0.0f;
+        }
+        return;
+    }
+    const int nw = (gridDim.x - a.n_pred) * 4, w = (blockIdx.x - a.n_pred) * 4 + wave;
     const MaskWords mw = load_mask_words(a.mask, a.H, lane);     // needed only further down
     u32x4 xr[NCH];
 #pragma unroll
@@ -284,23 +297,52 @@ __global__ __launch_bounds__(256) void attn_partial(const float *__restrict__ q,
     }
 }
 
-// grid = H workgroups of 128 threads: o_u = sum_c e^{m_c - M} o_c / sum_c e^{m_c - M} l_c
+// grid = H workgroups of 128 threads: o_u = sum_c e^{m_c - M} o_c / sum_c e^{m_c - M} l_c.
+// The chunk statistics are fetched by one thread per chunk and the value sums in batches of
+// independent loads, so the kernel pays two memory latencies, not two per chunk.
+constexpr int kMaxChunks = 1024;     // 131072 cached positions
+
 template <typename OT>
 __global__ __launch_bounds__(128) void attn_combine(const float *__restrict__ part, const uint8_t *__restrict__ mask,
                                                     int H, int chunks, OT *__restrict__ act)
 {
-    constexpr int dh = kHeadDim;
-    const int u = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
+    constexpr int dh = kHeadDim, kBatch = 8;
+    __shared__ float s_w[kMaxChunks];
+    __shared__ float s_red[2][2];
+    const int u = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const MaskWords mw = load_mask_words(mask, H, lane);
     if (u >= mw.count) return;
     const float *p = part + (size_t)u * chunks * kPartStride;
-    float M = -INFINITY;
-    for (int c = 0; c < chunks; ++c) M = fmaxf(M, p[(size_t)c * kPartStride]);
-    float L = 0.0f, o = 0.0f;
-    for (int c = 0; c < chunks; ++c) {
+    // pass 1: maximum of the chunk maxima
+    float m_loc = -INFINITY;
+    for (int c = tid; c < chunks; c += 128) m_loc = fmaxf(m_loc, p[(size_t)c * kPartStride]);
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) m_loc = fmaxf(m_loc, __shfl_xor(m_loc, off, kWave));
+    if (lane == 0) s_red[0][wave] = m_loc;
+    __syncthreads();
+    const float M = fmaxf(s_red[0][0], s_red[0][1]);
+    // pass 2: chunk weights and the denominator
+    float l_loc = 0.0f;
+    for (int c = tid; c < chunks; c += 128) {
         const float w = __expf(p[(size_t)c * kPartStride] - M);
-        L = __builtin_fmaf(w, p[(size_t)c * kPartStride + 1], L);
-        o = __builtin_fmaf(w, p[(size_t)c * kPartStride + 2 + tid], o);
+        s_w[c] = w;
+        l_loc = __builtin_fmaf(w, p[(size_t)c * kPartStride + 1], l_loc);
+    }
+    l_loc = wave_sum(l_loc);
+    if (lane == 0) s_red[1][wave] = l_loc;
+    __syncthreads();
+    const float L = s_red[1][0] + s_red[1][1];
+    float o = 0.0f;
+    for (int c0 = 0; c0 < chunks; c0 += kBatch) {
+        float v[kBatch];
+#pragma unroll
+        for (int i = 0; i < kBatch; ++i) {
+            const int c = c0 + i < chunks ? c0 + i : chunks - 1;
+            v[i] = p[(size_t)c * kPartStride + 2 + tid];
+        }
+#pragma unroll
+        for (int i = 0; i < kBatch; ++i)
+            if (c0 + i < chunks) o = __builtin_fmaf(s_w[c0 + i], v[i], o);
     }
     store_out(act + u * dh + tid, o / L);
 }
@@ -312,17 +354,26 @@ bool mha_shape_supported(int d, int head_dim) { return head_dim == kHeadDim && d
 
 hipError_t launch_mha_decode(const void *x, int d, int H, const void *Wq, const void *Wk, const void *Wv,
                              const void *Wo, void *k_cache, void *v_cache, int max_len, int pos,
-                             const uint8_t *mask, void *y, const MhaScratch &ws, hipStream_t s)
+                             const uint8_t *mask, void *y, const MhaScratch &ws, hipStream_t s,
+                             const AheadArgs *ahead, bool *ahead_fused)
 {
+    if (ahead_fused) *ahead_fused = false;
     if (H > 256) return hipErrorInvalidValue;                    // the mask-word helpers cover 256 heads
-    QkvArgs qa{(const bf16_t *)x, (const bf16_t *)Wq, (const bf16_t *)Wk, (const bf16_t *)Wv, (bf16_t *)k_cache,
-               (bf16_t *)v_cache, ws.q, mask, H, max_len, pos};
+    const int chunks = pos / kAttnChunk + 1;
+    if (chunks > kMaxChunks) return hipErrorInvalidValue;
     const bool fast = d == 4096 || d == 5120 || d == 8192;
+    const AheadArgs *ah = (fast && ahead && ahead_fused) ? ahead : nullptr;
+    if (ah) *ahead_fused = true;
+    const int n_pred = ah ? (ah->r + 3) / 4 : 0;
+    QkvArgs qa{(const bf16_t *)x, (const bf16_t *)Wq, (const bf16_t *)Wk, (const bf16_t *)Wv, (bf16_t *)k_cache,
+               (bf16_t *)v_cache, ws.q, mask, H, max_len, pos,
+               ah ? (const bf16_t *)ah->x_next : nullptr, ah ? (const bf16_t *)ah->At : nullptr,
+               ah ? ah->h : nullptr, ah ? ah->r : 0, n_pred};
     if (fast) {
         switch (d) {
-        case 4096: launch_timed("qkv_rows", qkv_rows<8>, dim3(256), dim3(256), s, qa); break;
-        case 5120: launch_timed("qkv_rows", qkv_rows<10>, dim3(256), dim3(256), s, qa); break;
-        default: launch_timed("qkv_rows", qkv_rows<16>, dim3(256), dim3(256), s, qa); break;
+        case 4096: launch_timed("qkv_rows", qkv_rows<8>, dim3(256 + n_pred), dim3(256), s, qa); break;
+        case 5120: launch_timed("qkv_rows", qkv_rows<10>, dim3(256 + n_pred), dim3(256), s, qa); break;
+        default: launch_timed("qkv_rows", qkv_rows<16>, dim3(256 + n_pred), dim3(256), s, qa); break;
         }
     } else {
         hipError_t e = launch_union(mask, 1, H, ws.dec.ulist, ws.dec.meta, s);
@@ -330,7 +381,6 @@ hipError_t launch_mha_decode(const void *x, int d, int H, const void *Wq, const 
         launch_timed("qkv_rows_generic", qkv_rows_generic, dim3(512), dim3(256), s, qa, d,
                      (const int32_t *)ws.dec.ulist, (const int32_t *)ws.dec.meta);
     }
-    const int chunks = pos / kAttnChunk + 1;
     attn_partial<<<dim3(chunks, H), dim3(256), 0, s>>>(ws.q, (const bf16_t *)k_cache, (const bf16_t *)v_cache, mask,
                                                        H, max_len, pos, ws.part);
     // the output projection is the FFN's down projection with heads as groups
@@ -338,7 +388,7 @@ hipError_t launch_mha_decode(const void *x, int d, int H, const void *Wq, const 
         attn_combine<bf16_t><<<dim3(H), dim3(128), 0, s>>>(ws.part, mask, H, chunks,
                                                            reinterpret_cast<bf16_t *>(ws.dec.act));
         return launch_down_t1((const bf16_t *)Wo, d, H, mask, reinterpret_cast<const bf16_t *>(ws.dec.act),
-                              (bf16_t *)y, s);
+                              (bf16_t *)y, s, ah);
     }
     attn_combine<float><<<dim3(H), dim3(128), 0, s>>>(ws.part, mask, H, chunks, ws.dec.act);
     return launch_down_generic_bf16(ws.dec.act, H * kHeadDim, d, kHeadDim, (const bf16_t *)Wo, ws.dec.ulist,

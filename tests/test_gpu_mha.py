@@ -189,3 +189,57 @@ def test_mha_many_steps_free_running_cache_and_graph_replay():
         g.replay()
         torch.cuda.synchronize()
         assert torch.equal(yb, ya) and torch.equal(kb, ka) and torch.equal(vb, va)
+
+
+@pytest.mark.parametrize("d", [4096, 1024])
+def test_mha_one_step_ahead_overlap_equals_the_serial_pass(d):
+    # attention of step s with the mask predicted one step earlier, predictor + mask of step s+1 beside
+    # it (d = 4096: in spare workgroups; d = 1024: enqueued afterwards): same bits as the serial form
+    w = dataclasses.replace(hs.LLAMA7B_MHA_DECODE, name="case", d=d, n_heads=10, rank=64, ctx=130, max_len=256, seed=35)
+    _say(f"halo_mha_forward_ahead vs halo_mha_forward d={d}")
+    L = MhaLayer(w)
+    Hh, K, n = w.n_heads, 5, 5
+    pd = torch.from_numpy(H.halo_build_schedule(K, w.device_plr())).to(hz.DEV)
+    xs = [hs.mha_hidden(w, i, hz.DEV) for i in range(n + 1)]
+    dd = [torch.from_numpy(hs.mha_drop_outcomes(w, 0, i)).to(hz.DEV) for i in range(n + 1)]
+    ws = torch.empty(H.halo_mha_workspace_bytes(L.shape, w.max_len), dtype=torch.uint8, device=hz.DEV)
+    k0, v0 = hs.kv_cache(w, 0, hz.DEV)
+    # serial reference on the GPU
+    ka, va = k0.clone(), v0.clone()
+    ya = torch.zeros((n, 1, w.d), dtype=torch.bfloat16, device=hz.DEV)
+    ma = torch.zeros((n + 1, 1, Hh), dtype=torch.uint8, device=hz.DEV)
+    for i in range(n):
+        H.halo_mha_forward(L.shape, xs[i], L.At, L.Bt, L.Wq, L.Wk, L.Wv, L.Wo, ka, va, w.ctx + i, K, pd, w.n_dev,
+                           dd[i], ya[i], ws, mask=ma[i])
+    torch.cuda.synchronize()
+    # overlapped form
+    ffn_shape = H.Shape(w.d, Hh * 128, 128, w.rank, "bf16")
+    sc = torch.empty((1, Hh), dtype=torch.float32, device=hz.DEV)
+    ws2 = torch.empty(H.halo_workspace_bytes(ffn_shape, 1, K), dtype=torch.uint8, device=hz.DEV)
+
+    def run(yb, mb, kb, vb):
+        for i in range(n):
+            H.halo_mha_forward_ahead(L.shape, xs[i], L.Wq, L.Wk, L.Wv, L.Wo, kb, vb, w.ctx + i, mb[i], yb[i],
+                                     xs[i + 1], L.At, L.Bt, K, pd, w.n_dev, dd[i + 1], mb[i + 1], ws)
+
+    kb, vb = k0.clone(), v0.clone()
+    yb = torch.zeros_like(ya)
+    mb = torch.zeros_like(ma)
+    H.halo_predict_scores(ffn_shape, xs[0], L.At, L.Bt, sc, ws2)
+    H.halo_build_group_mask(sc, K, pd, w.n_dev, dd[0], mb[0])
+    run(yb, mb, kb, vb)
+    torch.cuda.synchronize()
+    assert torch.equal(mb[:n], ma[:n]) and torch.equal(yb, ya) and torch.equal(kb, ka) and torch.equal(vb, va)
+    # captured and replayed twice
+    kc, vc = k0.clone(), v0.clone()
+    yc = torch.zeros_like(ya)
+    mc = mb.clone()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        run(yc, mc, kc, vc)
+    for _ in range(2):
+        kc.copy_(k0); vc.copy_(v0); yc.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(yc, ya) and torch.equal(mc, mb) and torch.equal(kc, ka)
