@@ -418,3 +418,49 @@ def test_run_to_run_determinism_and_graph_replay_of_the_serial_pass():
             g.replay()
         torch.cuda.synchronize()
         assert torch.equal(ys, y3) and torch.equal(ms, m3)
+
+
+def test_drop_strategies_low_norm_ordering_loses_less_than_random_ordering():
+    # Paper Sec. II-C: losing low-norm group activations costs far less than losing random ones.  The
+    # strategies differ only in the significance values given to halo_build_group_mask: the groups'
+    # true partial-output norms ("low-norm" ordering, the predictor's training target), or random
+    # values (the Random baseline).  Groups get a heavy-tailed output scale so that norms differ
+    # (the synthetic stand-in for the semantic imbalance the paper observes); the error of the
+    # group-sparse output against the dense block is then compared through the product entry points.
+    w = dataclasses.replace(hs.LLAMA13B_STACK, name="case", d=1024, ffn=16 * 128, rank=64, T=8, layers=1, seed=41)
+    _say("drop strategies: low-norm vs random ordering")
+    s = hz.shape_of(w)
+    T, G, K = w.T, w.n_groups, 8
+    Wg, Wu, WdT = hs.ffn_weights(w, 0, hz.DEV)
+    scale = torch.tensor([2.0 ** (g % 5) for g in range(G)], device=hz.DEV).repeat_interleave(128)
+    WdT = (WdT.float() * scale[:, None]).to(torch.bfloat16)
+    Wd = H.pack_down_proj(WdT, 128)
+    x = hs.hidden_states(w, 0, hz.DEV)
+    ws = torch.empty(H.halo_workspace_bytes(s, T, K), dtype=torch.uint8, device=hz.DEV)
+    pd = torch.from_numpy(H.halo_build_schedule(K, np.zeros(1))).to(hz.DEV)      # one lossless device
+
+    def ffn(mask):
+        y = torch.empty((T, w.d), dtype=torch.bfloat16, device=hz.DEV)
+        H.halo_group_sparse_ffn(s, x, Wg, Wu, Wd, mask, y, ws)
+        torch.cuda.synchronize()
+        return y.float()
+
+    dense = ffn(torch.ones((T, G), dtype=torch.uint8, device=hz.DEV))
+    norms = torch.empty((T, G), dtype=torch.float32, device=hz.DEV)
+    for g in range(G):                                    # ||partial_g(x_t)|| through single-group masks
+        m = torch.zeros((T, G), dtype=torch.uint8, device=hz.DEV)
+        m[:, g] = 1
+        norms[:, g] = ffn(m).norm(dim=1)
+
+    def error_with(scores):
+        mask = torch.empty((T, G), dtype=torch.uint8, device=hz.DEV)
+        H.halo_build_group_mask(scores.contiguous(), K, pd, 1, None, mask)
+        torch.cuda.synchronize()
+        assert (mask.sum(dim=1) == K).all()
+        return float(((ffn(mask) - dense).norm(dim=1) / dense.norm(dim=1)).mean())
+
+    e_norm = error_with(norms)
+    rnd = torch.from_numpy(hs.uniform01(T * G, hs.stream_key(w.seed, hs.TID_MISC)).astype(np.float32)).to(hz.DEV)
+    e_rand = error_with(rnd.view(T, G))
+    e_worst = error_with(-norms)                          # losing the high-norm groups instead
+    assert e_norm < 0.6 * e_rand < e_worst, (e_norm, e_rand, e_worst)
