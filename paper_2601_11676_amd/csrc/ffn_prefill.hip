@@ -282,46 +282,40 @@ __global__ __launch_bounds__(256) void down_pf(
             }
         }
     };
-    // groups in pairs: while group g is multiplied, group g+1's Wd tile travels global -> registers
-    // -> the other LDS buffer and its activation fragments travel to registers; the slots (which
-    // the fragment addresses depend on) are fetched one group further ahead
-    u32x4 rw[4];
+    // groups in pairs.  A group's Wd tile travels global -> registers -> LDS two groups ahead of its
+    // use, its activation fragments one group ahead, the slots (which the fragment addresses depend
+    // on) one group further.  Loads past the last group repeat the last group (harmless).
+    // Top of an even step g: sWd[0] holds W(g); rw1 = W(g+1) and F0 = act(g) are in flight;
+    // (s0, s1) are the slots of group g+1.
+    auto cl = [&](int g) { return g < G ? g : G - 1; };
+    u32x4 rw0[4], rw1[4];
     ActFrags F0, F1;
     int s0 = sl0[0], s1 = sl1[0];
-    int n0 = G > 1 ? sl0[1] : -1, n1 = G > 1 ? sl1[1] : -1;
-    load_w(rw, 0);
+    load_w(rw0, 0);
     load_act(F0, 0, s0, s1);
-    store_w(sWd[0], rw);
+    load_w(rw1, cl(1));
+    s0 = sl0[cl(1)]; s1 = sl1[cl(1)];
+    int n0 = sl0[cl(2)], n1 = sl1[cl(2)];       // slots of group g+2
+    store_w(sWd[0], rw0);
     __syncthreads();
     int g = 0;
-    for (; g + 2 < G; g += 2) {
-        s0 = n0; s1 = n1;                       // slots of group g+1
-        n0 = sl0[g + 2]; n1 = sl1[g + 2];       // slots of group g+2
-        load_w(rw, g + 1);
-        load_act(F1, g + 1, s0, s1);
+    for (; g + 1 < G; g += 2) {
+        load_act(F1, cl(g + 1), s0, s1);
+        load_w(rw0, cl(g + 2));
+        s0 = n0; s1 = n1;                       // slots of group g+2
+        n0 = sl0[cl(g + 3)]; n1 = sl1[cl(g + 3)];
         multiply(sWd[0], F0);
-        store_w(sWd[1], rw);
+        store_w(sWd[1], rw1);
         __syncthreads();
-        s0 = n0; s1 = n1;
-        const int gn = g + 3 < G ? g + 3 : g + 2;
-        n0 = sl0[gn]; n1 = sl1[gn];             // slots of group g+3 (or a harmless repeat)
-        load_w(rw, g + 2);
-        load_act(F0, g + 2, s0, s1);
+        load_act(F0, cl(g + 2), s0, s1);
+        load_w(rw1, cl(g + 3));
+        s0 = n0; s1 = n1;                       // slots of group g+3
+        n0 = sl0[cl(g + 4)]; n1 = sl1[cl(g + 4)];
         multiply(sWd[1], F1);
-        store_w(sWd[0], rw);
+        store_w(sWd[0], rw0);
         __syncthreads();
     }
-    // here sWd[0] / F0 hold group g (G-1 or G-2) and (n0, n1) are the slots of group g+1 if it exists
-    if (g + 1 < G) {
-        load_w(rw, g + 1);
-        load_act(F1, g + 1, n0, n1);
-        multiply(sWd[0], F0);
-        store_w(sWd[1], rw);
-        __syncthreads();
-        multiply(sWd[1], F1);
-    } else {
-        multiply(sWd[0], F0);
-    }
+    if (g < G) multiply(sWd[0], F0);            // an odd number of groups: the last one
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt) {
         const int t = t0 + tt * 16 + i16;
