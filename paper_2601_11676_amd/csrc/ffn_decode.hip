@@ -304,16 +304,18 @@ __device__ __forceinline__ void down_t1_body(DownShared<RQ> &sh, int d, int G,
     const bf16_t *wbase = Wd + (size_t)row * gs + piece;
     const size_t gstride = (size_t)d * gs;
     float acc0 = 0.0f, acc1 = 0.0f;
-    for (int u0 = half; u0 < count; u0 += 2 * kDownBatch) {
-        u32x4 v[kDownBatch], a[kDownBatch];
+    constexpr int kB = kDownBatch / 2;                             // two half batches in flight
+    auto fetch = [&](u32x4 (&v)[kB], u32x4 (&a)[kB], int u0) {
 #pragma unroll
-        for (int q = 0; q < kDownBatch; ++q) {
-            const int u = u0 + 2 * q < count ? u0 + 2 * q : u0;     // past the end: an in-range duplicate
+        for (int q = 0; q < kB; ++q) {
+            const int u = u0 + 2 * q < count ? u0 + 2 * q : (count > 0 ? count - 1 : 0);   // an in-range duplicate
             v[q] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(wbase + sh.list[u] * gstride));
             a[q] = *reinterpret_cast<const u32x4 *>(act + u * gs + piece);
         }
+    };
+    auto mac = [&](const u32x4 (&v)[kB], const u32x4 (&a)[kB], int u0) {
 #pragma unroll
-        for (int q = 0; q < kDownBatch; ++q) {
+        for (int q = 0; q < kB; ++q) {
             if (u0 + 2 * q < count) {
                 acc0 = dot2_bf16(v[q].x, a[q].x, acc0);
                 acc1 = dot2_bf16(v[q].y, a[q].y, acc1);
@@ -321,6 +323,21 @@ __device__ __forceinline__ void down_t1_body(DownShared<RQ> &sh, int d, int G,
                 acc1 = dot2_bf16(v[q].w, a[q].w, acc1);
             }
         }
+    };
+    if (count > 0) {
+        u32x4 v0[kB], a0[kB], v1[kB], a1[kB];
+        fetch(v0, a0, half);
+        fetch(v1, a1, half + 2 * kB);
+        int u0 = half;
+        while (u0 + 4 * kB < count) {
+            mac(v0, a0, u0);
+            fetch(v0, a0, u0 + 4 * kB);
+            mac(v1, a1, u0 + 2 * kB);
+            fetch(v1, a1, u0 + 6 * kB);
+            u0 += 4 * kB;
+        }
+        if (u0 < count) mac(v0, a0, u0);
+        if (u0 + 2 * kB < count) mac(v1, a1, u0 + 2 * kB);
     }
     float v = acc0 + acc1;
     v = dpp_add<0xB1>(v);    // the 16 lanes of a row: quad_perm, quad_perm, half mirror, mirror
