@@ -23,7 +23,7 @@ hipError_t launch_scores_and_mask(int dtype, const float *h, const void *Bt, int
 // ffn_decode.hip : float-ALU paths (any T; tuned for one token)
 struct DecodeScratch {
     int32_t *ulist;     // [G]   groups surviving for at least one token, ascending
-    int32_t *meta;      // [16 + ...] meta[0] = |ulist|; meta[16..] arrival counters
+    int32_t *meta;      // meta[0] = number of entries of ulist
     float *act;         // [T][ffn] activations SiLU(gate)*up, compacted by union slot
                         // (the matrix-core paths store bf16 in the same buffer)
     int32_t *tok_list;  // [G][T] prefill: tokens that keep each group, ascending
