@@ -17,6 +17,7 @@
 #include "kernels.hpp"
 #include "mask_device.hpp"
 #include "mask_words.hpp"
+#include "row_stream.hpp"
 
 namespace halo {
 
@@ -140,25 +141,6 @@ __global__ __launch_bounds__(256) void down_generic(
 // ---------------------------------------------------------------------------
 // one token, bf16, d = NCH*512, group size 128, G <= 256: the decode hot path
 // ---------------------------------------------------------------------------
-template <int NCH>
-struct RowPair {
-    u32x4 g[NCH], u[NCH];
-};
-
-template <int NCH>
-__device__ __forceinline__ void load_rows(RowPair<NCH> &r, const bf16_t *__restrict__ Wg,
-                                          const bf16_t *__restrict__ Wu, size_t row, int lane)
-{
-    constexpr int d = NCH * 512;
-    const u32x4 *pg = reinterpret_cast<const u32x4 *>(Wg + row * d) + lane;
-    const u32x4 *pu = reinterpret_cast<const u32x4 *>(Wu + row * d) + lane;
-#pragma unroll
-    for (int k = 0; k < NCH; ++k) {
-        r.g[k] = __builtin_nontemporal_load(pg + k * kWave);
-        r.u[k] = __builtin_nontemporal_load(pu + k * kWave);
-    }
-}
-
 // x stays packed (two bf16 per register); products go through the packed dot instruction
 template <int NCH>
 __device__ __forceinline__ float gate_up_dot(const RowPair<NCH> &r, const u32x4 (&xr)[NCH])

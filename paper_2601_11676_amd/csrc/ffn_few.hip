@@ -1,0 +1,141 @@
+// Gate/up projection for a few tokens (2..8) on the float ALUs, bf16.
+//
+// With a handful of tokens the block is still bound by streaming the union of the tokens'
+// surviving groups from HBM: 2*T multiply-adds per weight element fit beside the memory time of
+// that element as long as T is small.  So the kernel is the one-token kernel with more columns:
+// one wave per neuron, the neuron's gate and up rows fetched with 16-byte non-temporal loads
+// (1 KiB of consecutive bytes per instruction, no re-shaping), the next neuron's rows in flight
+// while the current one is reduced, and every weight register used T times against the token
+// rows of x, which live in LDS for the whole kernel.  (The matrix-core form of this kernel
+// re-shapes every weight tile through LDS and keeps fewer bytes in flight per row; it reached
+// 3.5 TB/s on a 63-group union of the 13B shape and 5.8 TB/s on the 70B shape.)
+// Output: act[t][n] = mask[t][group of n] ? SiLU(gate) * up : 0, bf16, n = position in the union.
+#include "kernels.hpp"
+#include "mask_words.hpp"
+#include "row_stream.hpp"
+
+namespace halo {
+
+template <int NCH, int TMAX>
+__global__ __launch_bounds__(256) void gate_up_ft(
+    const bf16_t *__restrict__ x, int T, int G, int gs, const bf16_t *__restrict__ Wg,
+    const bf16_t *__restrict__ Wu, const uint8_t *__restrict__ mask, bf16_t *__restrict__ act, int act_stride)
+{
+    constexpr int d = NCH * 512, XR = d + 8;                 // LDS row of x, elements (16-byte aligned)
+    extern __shared__ __attribute__((aligned(16))) bf16_t sx[];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    // the union of the tokens' surviving groups, built by every wave from the T*G mask bytes
+    // (no separate launch, no list in memory between the mask and the first weight load)
+    const MaskWords uw = load_union_words<TMAX>(mask, T, G, lane);
+    for (int p = tid; p < T * (d / 8); p += 256) {
+        const int t = p / (d / 8), e = (p - t * (d / 8)) * 8;
+        *reinterpret_cast<u32x4 *>(sx + t * XR + e) = *reinterpret_cast<const u32x4 *>(x + (size_t)t * d + e);
+    }
+    __syncthreads();
+    const long long total = (long long)uw.count * gs;
+    const int nw = gridDim.x * 4, w = blockIdx.x * 4 + wave;
+    const int n0 = (int)(total * w / nw), n1 = (int)(total * (w + 1) / nw);
+    if (n0 >= n1) return;                                    // no barrier below
+    // a run is shorter than a group (total / nw <= gs), so it touches at most two groups: their ids
+    // and the tokens' mask bits for them are fetched up front
+    const int u_first = n0 / gs, u_last = (n1 - 1) / gs;
+    const int g_first = nth_group(uw, u_first, lane), g_last = nth_group(uw, u_last, lane);
+    unsigned keep_first = 0, keep_last = 0;
+#pragma unroll
+    for (int t = 0; t < TMAX; ++t) {
+        const int tc = t < T ? t : T - 1;
+        const unsigned a = mask[(size_t)tc * G + g_first], b = mask[(size_t)tc * G + g_last];
+        if (t < T) {
+            keep_first |= (a ? 1u : 0u) << t;
+            keep_last |= (b ? 1u : 0u) << t;
+        }
+    }
+    auto row_of = [&](int n) -> size_t {
+        const int u = n / gs;
+        return (size_t)(u == u_first ? g_first : g_last) * gs + (n - u * gs);
+    };
+    const bf16_t *xl = sx + lane * 8;
+    auto finish = [&](const RowPair<NCH> &r, int n) {
+        float ag[TMAX], au[TMAX];
+#pragma unroll
+        for (int t = 0; t < TMAX; ++t) ag[t] = au[t] = 0.0f;
+#pragma unroll
+        for (int k = 0; k < NCH; ++k) {
+#pragma unroll
+            for (int t = 0; t < TMAX; ++t) {
+                if (t < T) {                                 // uniform
+                    const u32x4 xv = *reinterpret_cast<const u32x4 *>(xl + t * XR + k * 512);
+                    ag[t] = dot2_bf16(r.g[k].x, xv.x, ag[t]);
+                    au[t] = dot2_bf16(r.u[k].x, xv.x, au[t]);
+                    ag[t] = dot2_bf16(r.g[k].y, xv.y, ag[t]);
+                    au[t] = dot2_bf16(r.u[k].y, xv.y, au[t]);
+                    ag[t] = dot2_bf16(r.g[k].z, xv.z, ag[t]);
+                    au[t] = dot2_bf16(r.u[k].z, xv.z, au[t]);
+                    ag[t] = dot2_bf16(r.g[k].w, xv.w, ag[t]);
+                    au[t] = dot2_bf16(r.u[k].w, xv.w, au[t]);
+                }
+            }
+        }
+        const unsigned keep = (n / gs == u_first) ? keep_first : keep_last;
+        float mine = 0.0f;
+#pragma unroll
+        for (int t = 0; t < TMAX; ++t) {
+            if (t < T) {
+                const float v = silu_mul(wave_sum_fast(ag[t]), wave_sum_fast(au[t]));
+                if (lane == t) mine = ((keep >> t) & 1u) ? v : 0.0f;
+            }
+        }
+        if (lane < T) act[(size_t)lane * act_stride + n] = f32_to_bf16(mine);
+    };
+    RowPair<NCH> A, B;
+    load_rows<NCH>(A, Wg, Wu, row_of(n0), lane);
+    int n = n0;
+    while (n + 2 < n1) {
+        load_rows<NCH>(B, Wg, Wu, row_of(n + 1), lane);
+        finish(A, n);
+        load_rows<NCH>(A, Wg, Wu, row_of(n + 2), lane);
+        finish(B, n + 1);
+        n += 2;
+    }
+    if (n + 1 < n1) {
+        load_rows<NCH>(B, Wg, Wu, row_of(n + 1), lane);
+        finish(A, n);
+        finish(B, n + 1);
+    } else {
+        finish(A, n);
+    }
+}
+
+bool few_path_supported(int T, int d, int G, int gs)
+{
+    // up to 4 tokens: beyond that the 2*T multiply-adds per weight element no longer hide behind its
+    // memory time (8 tokens at the 70B shape: 250 us against 150 us for the matrix-core kernel)
+    return T >= 2 && T <= 4 && gs == 128 && G <= 256 && (d == 4096 || d == 5120 || d == 8192);
+}
+
+template <int NCH, int TMAX>
+static hipError_t launch_one(const bf16_t *x, int T, int G, int gs, const bf16_t *Wg, const bf16_t *Wu,
+                             const uint8_t *mask, bf16_t *act, int act_stride, hipStream_t s)
+{
+    constexpr size_t kMaxLds = 144 * 1024;
+    static const hipError_t lds_ok = hipFuncSetAttribute(reinterpret_cast<const void *>(gate_up_ft<NCH, TMAX>),
+                                                         hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLds);
+    if (lds_ok != hipSuccess) return lds_ok;
+    const size_t lds = (size_t)T * (NCH * 512 + 8) * sizeof(bf16_t);
+    launch_timed_lds("gate_up_ft", gate_up_ft<NCH, TMAX>, dim3(256), dim3(256), lds, s, x, T, G, gs, Wg, Wu, mask,
+                     act, act_stride);
+    return hipGetLastError();
+}
+
+hipError_t launch_gate_up_few(const bf16_t *x, int T, int d, int G, int gs, const bf16_t *Wg, const bf16_t *Wu,
+                              const uint8_t *mask, bf16_t *act, int act_stride, hipStream_t s)
+{
+    switch (d) {
+    case 4096: return launch_one<8, 4>(x, T, G, gs, Wg, Wu, mask, act, act_stride, s);
+    case 5120: return launch_one<10, 4>(x, T, G, gs, Wg, Wu, mask, act, act_stride, s);
+    case 8192: return launch_one<16, 4>(x, T, G, gs, Wg, Wu, mask, act, act_stride, s);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace halo

@@ -16,6 +16,7 @@
 // 8*(l/16)..+7 of the 32; B lane l holds column l%16, same elements; D lane l holds
 // column l%16, rows 4*(l/16)..+3.  Rows are neurons (or outputs j), columns are tokens.
 #include "kernels.hpp"
+#include "mask_words.hpp"
 
 namespace halo {
 
@@ -144,18 +145,40 @@ __global__ __launch_bounds__(256) void gate_up_mt(
 constexpr int kDownGroups = 4;              // groups in flight per wave
 constexpr int kTileRow = 128 + 8;           // padded LDS row, elements
 
+// UNION_IN_KERNEL: the union list is built here from the tokens' masks (T <= 4, G <= 256) instead of
+// being read from memory (ulist / meta written by an earlier launch).
+template <bool UNION_IN_KERNEL>
 __global__ __launch_bounds__(256) void down_mt(
-    int T, int d, const bf16_t *__restrict__ Wd, const int32_t *__restrict__ ulist,
-    const int32_t *__restrict__ meta, const bf16_t *__restrict__ act, int act_stride,
-    bf16_t *__restrict__ y)
+    int T, int d, int G, const bf16_t *__restrict__ Wd, const uint8_t *__restrict__ mask,
+    const int32_t *__restrict__ ulist_mem, const int32_t *__restrict__ meta,
+    const bf16_t *__restrict__ act, int act_stride, bf16_t *__restrict__ y)
 {
     constexpr int gs = 128;
     __shared__ __attribute__((aligned(16))) bf16_t sT[4][kDownGroups][16 * kTileRow];
     __shared__ float red[4][64][4];
+    __shared__ int s_list[256];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int i = lane & 15, q = lane >> 4;
     const int j0 = blockIdx.x * 16;
-    const int n_u = meta[0];
+    int n_u;
+    const int32_t *ulist = ulist_mem;
+    if (UNION_IN_KERNEL) {
+        const MaskWords uw = load_union_words<4>(mask, T, G, lane);
+        if (wave == 0) {
+            int base = 0;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                if ((uw.w[k] >> lane) & 1ull)
+                    s_list[base + __popcll(uw.w[k] & ((1ull << lane) - 1ull))] = k * kWave + lane;
+                base += __popcll(uw.w[k]);
+            }
+        }
+        __syncthreads();
+        n_u = uw.count;
+        ulist = s_list;
+    } else {
+        n_u = meta[0];
+    }
     const int u0 = n_u * wave / 4, u1 = n_u * (wave + 1) / 4;
     const int tok = i < T ? i : T - 1;
     const bf16_t *arow = act + (size_t)tok * act_stride + q * 8;
@@ -218,12 +241,19 @@ hipError_t launch_ffn_mfma(const bf16_t *x, int T, int d, int G, int gs, const b
 {
     const int ffn = G * gs;
     bf16_t *act = reinterpret_cast<bf16_t *>(ws.act);
+    if (few_path_supported(T, d, G, gs)) {
+        // up to four tokens: rows streamed as in the one-token path, union built inside the kernels
+        hipError_t e = launch_gate_up_few(x, T, d, G, gs, Wg, Wu, mask, act, ffn, s);
+        if (e != hipSuccess) return e;
+        down_mt<true><<<dim3(d / 16), dim3(256), 0, s>>>(T, d, G, Wd, mask, nullptr, nullptr, act, ffn, y);
+        return hipGetLastError();
+    }
     hipError_t e = launch_union(mask, T, G, ws.ulist, ws.meta, s);
     if (e != hipSuccess) return e;
     // one workgroup per compute unit (the kernel holds two row batches in registers, one wave per SIMD)
     launch_timed("gate_up_mt", gate_up_mt, dim3(256), dim3(256), s, x, T, d, G, gs, Wg, Wu, mask,
                  (const int32_t *)ws.ulist, (const int32_t *)ws.meta, act, ffn);
-    down_mt<<<dim3(d / 16), dim3(256), 0, s>>>(T, d, Wd, ws.ulist, ws.meta, act, ffn, y);
+    down_mt<false><<<dim3(d / 16), dim3(256), 0, s>>>(T, d, G, Wd, mask, ws.ulist, ws.meta, act, ffn, y);
     return hipGetLastError();
 }
 

@@ -80,6 +80,11 @@ hipError_t launch_ffn_mfma(const bf16_t *x, int T, int d, int G, int gs, const b
                            const bf16_t *Wu, const bf16_t *Wd, const uint8_t *mask, bf16_t *y,
                            const DecodeScratch &ws, hipStream_t s);
 
+// ffn_few.hip : gate/up for 2..8 tokens on the float ALUs (rows streamed as in the one-token path)
+bool few_path_supported(int T, int d, int G, int gs);
+hipError_t launch_gate_up_few(const bf16_t *x, int T, int d, int G, int gs, const bf16_t *Wg, const bf16_t *Wu,
+                              const uint8_t *mask, bf16_t *act, int act_stride, hipStream_t s);
+
 // ffn_prefill.hip : bf16 matrix-core path for many tokens
 bool prefill_path_supported(int T, int d, int gs);
 hipError_t launch_ffn_prefill(const bf16_t *x, int T, int d, int G, int gs, const bf16_t *Wg,

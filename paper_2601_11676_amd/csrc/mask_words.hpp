@@ -32,6 +32,33 @@ __device__ __forceinline__ MaskWords load_mask_words(const uint8_t *__restrict__
     return mw;
 }
 
+// The union of T tokens' masks ([T][G] bytes) in the same form: a group is in it if any token
+// keeps it.  All T*4 byte loads are issued together.  TMAX bounds T at compile time.
+template <int TMAX>
+__device__ __forceinline__ MaskWords load_union_words(const uint8_t *__restrict__ mask, int T, int G, int lane)
+{
+    uint8_t v[TMAX][4];
+#pragma unroll
+    for (int t = 0; t < TMAX; ++t)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int g = k * kWave + lane;
+            v[t][k] = mask[(size_t)(t < T ? t : T - 1) * G + (g < G ? g : 0)];
+        }
+    MaskWords mw;
+    mw.count = 0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int g = k * kWave + lane;
+        uint8_t any = 0;
+#pragma unroll
+        for (int t = 0; t < TMAX; ++t) any |= v[t][k];
+        mw.w[k] = __ballot(g < G && any != 0);
+        mw.count += __popcll(mw.w[k]);
+    }
+    return mw;
+}
+
 // index of the u-th surviving group (u < count), wave-uniform
 __device__ __forceinline__ int nth_group(const MaskWords &mw, int u, int lane)
 {
