@@ -46,15 +46,37 @@ struct RowRegs {
     u32x4 v[16];
 };
 
+// UNION_IN_KERNEL (T <= 16, G <= 256): the union list is built here from the tokens' masks instead of
+// being read from memory (ulist / meta written by an earlier launch).
+template <bool UNION_IN_KERNEL>
 __global__ __launch_bounds__(256) void gate_up_mt(
     const bf16_t *__restrict__ x, int T, int d, int G, int gs, const bf16_t *__restrict__ Wg,
-    const bf16_t *__restrict__ Wu, const uint8_t *__restrict__ mask, const int32_t *__restrict__ ulist,
+    const bf16_t *__restrict__ Wu, const uint8_t *__restrict__ mask, const int32_t *__restrict__ ulist_mem,
     const int32_t *__restrict__ meta, bf16_t *__restrict__ act, int act_stride)
 {
     __shared__ __attribute__((aligned(16))) bf16_t sW[4][16 * kChunkRow];
+    __shared__ int s_list[256];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     bf16_t *my = sW[wave];
-    const long long total = (long long)meta[0] * gs;
+    const int32_t *ulist = ulist_mem;
+    long long total;
+    if (UNION_IN_KERNEL) {
+        const MaskWords uw = load_union_words<16>(mask, T, G, lane);
+        if (wave == 0) {
+            int base = 0;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                if ((uw.w[k] >> lane) & 1ull)
+                    s_list[base + __popcll(uw.w[k] & ((1ull << lane) - 1ull))] = k * kWave + lane;
+                base += __popcll(uw.w[k]);
+            }
+        }
+        __syncthreads();
+        total = (long long)uw.count * gs;
+        ulist = s_list;
+    } else {
+        total = (long long)meta[0] * gs;
+    }
     int nw = gridDim.x * 4;
     const long long want = (total + 11) / 12;
     if (want < nw) nw = want < 1 ? 1 : (int)want;
@@ -145,8 +167,7 @@ __global__ __launch_bounds__(256) void gate_up_mt(
 constexpr int kDownGroups = 4;              // groups in flight per wave
 constexpr int kTileRow = 128 + 8;           // padded LDS row, elements
 
-// UNION_IN_KERNEL: the union list is built here from the tokens' masks (T <= 4, G <= 256) instead of
-// being read from memory (ulist / meta written by an earlier launch).
+// UNION_IN_KERNEL: as in gate_up_mt.
 template <bool UNION_IN_KERNEL>
 __global__ __launch_bounds__(256) void down_mt(
     int T, int d, int G, const bf16_t *__restrict__ Wd, const uint8_t *__restrict__ mask,
@@ -163,7 +184,7 @@ __global__ __launch_bounds__(256) void down_mt(
     int n_u;
     const int32_t *ulist = ulist_mem;
     if (UNION_IN_KERNEL) {
-        const MaskWords uw = load_union_words<4>(mask, T, G, lane);
+        const MaskWords uw = load_union_words<16>(mask, T, G, lane);
         if (wave == 0) {
             int base = 0;
 #pragma unroll
@@ -248,10 +269,17 @@ hipError_t launch_ffn_mfma(const bf16_t *x, int T, int d, int G, int gs, const b
         down_mt<true><<<dim3(d / 16), dim3(256), 0, s>>>(T, d, G, Wd, mask, nullptr, nullptr, act, ffn, y);
         return hipGetLastError();
     }
+    if (G <= 256) {
+        // the union of the tokens' groups is built inside the kernels: no union launch, no list in memory
+        launch_timed("gate_up_mt", gate_up_mt<true>, dim3(256), dim3(256), s, x, T, d, G, gs, Wg, Wu, mask,
+                     (const int32_t *)nullptr, (const int32_t *)nullptr, act, ffn);
+        down_mt<true><<<dim3(d / 16), dim3(256), 0, s>>>(T, d, G, Wd, mask, nullptr, nullptr, act, ffn, y);
+        return hipGetLastError();
+    }
     hipError_t e = launch_union(mask, T, G, ws.ulist, ws.meta, s);
     if (e != hipSuccess) return e;
     // one workgroup per compute unit (the kernel holds two row batches in registers, one wave per SIMD)
-    launch_timed("gate_up_mt", gate_up_mt, dim3(256), dim3(256), s, x, T, d, G, gs, Wg, Wu, mask,
+    launch_timed("gate_up_mt", gate_up_mt<false>, dim3(256), dim3(256), s, x, T, d, G, gs, Wg, Wu, mask,
                  (const int32_t *)ws.ulist, (const int32_t *)ws.meta, act, ffn);
     down_mt<false><<<dim3(d / 16), dim3(256), 0, s>>>(T, d, G, Wd, mask, ws.ulist, ws.meta, act, ffn, y);
     return hipGetLastError();
