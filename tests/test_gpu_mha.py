@@ -243,3 +243,14 @@ def test_mha_one_step_ahead_overlap_equals_the_serial_pass(d):
         g.replay()
         torch.cuda.synchronize()
         assert torch.equal(yc, ya) and torch.equal(mc, mb) and torch.equal(kc, ka)
+
+
+def test_mha_long_context_many_chunks():
+    # 8191 cached rows = 64 chunks of 128 per surviving head
+    w = dataclasses.replace(hs.LLAMA7B_MHA_DECODE, name="case", n_heads=6, rank=64, ctx=8191, max_len=8192, seed=36)
+    _say("mha long context")
+    L = MhaLayer(w)
+    kc, vc = hs.kv_cache(w, 0, hz.DEV)
+    pd = H.halo_build_schedule(3, w.device_plr())
+    _check_step(L, hs.mha_hidden(w, 0, hz.DEV), kc, vc, w.ctx, 3, pd, None)
+    _check_step(L, hs.mha_hidden(w, 1, hz.DEV), kc, vc, 4095, 6, H.halo_build_schedule(6, w.device_plr()), None)

@@ -152,3 +152,41 @@ def test_q4_one_step_ahead_overlap_equals_the_serial_pass(d, T):
         g.replay()
         torch.cuda.synchronize()
         assert torch.equal(ys2, ys) and torch.equal(masks2, masks)
+
+
+@pytest.mark.parametrize("wl", [hs.LLAMA13B_STACK, hs.LLAMA70B_STACK])
+def test_q4_full_size_single_layer_of_the_stacks(wl):
+    # 4 / 8 tokens at the 13B / 70B layer shapes (the plain 4-bit path); y for every token
+    _say(f"q4 {wl.name} one full-size layer")
+    L = hz.Q4Layer(wl, layer=2)
+    x = hs.hidden_states(wl, 0, hz.DEV)
+    K = wl.k_keep(0.5)
+    pd = H.halo_build_schedule(K, wl.device_plr())
+    drop = hs.drop_outcomes(wl, 2, 0)
+    g = hz.gpu_forward_q4(wl, L, x, K, pd, drop)
+    c = hz.oracle_forward(wl, L, x, K, pd, drop)
+    hz.assert_parity(g, c, TOL["bf16"], "q4 " + wl.name)
+
+
+def test_q4_llama7b_prefill_sampled_tokens():
+    w = hs.LLAMA7B_PREFILL
+    _say("q4 7B prefill, 512 tokens")
+    L = hz.Q4Layer(w)
+    x = hs.hidden_states(w, 0, hz.DEV)
+    K = w.k_keep()
+    pd = H.halo_build_schedule(K, w.device_plr())
+    drop = hs.drop_outcomes(w)
+    g = hz.gpu_forward_q4(w, L, x, K, pd, drop)
+    At, Bt, Wg, Wu, WdT = L.host()
+    xn = hz.to_np32(x)
+    sc = ref.predict_scores(xn, At, Bt)
+    assert np.array_equal(g["scores"].view(np.uint32), sc.view(np.uint32))
+    m = ref.build_group_mask(sc, K, pd, w.n_dev, drop)
+    for k in hz.INT_KEYS:
+        assert np.array_equal(g[k], m[k]), k
+    sample = [0, 1, 255, 256, 511] + [int(t) for t in np.where(m["n_surv"] == m["n_surv"].min())[0][:1]]
+    y_ref = ref.group_sparse_ffn(xn[sample], Wg, Wu, WdT, w.group_size, m["mask"][sample])
+    for k, t in enumerate(sample):
+        err = np.linalg.norm(g["y"][t] - y_ref[k]) / np.linalg.norm(y_ref[k])
+        assert err <= TOL["bf16"], (t, err)
+    assert np.isfinite(g["y"]).all()
