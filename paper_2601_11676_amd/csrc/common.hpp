@@ -90,12 +90,49 @@ __device__ __forceinline__ void store8(bf16_t *p, const float (&v)[8])
     *reinterpret_cast<u32x4 *>(p) = o;
 }
 
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float v)
+{
+    const int o = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true);
+    return v + __builtin_bit_cast(float, o);
+}
+
+// v + (v of lane ^ OFF) for every lane, OFF in {32, 16, 8, 4, 2, 1}: one step of the butterfly the
+// predictor's summation order is made of.  Each distance uses the cheapest exchange gfx950 has for
+// exactly that pairing: the half-wave and row swaps (the sum of the two swapped copies is the sum
+// of the pair in both lanes), a swizzle within 32 lanes, the quad permutations of the DPP path.
+template <int OFF>
+__device__ __forceinline__ float xor_add(float v)
+{
+    static_assert(OFF == 32 || OFF == 16 || OFF == 8 || OFF == 4 || OFF == 2 || OFF == 1, "butterfly distance");
+    if constexpr (OFF == 32) {
+        const unsigned u = __builtin_bit_cast(unsigned, v);
+        const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+        return __builtin_bit_cast(float, (unsigned)r[0]) + __builtin_bit_cast(float, (unsigned)r[1]);
+    } else if constexpr (OFF == 16) {
+        const unsigned u = __builtin_bit_cast(unsigned, v);
+        const auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+        return __builtin_bit_cast(float, (unsigned)r[0]) + __builtin_bit_cast(float, (unsigned)r[1]);
+    } else if constexpr (OFF == 8 || OFF == 4) {
+        const int o = __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, v), (OFF << 10) | 0x1f);
+        return v + __builtin_bit_cast(float, o);
+    } else if constexpr (OFF == 2) {
+        return dpp_add<0x4E>(v);            // quad_perm [2,3,0,1]
+    } else {
+        return dpp_add<0xB1>(v);            // quad_perm [1,0,3,2]
+    }
+}
+
 // Butterfly sum over the 64 lanes of a wave, partner distance 32,16,8,4,2,1.
 // Every lane ends with the same value (float addition is commutative).
 __device__ __forceinline__ float wave_sum(float v)
 {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) v = v + __shfl_xor(v, off, kWave);
+    v = xor_add<32>(v);
+    v = xor_add<16>(v);
+    v = xor_add<8>(v);
+    v = xor_add<4>(v);
+    v = xor_add<2>(v);
+    v = xor_add<1>(v);
     return v;
 }
 
@@ -146,13 +183,6 @@ __device__ __forceinline__ float dot_order64_fixed(const bf16_t *__restrict__ xp
 
 // Wave-wide sum through the DPP cross-lane paths (no LDS traffic); result is uniform.
 // Used where the summation order is free (FFN dot products), not by the predictor.
-template <int CTRL>
-__device__ __forceinline__ float dpp_add(float v)
-{
-    const int o = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true);
-    return v + __builtin_bit_cast(float, o);
-}
-
 __device__ __forceinline__ float wave_sum_fast(float v)
 {
     v = dpp_add<0xB1>(v);    // quad_perm [1,0,3,2]

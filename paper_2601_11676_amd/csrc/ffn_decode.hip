@@ -269,15 +269,7 @@ __device__ __forceinline__ void down_t1_body(DownShared<RQ> &sh, int d, int G,
     constexpr int gs = 128;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const MaskWords mw = load_mask_words(mask, G, lane);
-    if (wave == 0) {
-        int base = 0;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            if ((mw.w[k] >> lane) & 1ull)
-                sh.list[base + __popcll(mw.w[k] & ((1ull << lane) - 1ull))] = k * kWave + lane;
-            base += __popcll(mw.w[k]);
-        }
-    }
+    if (wave == 0) write_group_list(mw, lane, sh.list);
     __syncthreads();
     const int count = mw.count;
     const int rq = wave % RQ, half = wave / RQ;                     // row quad, even/odd groups

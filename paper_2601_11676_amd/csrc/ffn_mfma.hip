@@ -62,15 +62,7 @@ __global__ __launch_bounds__(256) void gate_up_mt(
     long long total;
     if (UNION_IN_KERNEL) {
         const MaskWords uw = load_union_words<16>(mask, T, G, lane);
-        if (wave == 0) {
-            int base = 0;
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                if ((uw.w[k] >> lane) & 1ull)
-                    s_list[base + __popcll(uw.w[k] & ((1ull << lane) - 1ull))] = k * kWave + lane;
-                base += __popcll(uw.w[k]);
-            }
-        }
+        if (wave == 0) write_group_list(uw, lane, s_list);
         __syncthreads();
         total = (long long)uw.count * gs;
         ulist = s_list;
@@ -185,15 +177,7 @@ __global__ __launch_bounds__(256) void down_mt(
     const int32_t *ulist = ulist_mem;
     if (UNION_IN_KERNEL) {
         const MaskWords uw = load_union_words<16>(mask, T, G, lane);
-        if (wave == 0) {
-            int base = 0;
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                if ((uw.w[k] >> lane) & 1ull)
-                    s_list[base + __popcll(uw.w[k] & ((1ull << lane) - 1ull))] = k * kWave + lane;
-                base += __popcll(uw.w[k]);
-            }
-        }
+        if (wave == 0) write_group_list(uw, lane, s_list);
         __syncthreads();
         n_u = uw.count;
         ulist = s_list;

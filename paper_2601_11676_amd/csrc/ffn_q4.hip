@@ -202,15 +202,7 @@ __global__ __launch_bounds__(512, 4) void down_q4_t1(int d, int G, const uint32_
         u32x4 *adst = reinterpret_cast<u32x4 *>(sh.act);
         for (int i = tid; i < count * 16; i += 512) adst[i] = asrc[i];
     }
-    if (wave == 0) {
-        int base = 0;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            if ((mw.w[k] >> lane) & 1ull)
-                sh.list[base + __popcll(mw.w[k] & ((1ull << lane) - 1ull))] = k * kWave + lane;
-            base += __popcll(mw.w[k]);
-        }
-    }
+    if (wave == 0) write_group_list(mw, lane, sh.list);
     __syncthreads();
     for (int i = tid; i < count * 4; i += 512) {
         u32x4 a[4];

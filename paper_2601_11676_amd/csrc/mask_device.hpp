@@ -88,15 +88,11 @@ __device__ __forceinline__ void mask_scores_block(
 #pragma unroll
                     for (int e = 0; e < 8; ++e) p[b] = __builtin_fmaf(hx[e], wf[e], p[b]);
                 }
-                // the eight butterflies advance together: one exchange round trip per distance
-#pragma unroll
-                for (int off = 32; off >= 1; off >>= 1) {
-                    float q[GB];
-#pragma unroll
-                    for (int b = 0; b < GB; ++b) q[b] = __shfl_xor(p[b], off, kWave);
-#pragma unroll
-                    for (int b = 0; b < GB; ++b) p[b] = p[b] + q[b];
-                }
+                // the butterflies advance together, distance by distance
+#define HALO_STEP(OFF)                                           \
+    _Pragma("unroll") for (int b = 0; b < GB; ++b) p[b] = xor_add<OFF>(p[b]);
+                HALO_STEP(32) HALO_STEP(16) HALO_STEP(8) HALO_STEP(4) HALO_STEP(2) HALO_STEP(1)
+#undef HALO_STEP
 #pragma unroll
                 for (int b = 0; b < GB; ++b) {
                     const int g = g0 + kWaves * b;

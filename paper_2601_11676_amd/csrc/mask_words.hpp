@@ -59,6 +59,17 @@ __device__ __forceinline__ MaskWords load_union_words(const uint8_t *__restrict_
     return mw;
 }
 
+// The groups of `mw` in ascending order, written by ONE wave to list[0 .. count-1] (LDS or global).
+__device__ __forceinline__ void write_group_list(const MaskWords &mw, int lane, int *list)
+{
+    int base = 0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        if ((mw.w[k] >> lane) & 1ull) list[base + __popcll(mw.w[k] & ((1ull << lane) - 1ull))] = k * kWave + lane;
+        base += __popcll(mw.w[k]);
+    }
+}
+
 // index of the u-th surviving group (u < count), wave-uniform
 __device__ __forceinline__ int nth_group(const MaskWords &mw, int u, int lane)
 {

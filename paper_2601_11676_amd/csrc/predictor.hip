@@ -77,18 +77,11 @@ __global__ __launch_bounds__(256) void hidden_rows_kernel(const bf16_t *__restri
                     for (int e = 0; e < 8; ++e) p[c][b] = __builtin_fmaf(xf[e], wr[b][k][e], p[c][b]);
             }
         }
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) {
-            float qv[TB][JB];
-#pragma unroll
-            for (int c = 0; c < TB; ++c)
-#pragma unroll
-                for (int b = 0; b < JB; ++b) qv[c][b] = __shfl_xor(p[c][b], off, kWave);
-#pragma unroll
-            for (int c = 0; c < TB; ++c)
-#pragma unroll
-                for (int b = 0; b < JB; ++b) p[c][b] = p[c][b] + qv[c][b];
-        }
+#define HALO_STEP(OFF)                                               \
+    _Pragma("unroll") for (int c = 0; c < TB; ++c)                   \
+        _Pragma("unroll") for (int b = 0; b < JB; ++b) p[c][b] = xor_add<OFF>(p[c][b]);
+        HALO_STEP(32) HALO_STEP(16) HALO_STEP(8) HALO_STEP(4) HALO_STEP(2) HALO_STEP(1)
+#undef HALO_STEP
         if (lane == 0) {
 #pragma unroll
             for (int c = 0; c < TB; ++c)
