@@ -6,12 +6,9 @@
 //
 //   group_tokens : for every group, the ascending list of tokens that keep it, and for
 //                  every (token, group) the token's slot in that list (-1 = not kept).
-//   gate_up_pf   : one workgroup = 64 neurons of one group x up to 128 of the group's
-//                  tokens.  The 128 weight rows (64 gate + 64 up) are staged through LDS once
-//                  per 64-element K step and shared by the four waves; each wave owns 32
-//                  tokens and loads their x rows (gathered by the token list) straight into
-//                  registers as the B operand.  A group's weights are read once from HBM and
-//                  once more from cache per further 128 tokens.
+//   gate_up_pf_ring : one workgroup = 64 neurons of one group (64 gate + 64 up rows) x up to 256
+//                  of the group's tokens (x rows gathered by the token list); both operands
+//                  travel straight from memory into a ring of K stages in LDS.
 //                  act[g][slot][m] = SiLU(gate) * up in bf16.
 //   down_pf      : output-stationary: one workgroup = 128 tokens x 64 outputs, walking all
 //                  groups (Wd tiles through LDS, activation rows gathered into registers); a
@@ -20,6 +17,7 @@
 //
 // v_mfma_f32_16x16x32_bf16 operand layout as in ffn_mfma.hip: A lane l = row l%16, elements
 // 8*(l/16)..+7; B lane l = column l%16, same elements; D lane l = column l%16, rows 4*(l/16)..+3.
+
 #include "kernels.hpp"
 
 namespace halo {
@@ -65,141 +63,287 @@ __global__ __launch_bounds__(256) void group_tokens_kernel(const uint8_t *__rest
 }
 
 // ---------------------------------------------------------------------------
-// gate/up: grid (G * gs/NB, ceil(T/128)), 256 threads
+// gate/up through rings in LDS filled by direct global -> LDS loads
+// grid: 8 * ceil(items / 8) workgroups of 256 threads, 144 KiB of dynamic LDS, one per compute unit
 // ---------------------------------------------------------------------------
-constexpr int kKS = 64;             // K elements per LDS stage (32 and 128 measured slower)
-constexpr int kARow = kKS + 8;      // padded LDS row (elements): rows start 16 bytes apart in bank space
-constexpr int kKH = kKS / 32;       // matrix-instruction K steps per stage
+// Workgroup tile: 128 weight rows (64 gate + 64 up neurons of one group) x 256 of the group's
+// tokens; K advances 64 elements per stage.  In LDS a stage is 128 weight rows and 256 gathered x
+// rows of 128 bytes.  One load instruction moves 1 KiB = 8 rows x 128 bytes, lane l landing at byte
+// 16 l of the block; to keep the operand reads free of bank conflicts the 16-byte piece p of tile row
+// r is parked at position p ^ (r & 7) of its row, which the loading lane arranges by fetching piece
+// (l & 7) ^ (l >> 3).  Nothing passes through registers on the way.
+//
+// A stage is 48 KiB and a ring holds three, so a stage is requested three steps before the matrix
+// instructions use it.  Each wave fetches a quarter of every stage (4 blocks of weight rows, 8 blocks
+// of x rows).  Lanes whose token row lies past the end of the group's list are switched off for the
+// load (lane 0 stays on, so that the load counts as one of the wave's outstanding loads whatever the
+// hardware does with an empty one): the number of loads per stage stays fixed and nothing is moved
+// for rows that do not exist.
+//
+// For the matrix work the four waves are a 2 x 2 grid: two halves of the stage's K range (elements
+// 0..31 / 32..63) times two halves of the token tile, so a wave owns a 128 x 128 partial tile (256
+// accumulator registers) and reads 16 KiB of LDS per 64 matrix instructions; the two K halves are
+// added through LDS once at the end.
+constexpr int kRingTok = 256;
+constexpr int kRingStages = 3;
+constexpr int kRingStageBytes = (128 + kRingTok) * 128;          // 48 KiB: weight rows, then x rows
+constexpr int kRingBytes = kRingStages * kRingStageBytes;        // 144 KiB (the final exchange needs 128 KiB)
 
-// TT = 16-token tiles per wave (a workgroup covers 4 * TT * 16 tokens of the group's list);
-// NB = neurons per workgroup (32 or 64).  Both operands go through LDS: the 2*NB weight rows and
-// the workgroup's gathered x rows are fetched with coalesced 128-byte row segments (eight lanes
-// per row), parked in registers for a stage and written to the other LDS buffer, so both are
-// requested two stages before the matrix instructions read them.  (Letting each lane fetch
-// its own x operand piece straight from memory touched 16 rows per instruction and could only
-// be requested one stage ahead; waves spent more than half their time waiting.)
-template <int TT, int NB>
-__global__ __launch_bounds__(256) void gate_up_pf(
-    const bf16_t *__restrict__ x, int T, int d, int gs, const bf16_t *__restrict__ Wg,
-    const bf16_t *__restrict__ Wu, const int32_t *__restrict__ tok_list,
-    const int32_t *__restrict__ tok_cnt, bf16_t *__restrict__ act)
+// One direct global -> LDS load of 16 bytes per lane: lane l's bytes at base + offset land at LDS
+// address lds_addr + 16 l (m0 carries the LDS address).  Done only if the wave-uniform `cond` holds,
+// and only for the lanes of `lanes` (all 64 lanes of the wave are active around it).  The branch is
+// inside the statement on purpose: a branch the compiler can see splits the step into basic blocks,
+// and it then shuffles the accumulators between register files at the joins.
+__device__ __forceinline__ void load_to_lds16_if(bool cond, unsigned long long lanes, const void *base,
+                                                 uint32_t offset, uint32_t lds_addr)
 {
-    constexpr int HT = NB / 16;                              // 16-row tiles per matrix
-    constexpr int RPP = 256 / (kKS / 8);                     // rows staged per pass (kKS/8 threads per row)
-    constexpr int NP = NB / RPP;                             // staging passes per weight matrix
-    constexpr int kTok = 4 * TT * 16;                        // tokens per workgroup
-    constexpr int NPX = kTok / RPP;                          // staging passes for the x tile
-    __shared__ __attribute__((aligned(16))) bf16_t sA[2][2 * NB * kARow];
-    __shared__ __attribute__((aligned(16))) bf16_t sX[2][kTok * kARow];
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    asm volatile("s_cmp_eq_u32 %3, 0\n\ts_cbranch_scc1 1f\n\ts_mov_b32 m0, %2\n\ts_mov_b64 exec, %4\n\t"
+                 "global_load_lds_dwordx4 %0, %1\n\ts_mov_b64 exec, -1\n1:" ::"v"(offset), "s"(base), "s"(lds_addr),
+                 "s"(__builtin_amdgcn_readfirstlane((uint32_t)cond)), "s"(lanes)
+                 : "memory", "scc");
+}
+
+// wait until at most N (deep) or none of the wave's loads are outstanding
+template <int N>
+__device__ __forceinline__ void wait_loads(bool deep)
+{
+    asm volatile("s_cmp_eq_u32 %0, 0\n\ts_cbranch_scc1 1f\n\ts_waitcnt vmcnt(%1)\n\ts_branch 2f\n1:\n\t"
+                 "s_waitcnt vmcnt(0)\n2:" ::"s"(__builtin_amdgcn_readfirstlane((uint32_t)deep)),
+                 "n"(N)
+                 : "memory", "scc");
+}
+
+// acc += a * b with the accumulator pinned to the accumulation registers and updated in place.
+// (Left to itself the compiler gives the 64 tiles of this kernel rotating destination registers and
+// moves a few hundred registers between the two files per step to make that work.)  A statement the
+// compiler cannot look into also gets none of its matrix-pipeline wait states, which is safe here:
+// a tile is touched again 63 matrix instructions later, and the first ordinary read of the
+// accumulators comes after a barrier and an explicit pause.
+__device__ __forceinline__ void mfma16_inplace(f32x4_t &acc, const u32x4 &a, const u32x4 &b)
+{
+    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+
+// Token tiles are numbered group by group (group g has ceil(cnt[g] / tile_tokens) of them), and only
+// tiles that exist get a number, so the working workgroups are consecutive.  Called by whole waves;
+// results are the same in every lane.
+__device__ __forceinline__ int wave_inclusive_sum(int n, int lane)
+{
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int v = __shfl_up(n, off);
+        if (lane >= off) n += v;
+    }
+    return n;
+}
+
+__device__ __forceinline__ int count_tiles(const int32_t *__restrict__ tok_cnt, int G, int tile_tokens, int lane)
+{
+    int total = 0;
+    for (int g0 = 0; g0 < G; g0 += 64) {
+        const int g = g0 + lane;
+        const int n = g < G ? (tok_cnt[g] + tile_tokens - 1) / tile_tokens : 0;
+        total += __shfl(wave_inclusive_sum(n, lane), 63);
+    }
+    return total;
+}
+
+// group and tile within the group of tile number `target` (< count_tiles)
+__device__ __forceinline__ int2 find_tile(const int32_t *__restrict__ tok_cnt, int G, int tile_tokens, int target,
+                                          int lane)
+{
+    int base = 0;
+    for (int g0 = 0; g0 < G; g0 += 64) {
+        const int g = g0 + lane;
+        const int n = g < G ? (tok_cnt[g] + tile_tokens - 1) / tile_tokens : 0;
+        const int incl = wave_inclusive_sum(n, lane);
+        const int total = __shfl(incl, 63);
+        if (target < base + total) {
+            const unsigned long long m = __ballot(target < base + incl);
+            const int l = __ffsll((long long)m) - 1;
+            const int excl = __shfl(incl - n, l);
+            return make_int2(g0 + l, target - base - excl);
+        }
+        base += total;
+    }
+    return make_int2(-1, 0);
+}
+
+struct RingFrags {
+    u32x4 a[8], b[8];
+};
+
+template <int KS_HALF>
+__device__ __forceinline__ void ring_finish(f32x4_t (&acc)[8][8], unsigned char *ring, int wave, int lane,
+                                            bool active, bf16_t *__restrict__ act_row0, int sl0, int cnt)
+{
+    // the wave keeps token tiles 4 KS_HALF .. +3 and hands the other four to its partner (wave ^ 1)
+    constexpr int own = 4 * KS_HALF, other = 4 - own;
+    if (active) {
+        unsigned char *mine = ring + wave * 32768 + lane * 16;
+#pragma unroll
+        for (int mt = 0; mt < 8; ++mt)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) *reinterpret_cast<f32x4_t *>(mine + (mt * 4 + j) * 1024) = acc[mt][other + j];
+    }
+    __syncthreads();
+    if (!active) return;
+    const unsigned char *theirs = ring + (wave ^ 1) * 32768 + lane * 16;
     const int i16 = lane & 15, q = lane >> 4;
-    const int per_group = gs / NB;
-    const int g = blockIdx.x / per_group, nt = blockIdx.x - g * per_group;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int sl = sl0 + (own + j) * 16 + i16;
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) {
+            const f32x4_t g = acc[mt][own + j] + *reinterpret_cast<const f32x4_t *>(theirs + (mt * 4 + j) * 1024);
+            const f32x4_t u = acc[mt + 4][own + j] + *reinterpret_cast<const f32x4_t *>(theirs + ((mt + 4) * 4 + j) * 1024);
+            const uint32_t lo = (uint32_t)f32_to_bf16(silu_mul_fast(g[0], u[0])) | ((uint32_t)f32_to_bf16(silu_mul_fast(g[1], u[1])) << 16);
+            const uint32_t hi = (uint32_t)f32_to_bf16(silu_mul_fast(g[2], u[2])) | ((uint32_t)f32_to_bf16(silu_mul_fast(g[3], u[3])) << 16);
+            if (sl < cnt) *reinterpret_cast<uint2 *>(act_row0 + (size_t)sl * 128 + mt * 16 + 4 * q) = make_uint2(lo, hi);
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void gate_up_pf_ring(
+    const bf16_t *__restrict__ x, int T, int d, int G, const bf16_t *__restrict__ Wg, const bf16_t *__restrict__ Wu,
+    const int32_t *__restrict__ tok_list, const int32_t *__restrict__ tok_cnt, bf16_t *__restrict__ act)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char ring[];
+    constexpr int gs = 128;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int ks = wave & 1, nh = wave >> 1;
+    const int i16 = lane & 15, q = lane >> 4;
+    // Workgroups are dealt to the eight dies round-robin by their index.  The work items (tile, half
+    // of the group's neurons) are numbered so that a die gets a consecutive run of them: the two
+    // halves of a tile share their x rows, the tiles of a group share its weight rows, and all
+    // workgroups of a die walk K from the same starting stage, so those rows are found in the die's
+    // own L2.  Numbering only the tiles that exist also spreads the work evenly over the dies (with
+    // a (group, chunk) grid the empty chunks left some dies with more workgroups than compute units).
+    const int n_items = 2 * count_tiles(tok_cnt, G, kRingTok, lane);
+    const int per_die = (n_items + 7) >> 3;
+    const int die = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int item = __builtin_amdgcn_readfirstlane(die * per_die + slot);
+    if (slot >= per_die || item >= n_items) return;              // uniform for the workgroup
+    const int nt = item & 1;
+    const int2 tile = find_tile(tok_cnt, G, kRingTok, item >> 1, lane);
+    const int g = __builtin_amdgcn_readfirstlane(tile.x);
     const int cnt = tok_cnt[g];
-    const int c0 = blockIdx.y * kTok;
-    if (c0 >= cnt) return;                                   // uniform for the workgroup
+    const int c0 = __builtin_amdgcn_readfirstlane(tile.y) * kRingTok;
     const int32_t *list = tok_list + (size_t)g * T;
-    // staging role of this thread: kKS/8 threads share a row's segment of a stage; per pass the
-    // thread takes gate row sr + RPP*p and up row sr + RPP*p (LDS rows r and NB + r), piece sp,
-    // and x row (= token slot) sr + RPP*p of the workgroup's tile
-    const int sr = tid / (kKS / 8), sp = tid % (kKS / 8);
-    const size_t neuron0 = (size_t)g * gs + nt * NB;
-    const bf16_t *wsrc_g = Wg + (neuron0 + sr) * d + sp * 8;
-    const bf16_t *wsrc_u = Wu + (neuron0 + sr) * d + sp * 8;
-    const int dst_off = sr * kARow + sp * 8;
-    const bf16_t *xsrc[NPX];
+    const bool active = c0 + nh * 128 < cnt;                     // this wave's half of the tile holds tokens
+
+    // The dies start at different K stages (rows are a power of two apart: with everybody at the same
+    // K offset all requests of a moment would go to the same few memory channels).
+    const int ns = d / 64;                                       // even, >= 2
+    int kstage = (die * ns) >> 3;                                // stage of the next request
+    // loading role: the stage's 48 blocks of 8 rows are dealt round-robin, wave w takes blocks w + 4 j:
+    // j = 0, 1 gate rows, j = 2, 3 up rows, then j = 0..7 of the x rows
+    const int br = lane >> 3;
+    const int piece = (lane & 7) ^ br;
+    const bf16_t *src_g = Wg + ((size_t)g * gs + nt * 64) * d + kstage * 64;
+    const bf16_t *src_u = Wu + ((size_t)g * gs + nt * 64) * d + kstage * 64;
+    const bf16_t *src_x = x + kstage * 64;
+    uint32_t off_w[4], off_x[8];                                 // byte offset of the lane's piece of block j
+    unsigned long long lanes_x[8];                               // lanes whose token row exists
 #pragma unroll
-    for (int p = 0; p < NPX; ++p) {
-        int sl = c0 + sr + RPP * p;
-        sl = sl < cnt ? sl : cnt - 1;                        // past the end: a valid duplicate, never stored
-        xsrc[p] = x + (size_t)list[sl] * d + sp * 8;
+    for (int j = 0; j < 4; ++j) {
+        const int r = (wave + 4 * (j & 1)) * 8 + br;             // 0..63 within the gate or the up half
+        off_w[j] = (uint32_t)(r * d + piece * 8) * 2u;
     }
-
-    f32x4_t acc[2 * HT][TT];
 #pragma unroll
-    for (int mt = 0; mt < 2 * HT; ++mt)
-#pragma unroll
-        for (int tt = 0; tt < TT; ++tt) acc[mt][tt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-
-    struct Stage {
-        u32x4 g[NP], u[NP], x[NPX];
-    };
-    auto load_stage = [&](int k0, Stage &r) {
-#pragma unroll
-        for (int p = 0; p < NPX; ++p) r.x[p] = *reinterpret_cast<const u32x4 *>(xsrc[p] + k0);
-#pragma unroll
-        for (int p = 0; p < NP; ++p) {
-            r.g[p] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(wsrc_g + (size_t)p * RPP * d + k0));
-            r.u[p] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(wsrc_u + (size_t)p * RPP * d + k0));
-        }
-    };
-    auto store_stage = [&](int buf, const Stage &r) {
-#pragma unroll
-        for (int p = 0; p < NPX; ++p) *reinterpret_cast<u32x4 *>(sX[buf] + dst_off + p * RPP * kARow) = r.x[p];
-#pragma unroll
-        for (int p = 0; p < NP; ++p) {
-            *reinterpret_cast<u32x4 *>(sA[buf] + dst_off + p * RPP * kARow) = r.g[p];
-            *reinterpret_cast<u32x4 *>(sA[buf] + dst_off + (NB + p * RPP) * kARow) = r.u[p];
-        }
-    };
-    auto compute = [&](int buf) {
-        const bf16_t *a_lds = sA[buf], *x_lds = sX[buf];
-#pragma unroll
-        for (int kh = 0; kh < kKH; ++kh) {
-            u32x4 a[2 * HT], b[TT];
-#pragma unroll
-            for (int tt = 0; tt < TT; ++tt)
-                b[tt] = *reinterpret_cast<const u32x4 *>(x_lds + ((wave * TT + tt) * 16 + i16) * kARow + kh * 32 + q * 8);
-#pragma unroll
-            for (int mt = 0; mt < 2 * HT; ++mt)
-                a[mt] = *reinterpret_cast<const u32x4 *>(a_lds + (mt * 16 + i16) * kARow + kh * 32 + q * 8);
-#pragma unroll
-            for (int mt = 0; mt < 2 * HT; ++mt)
-#pragma unroll
-                for (int tt = 0; tt < TT; ++tt) acc[mt][tt] = mfma16p(a[mt], b[tt], acc[mt][tt]);
-        }
-    };
-
-    // software pipeline over K (an even number of stages, d % 128 == 0).  Top of an even stage s:
-    // LDS buffer 0 holds stage s; r1 = stage s+1 is in flight.
-    const int nstage = d / kKS;
-    Stage r0, r1;
-    load_stage(0, r0);
-    load_stage(kKS, r1);
-    store_stage(0, r0);
-    __syncthreads();
-    int s = 0;
-    for (; s + 2 < nstage; s += 2) {
-        load_stage((s + 2) * kKS, r0);
-        compute(0);
-        store_stage(1, r1);
-        __syncthreads();
-        load_stage((s + 3) * kKS, r1);
-        compute(1);
-        store_stage(0, r0);
-        __syncthreads();
+    for (int j = 0; j < 8; ++j) {
+        const int sl = c0 + (wave + 4 * j) * 8 + br;
+        lanes_x[j] = __ballot(sl < cnt) | 1ull;
+        off_x[j] = (uint32_t)(list[sl < cnt ? sl : cnt - 1] * d + piece * 8) * 2u;
     }
-    compute(0);
-    store_stage(1, r1);
-    __syncthreads();
-    compute(1);
+    const uint32_t wdst0 = (uint32_t)(size_t)ring + wave * 1024; // this wave's first block of stage buffer 0
+    auto advance = [&](bool yes) {                               // on to the next stage, with wrap-around
+        const bool wrap = kstage + 1 == ns;
+        const int delta = yes ? (wrap ? 64 - d : 64) : 0;
+        src_g += delta;
+        src_u += delta;
+        src_x += delta;
+        kstage = yes ? (wrap ? 0 : kstage + 1) : kstage;
+    };
+    // operand reads: tile row mt*16 + i16 (or token row), piece (4 ks + q) at its swizzled position
+    const int loff = i16 * 128 + (((4 * ks + q) ^ (i16 & 7)) * 16);
+    f32x4_t acc[8][8];
+#pragma unroll
+    for (int mt = 0; mt < 8; ++mt)
+#pragma unroll
+        for (int tt = 0; tt < 8; ++tt) acc[mt][tt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-    // D: column = token i16 of tile tt, rows 4q..4q+3 of a neuron tile (tiles 0..HT-1 gate, HT.. up)
+    // Stage s lives in ring buffer s % 3.  At the top of step s the fragments of stage s are in
+    // registers.  The barrier of step s says: everybody's part of stage s+1 has landed and everybody
+    // has finished reading stage s, whose buffer is then handed to stage s+3.  The matrix work of a
+    // step is cut into eight slices of eight instructions (one 16-row tile of the weights against the
+    // eight token tiles) with one or two of the step's twelve loads in front of each: a wave issues in
+    // order, and a burst of memory instructions fills the memory pipelines' queues and holds the
+    // matrix instructions behind it back for as long as the burst takes to drain.
+    // (Waves whose half of the token tile is empty run the matrix work all the same, on whatever the
+    // x buffer holds: they sit on a SIMD of their own and nothing they compute is stored.)
+    for (int i = 0; i < kRingStages && i < ns; ++i) {
+        const uint32_t dst = wdst0 + i * kRingStageBytes;
 #pragma unroll
-    for (int tt = 0; tt < TT; ++tt) {
-        const int sl = c0 + (wave * TT + tt) * 16 + i16;
-        if (sl < cnt) {
+        for (int j = 0; j < 4; ++j) load_to_lds16_if(true, ~0ull, j < 2 ? src_g : src_u, off_w[j], dst + j * 4096);
 #pragma unroll
-            for (int mt = 0; mt < HT; ++mt) {
-                uint32_t lo = (uint32_t)f32_to_bf16(silu_mul(acc[mt][tt][0], acc[mt + HT][tt][0])) |
-                              ((uint32_t)f32_to_bf16(silu_mul(acc[mt][tt][1], acc[mt + HT][tt][1])) << 16);
-                uint32_t hi = (uint32_t)f32_to_bf16(silu_mul(acc[mt][tt][2], acc[mt + HT][tt][2])) |
-                              ((uint32_t)f32_to_bf16(silu_mul(acc[mt][tt][3], acc[mt + HT][tt][3])) << 16);
-                bf16_t *dst = act + ((size_t)g * T + sl) * gs + nt * NB + mt * 16 + 4 * q;
-                *reinterpret_cast<uint2 *>(dst) = make_uint2(lo, hi);
+        for (int j = 0; j < 8; ++j) load_to_lds16_if(true, lanes_x[j], src_x, off_x[j], dst + 16384 + j * 4096);
+        advance(true);
+    }
+    wait_loads<24>(ns >= kRingStages);
+    __syncthreads();
+    RingFrags F0, F1;
+    {
+        const unsigned char *pa = ring + loff, *px = ring + 16384 + nh * 16384 + loff;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            F0.a[c] = *reinterpret_cast<const u32x4 *>(pa + c * 2048);
+            F0.b[c] = *reinterpret_cast<const u32x4 *>(px + c * 2048);
+        }
+    }
+    int buf = 0;                                                 // buffer of stage s
+    auto step = [&](const RingFrags &cur, RingFrags &next, int s) __attribute__((always_inline)) {
+        const int nbuf = buf == kRingStages - 1 ? 0 : buf + 1;
+        wait_loads<12>(s + kRingStages <= ns);                   // stage s+2 may still be on its way
+        __syncthreads();
+        const bool go = s + kRingStages < ns;
+        const uint32_t dst = wdst0 + buf * kRingStageBytes;
+        __builtin_amdgcn_sched_barrier(0);
+        {   // (in the last step this reads a stage that does not exist: in bounds, unused)
+            const unsigned char *pa = ring + nbuf * kRingStageBytes + loff;
+            const unsigned char *px = pa + 16384 + nh * 16384;
+#pragma unroll
+            for (int c = 0; c < 8; ++c) {
+                next.a[c] = *reinterpret_cast<const u32x4 *>(pa + c * 2048);
+                next.b[c] = *reinterpret_cast<const u32x4 *>(px + c * 2048);
             }
         }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            load_to_lds16_if(go, lanes_x[c], src_x, off_x[c], dst + 16384 + c * 4096);
+            if (c < 4) load_to_lds16_if(go, ~0ull, c < 2 ? src_g : src_u, off_w[c], dst + c * 4096);
+#pragma unroll
+            for (int tt = 0; tt < 8; ++tt) mfma16_inplace(acc[c][tt], cur.a[c], cur.b[tt]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        advance(go);
+        buf = nbuf;
+    };
+    for (int s = 0; s < ns; s += 2) {
+        step(F0, F1, s);
+        step(F1, F0, s + 1);
     }
+    __syncthreads();                                             // every wave is done with the rings
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");           // the last matrix results are in the registers
+
+    bf16_t *act_row0 = act + (size_t)g * T * gs + nt * 64;
+    const int sl0 = c0 + nh * 128;
+    if (ks == 0)
+        ring_finish<0>(acc, ring, wave, lane, active, act_row0, sl0, cnt);
+    else
+        ring_finish<1>(acc, ring, wave, lane, active, act_row0, sl0, cnt);
 }
 
 // ---------------------------------------------------------------------------
@@ -335,7 +479,8 @@ __global__ __launch_bounds__(256) void down_pf(
 // ---------------------------------------------------------------------------
 bool prefill_path_supported(int T, int d, int gs)
 {
-    return T > 1 && d % 128 == 0 && gs == 128;
+    // (the ring kernel addresses x rows with 32-bit byte offsets)
+    return T > 1 && d % 128 == 0 && gs == 128 && (size_t)T * d * sizeof(bf16_t) < (1ull << 31);
 }
 
 hipError_t launch_ffn_prefill(const bf16_t *x, int T, int d, int G, int gs, const bf16_t *Wg,
@@ -344,11 +489,12 @@ hipError_t launch_ffn_prefill(const bf16_t *x, int T, int d, int G, int gs, cons
 {
     bf16_t *act = reinterpret_cast<bf16_t *>(ws.act);
     group_tokens_kernel<<<dim3(G), dim3(256), 0, s>>>(mask, T, G, ws.tok_list, ws.tok_cnt, ws.slot);
-    // 128 tokens x 64 neurons per workgroup.  Measured on the 512-token LLaMA-7B shape: 32 neurons
-    // 169 us, 64 neurons 120 us, the whole group with 64 tokens 151 us.
-    constexpr int TT = 2, NB = 64;
-    launch_timed("gate_up_pf", gate_up_pf<TT, NB>, dim3(G * (gs / NB), (T + 64 * TT - 1) / (64 * TT)), dim3(256),
-                 s, x, T, d, gs, Wg, Wu, (const int32_t *)ws.tok_list, (const int32_t *)ws.tok_cnt, act);
+    static const hipError_t lds_ok = hipFuncSetAttribute(reinterpret_cast<const void *>(gate_up_pf_ring),
+                                                         hipFuncAttributeMaxDynamicSharedMemorySize, kRingBytes);
+    if (lds_ok != hipSuccess) return lds_ok;
+    const int items_max = 2 * G * ((T + kRingTok - 1) / kRingTok);          // every group kept by every token
+    launch_timed_lds("gate_up_pf_ring", gate_up_pf_ring, dim3((items_max + 7) / 8 * 8), dim3(256), kRingBytes, s, x, T,
+                     d, G, Wg, Wu, (const int32_t *)ws.tok_list, (const int32_t *)ws.tok_cnt, act);
     down_pf<<<dim3(d / 64, (T + 127) / 128), dim3(256), 0, s>>>(T, d, G, Wd, ws.slot, act, y);
     return hipGetLastError();
 }
