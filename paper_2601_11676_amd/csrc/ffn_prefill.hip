@@ -37,7 +37,7 @@ __device__ __forceinline__ f32x4_t mfma16p(const u32x4 &a, const u32x4 &b, const
 __global__ __launch_bounds__(256) void group_tokens_kernel(const uint8_t *__restrict__ mask, int T, int G,
                                                            int32_t *__restrict__ tok_list,
                                                            int32_t *__restrict__ tok_cnt,
-                                                           int32_t *__restrict__ slot)
+                                                           int32_t *__restrict__ slot, bf16_t *__restrict__ act)
 {
     __shared__ int s_wave[4];
     __shared__ int s_base;
@@ -60,6 +60,10 @@ __global__ __launch_bounds__(256) void group_tokens_kernel(const uint8_t *__rest
         __syncthreads();
     }
     if (tid == 0) tok_cnt[g] = s_base;
+    // the row after the group's last activation row is kept zero (group size 128): the down
+    // projection points the tokens that do not keep the group at it
+    const int cnt = s_base;
+    if (cnt < T && tid < 64) reinterpret_cast<uint32_t *>(act + ((size_t)g * T + cnt) * 128)[tid] = 0u;
 }
 
 // ---------------------------------------------------------------------------
@@ -475,6 +479,226 @@ __global__ __launch_bounds__(256) void down_pf(
 }
 
 // ---------------------------------------------------------------------------
+// down projection through the same kind of ring, groups split over workgroups
+// grid: 8 * ceil(items / 8) workgroups of 256 threads, 160 KiB of dynamic LDS
+// ---------------------------------------------------------------------------
+// Workgroup tile: 128 outputs x 256 tokens, over a contiguous range of the groups (the K
+// dimension): with 128 x 256 tiles alone a 512-token call would occupy 64 compute units, so the
+// groups are cut into `splits` ranges and every range goes to its own workgroup, which leaves its
+// fp32 partial sums in partial[split][t][j]; reduce_partials adds the ranges in fixed order.  With a
+// single range the workgroup writes y itself.
+//
+// A stage is half a group (64 of its 128 neurons): 128 rows of Wd (the group's 128 x 128 tile is 32
+// KiB of consecutive bytes, a stage takes alternate halves of its 256-byte rows) and the 256 token
+// rows of act, found through the slot table.  A token that does not keep the group is pointed at
+// the group's row of zeros (row cnt[g], written by group_tokens), so it contributes exactly nothing.
+// The row indices of the workgroup's tokens for all its groups are put into LDS once, 16 bits each.
+// Everything else is as in gate_up_pf_ring.
+constexpr int kDownSlotBytes = 160 * 1024 - kRingBytes;          // 16 KiB: 32 groups x 256 tokens x 2 bytes
+constexpr int kDownMaxGroups = kDownSlotBytes / (kRingTok * 2);
+constexpr int kDownMaxSplits = 8;
+
+// number of group ranges for the ring kernel, 0 = shape not covered by it
+int prefill_down_splits(int T, int d, int G)
+{
+    if (d % 128 != 0 || T > 32767) return 0;
+    const int tiles = (d / 128) * ((T + kRingTok - 1) / kRingTok);
+    int splits = (256 + tiles / 2) / tiles;                      // about one workgroup per compute unit
+    const int need = (G + kDownMaxGroups - 1) / kDownMaxGroups;  // the slot table must fit
+    splits = splits < need ? need : splits;
+    splits = splits < 1 ? 1 : splits;
+    splits = splits > G ? G : splits;
+    if (splits > kDownMaxSplits || (G + splits - 1) / splits > kDownMaxGroups) return 0;
+    return splits;
+}
+
+template <int KS_HALF>
+__device__ __forceinline__ void down_finish(f32x4_t (&acc)[8][8], unsigned char *ring, int wave, int lane, int t0,
+                                            int T, int d, int j0, float *__restrict__ partial, bf16_t *__restrict__ y)
+{
+    // the wave keeps token tiles 4 KS_HALF .. +3 and hands the other four to its partner (wave ^ 1)
+    constexpr int own = 4 * KS_HALF, other = 4 - own;
+    unsigned char *mine = ring + wave * 32768 + lane * 16;
+#pragma unroll
+    for (int mt = 0; mt < 8; ++mt)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) *reinterpret_cast<f32x4_t *>(mine + (mt * 4 + j) * 1024) = acc[mt][other + j];
+    __syncthreads();
+    const unsigned char *theirs = ring + (wave ^ 1) * 32768 + lane * 16;
+    const int i16 = lane & 15, q = lane >> 4;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int t = t0 + (own + j) * 16 + i16;
+#pragma unroll
+        for (int mt = 0; mt < 8; ++mt) {
+            const f32x4_t v = acc[mt][own + j] + *reinterpret_cast<const f32x4_t *>(theirs + (mt * 4 + j) * 1024);
+            if (t < T) {
+                const size_t at = (size_t)t * d + j0 + mt * 16 + 4 * q;
+                if (partial) {
+                    *reinterpret_cast<f32x4_t *>(partial + at) = v;
+                } else {
+                    const uint32_t lo = (uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16);
+                    const uint32_t hi = (uint32_t)f32_to_bf16(v[2]) | ((uint32_t)f32_to_bf16(v[3]) << 16);
+                    *reinterpret_cast<uint2 *>(y + at) = make_uint2(lo, hi);
+                }
+            }
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void down_pf_ring(
+    int T, int d, int G, int splits, const bf16_t *__restrict__ Wd, const int32_t *__restrict__ slot,
+    const int32_t *__restrict__ tok_cnt, const bf16_t *__restrict__ act, float *__restrict__ partial,
+    bf16_t *__restrict__ y)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char ring[];
+    int16_t *s_row = reinterpret_cast<int16_t *>(ring + kRingBytes);    // [group of the range][token of the tile]
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int ks = wave & 1, nh = wave >> 1;
+    const int i16 = lane & 15, q = lane >> 4;
+    // work items: (token tile, group range) pairs, and within a pair the output tiles; a die gets a
+    // consecutive run of them, i.e. workgroups that share their act rows
+    const int n_ot = d / 128;
+    const int n_items = n_ot * ((T + kRingTok - 1) / kRingTok) * splits;
+    const int per_die = (n_items + 7) >> 3;
+    const int die = blockIdx.x & 7, dslot = blockIdx.x >> 3;
+    const int item = die * per_die + dslot;
+    if (dslot >= per_die || item >= n_items) return;             // uniform for the workgroup
+    const int pair = item / n_ot, j0 = (item - pair * n_ot) * 128;
+    const int ttile = pair / splits, split = pair - ttile * splits;
+    const int t0 = ttile * kRingTok;
+    const int g_lo = (int)((long long)split * G / splits), g_hi = (int)((long long)(split + 1) * G / splits);
+    const int ng = g_hi - g_lo;                                  // >= 1, <= kDownMaxGroups
+    const int ns = 2 * ng;
+
+    // rows of act for this thread's token and every group of the range
+    {
+        const int t = t0 + tid;
+        for (int gi = 0; gi < ng; ++gi) {
+            int row = 0;                                         // a token past the end: any row, never stored
+            if (t < T) {
+                row = slot[(size_t)t * G + g_lo + gi];
+                row = row < 0 ? tok_cnt[g_lo + gi] : row;        // the group's row of zeros
+            }
+            s_row[gi * kRingTok + tid] = (int16_t)row;
+        }
+    }
+    __syncthreads();
+
+    // loading role: the stage's 48 blocks of 8 rows are dealt round-robin, wave w takes blocks w + 4 j:
+    // j = 0..3 of the Wd rows, j = 0..7 of the act rows
+    const int br = lane >> 3;
+    const int piece = (lane & 7) ^ br;
+    const bf16_t *src_w = Wd + ((size_t)g_lo * d + j0) * 128;    // the stage's Wd half rows; + 64 elements for odd stages
+    const bf16_t *src_a = act + (size_t)g_lo * T * 128;
+    uint32_t off_w[4], off_a[8];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) off_w[j] = (uint32_t)(((wave + 4 * j) * 8 + br) * 128 + piece * 8) * 2u;
+    auto rows_of_group = [&](int gi) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            off_a[j] = (uint32_t)(s_row[gi * kRingTok + (wave + 4 * j) * 8 + br] * 128 + piece * 8) * 2u;
+    };
+    const uint32_t wdst0 = (uint32_t)(size_t)ring + wave * 1024;
+    int next_stage = 0;                                          // stage of the next request
+    auto advance = [&](bool yes) {
+        const bool odd = next_stage & 1;
+        src_w += yes ? (odd ? (ptrdiff_t)d * 128 - 64 : 64) : 0;
+        src_a += yes ? (odd ? (ptrdiff_t)T * 128 - 64 : 64) : 0;
+        next_stage += yes ? 1 : 0;
+    };
+    const int loff = i16 * 128 + (((4 * ks + q) ^ (i16 & 7)) * 16);
+    f32x4_t acc[8][8];
+#pragma unroll
+    for (int mt = 0; mt < 8; ++mt)
+#pragma unroll
+        for (int tt = 0; tt < 8; ++tt) acc[mt][tt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+    rows_of_group(0);
+    for (int i = 0; i < kRingStages && i < ns; ++i) {
+        if (i == 2) rows_of_group(1);                            // ns > 2: a second group exists
+        const uint32_t dst = wdst0 + i * kRingStageBytes;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) load_to_lds16_if(true, ~0ull, src_w, off_w[j], dst + j * 4096);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) load_to_lds16_if(true, ~0ull, src_a, off_a[j], dst + 16384 + j * 4096);
+        advance(true);
+    }
+    wait_loads<24>(ns >= kRingStages);
+    __syncthreads();
+    RingFrags F0, F1;
+    {
+        const unsigned char *pa = ring + loff, *px = ring + 16384 + nh * 16384 + loff;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            F0.a[c] = *reinterpret_cast<const u32x4 *>(pa + c * 2048);
+            F0.b[c] = *reinterpret_cast<const u32x4 *>(px + c * 2048);
+        }
+    }
+    int buf = 0;                                                 // buffer of stage s
+    auto step = [&](const RingFrags &cur, RingFrags &next, int s, bool new_group) __attribute__((always_inline)) {
+        const int nbuf = buf == kRingStages - 1 ? 0 : buf + 1;
+        wait_loads<12>(s + kRingStages <= ns);                   // stage s+2 may still be on its way
+        __syncthreads();
+        const bool go = s + kRingStages < ns;
+        const uint32_t dst = wdst0 + buf * kRingStageBytes;
+        // stage s+3 is the first half of a group in odd steps: its act rows
+        if (new_group) rows_of_group(go ? (s + kRingStages) >> 1 : 0);
+        __builtin_amdgcn_sched_barrier(0);
+        {   // (in the last step this reads a stage that does not exist: in bounds, unused)
+            const unsigned char *pa = ring + nbuf * kRingStageBytes + loff;
+            const unsigned char *px = pa + 16384 + nh * 16384;
+#pragma unroll
+            for (int c = 0; c < 8; ++c) {
+                next.a[c] = *reinterpret_cast<const u32x4 *>(pa + c * 2048);
+                next.b[c] = *reinterpret_cast<const u32x4 *>(px + c * 2048);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            load_to_lds16_if(go, ~0ull, src_a, off_a[c], dst + 16384 + c * 4096);
+            if (c < 4) load_to_lds16_if(go, ~0ull, src_w, off_w[c], dst + c * 4096);
+#pragma unroll
+            for (int tt = 0; tt < 8; ++tt) mfma16_inplace(acc[c][tt], cur.a[c], cur.b[tt]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        advance(go);
+        buf = nbuf;
+    };
+    for (int s = 0; s < ns; s += 2) {
+        step(F0, F1, s, false);
+        step(F1, F0, s + 1, true);
+    }
+    __syncthreads();                                             // every wave is done with the ring
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");           // the last matrix results are in the registers
+
+    float *out = partial ? partial + (size_t)split * T * d : nullptr;
+    if (ks == 0)
+        down_finish<0>(acc, ring, wave, lane, t0 + nh * 128, T, d, j0, out, y);
+    else
+        down_finish<1>(acc, ring, wave, lane, t0 + nh * 128, T, d, j0, out, y);
+}
+
+// y = sum of the ranges' partial sums, added in the order of the ranges; n = T * d, a multiple of 8
+__global__ __launch_bounds__(256) void reduce_partials(const float *__restrict__ partial, int splits, size_t n,
+                                                       bf16_t *__restrict__ y)
+{
+    const size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 8;
+    if (i >= n) return;
+    float v[8];
+    load8(partial + i, v);
+    for (int k = 1; k < splits; ++k) {
+        float w[8];
+        load8(partial + (size_t)k * n + i, w);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] += w[e];
+    }
+    store8(y + i, v);
+}
+
+// ---------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------
 bool prefill_path_supported(int T, int d, int gs)
@@ -488,14 +712,31 @@ hipError_t launch_ffn_prefill(const bf16_t *x, int T, int d, int G, int gs, cons
                               const DecodeScratch &ws, hipStream_t s)
 {
     bf16_t *act = reinterpret_cast<bf16_t *>(ws.act);
-    group_tokens_kernel<<<dim3(G), dim3(256), 0, s>>>(mask, T, G, ws.tok_list, ws.tok_cnt, ws.slot);
+    group_tokens_kernel<<<dim3(G), dim3(256), 0, s>>>(mask, T, G, ws.tok_list, ws.tok_cnt, ws.slot, act);
     static const hipError_t lds_ok = hipFuncSetAttribute(reinterpret_cast<const void *>(gate_up_pf_ring),
                                                          hipFuncAttributeMaxDynamicSharedMemorySize, kRingBytes);
     if (lds_ok != hipSuccess) return lds_ok;
     const int items_max = 2 * G * ((T + kRingTok - 1) / kRingTok);          // every group kept by every token
     launch_timed_lds("gate_up_pf_ring", gate_up_pf_ring, dim3((items_max + 7) / 8 * 8), dim3(256), kRingBytes, s, x, T,
                      d, G, Wg, Wu, (const int32_t *)ws.tok_list, (const int32_t *)ws.tok_cnt, act);
-    down_pf<<<dim3(d / 64, (T + 127) / 128), dim3(256), 0, s>>>(T, d, G, Wd, ws.slot, act, y);
+    const int splits = prefill_down_splits(T, d, G);
+    if (splits == 0) {
+        down_pf<<<dim3(d / 64, (T + 127) / 128), dim3(256), 0, s>>>(T, d, G, Wd, ws.slot, act, y);
+        return hipGetLastError();
+    }
+    static const hipError_t lds_ok2 = hipFuncSetAttribute(reinterpret_cast<const void *>(down_pf_ring),
+                                                          hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                          kRingBytes + kDownSlotBytes);
+    if (lds_ok2 != hipSuccess) return lds_ok2;
+    const int items = (d / 128) * ((T + kRingTok - 1) / kRingTok) * splits;
+    float *partial = splits > 1 ? ws.partial : nullptr;
+    launch_timed_lds("down_pf_ring", down_pf_ring, dim3((items + 7) / 8 * 8), dim3(256), kRingBytes + kDownSlotBytes, s, T,
+                     d, G, splits, Wd, (const int32_t *)ws.slot, (const int32_t *)ws.tok_cnt, (const bf16_t *)act,
+                     partial, y);
+    if (splits > 1) {
+        const size_t n = (size_t)T * d;
+        reduce_partials<<<dim3((unsigned)((n / 8 + 255) / 256)), dim3(256), 0, s>>>(partial, splits, n, y);
+    }
     return hipGetLastError();
 }
 

@@ -60,6 +60,11 @@ struct Workspace {
         dec.tok_list = reinterpret_cast<int32_t *>(take(G * t * sizeof(int32_t)));
         dec.tok_cnt = reinterpret_cast<int32_t *>(take(G * sizeof(int32_t)));
         dec.slot = reinterpret_cast<int32_t *>(take(G * t * sizeof(int32_t)));
+        const int splits = s.dtype == HALO_BF16 && prefill_path_supported(T, s.d, s.group_size) &&
+                                   !mfma_path_supported(T, s.d, s.group_size) && T > 1
+                               ? prefill_down_splits(T, s.d, s.n_groups)
+                               : 0;
+        dec.partial = reinterpret_cast<float *>(take(splits > 1 ? (size_t)splits * t * s.d * sizeof(float) : 0));
         bytes = off;
     }
 };

@@ -29,6 +29,7 @@ struct DecodeScratch {
     int32_t *tok_list;  // [G][T] prefill: tokens that keep each group, ascending
     int32_t *tok_cnt;   // [G]
     int32_t *slot;      // [T][G] position of the token in its group's list, -1 = not kept
+    float *partial;     // [splits][T][d] prefill: the down projection's sums per range of groups
 };
 // The next block's prediction (predictor + mask from x_next), see halo_ffn_forward_ahead.
 struct AheadArgs {
@@ -87,6 +88,7 @@ hipError_t launch_gate_up_few(const bf16_t *x, int T, int d, int G, int gs, cons
 
 // ffn_prefill.hip : bf16 matrix-core path for many tokens
 bool prefill_path_supported(int T, int d, int gs);
+int prefill_down_splits(int T, int d, int G);   // ranges of groups in the down projection (0: one pass, no ranges)
 hipError_t launch_ffn_prefill(const bf16_t *x, int T, int d, int G, int gs, const bf16_t *Wg,
                               const bf16_t *Wu, const bf16_t *Wd, const uint8_t *mask, bf16_t *y,
                               const DecodeScratch &ws, hipStream_t s);

@@ -332,6 +332,9 @@ def test_llama7b_prefill_sampled_tokens():
     (18, 8192, 3, 512, False),    # register-tiled predictor, 70B row length
     (33, 256, 1, 64, True),       # a single group
     (70, 256, 2, 64, False),
+    (20, 256, 300, 64, False),    # more groups than the ring down projection's slot table takes: its fallback
+    (1536, 4096, 2, 64, False),   # enough output x token tiles for a single range of groups: y written directly
+    (600, 512, 9, 64, False),     # three token tiles, ragged; several ranges of groups of unequal length
 ])
 def test_many_tokens_matrix_core_path_all_tokens(T, d, G, r, keepall):
     w = dataclasses.replace(hs.LLAMA7B_PREFILL, name="case", d=d, ffn=G * 128, rank=r, T=T, seed=23)
