@@ -1,4 +1,4 @@
-// Gate/up projection for a few tokens (2..8) on the float ALUs, bf16.
+// Gate/up projection for a few tokens (2..4) on the float ALUs, bf16.
 //
 // With a handful of tokens the block is still bound by streaming the union of the tokens'
 // surviving groups from HBM: 2*T multiply-adds per weight element fit beside the memory time of
@@ -16,11 +16,15 @@
 
 namespace halo {
 
-template <int NCH, int TMAX>
+// T is a template parameter on purpose: with a run-time token count every (K piece, token) pair sat
+// behind a branch of its own, each with its own wait for the LDS read in front of it, and the
+// kernel spent more time on LDS latency than on memory (40 us at the 13B shape, 4 tokens).
+template <int NCH, int T>
 __global__ __launch_bounds__(256) void gate_up_ft(
-    const bf16_t *__restrict__ x, int T, int G, int gs, const bf16_t *__restrict__ Wg,
+    const bf16_t *__restrict__ x, int G, int gs, const bf16_t *__restrict__ Wg,
     const bf16_t *__restrict__ Wu, const uint8_t *__restrict__ mask, bf16_t *__restrict__ act, int act_stride)
 {
+    constexpr int TMAX = T;
     constexpr int d = NCH * 512, XR = d + 8;                 // LDS row of x, elements (16-byte aligned)
     extern __shared__ __attribute__((aligned(16))) bf16_t sx[];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -42,13 +46,10 @@ __global__ __launch_bounds__(256) void gate_up_ft(
     const int g_first = nth_group(uw, u_first, lane), g_last = nth_group(uw, u_last, lane);
     unsigned keep_first = 0, keep_last = 0;
 #pragma unroll
-    for (int t = 0; t < TMAX; ++t) {
-        const int tc = t < T ? t : T - 1;
-        const unsigned a = mask[(size_t)tc * G + g_first], b = mask[(size_t)tc * G + g_last];
-        if (t < T) {
-            keep_first |= (a ? 1u : 0u) << t;
-            keep_last |= (b ? 1u : 0u) << t;
-        }
+    for (int t = 0; t < T; ++t) {
+        const unsigned a = mask[(size_t)t * G + g_first], b = mask[(size_t)t * G + g_last];
+        keep_first |= (a ? 1u : 0u) << t;
+        keep_last |= (b ? 1u : 0u) << t;
     }
     auto row_of = [&](int n) -> size_t {
         const int u = n / gs;
@@ -62,28 +63,24 @@ __global__ __launch_bounds__(256) void gate_up_ft(
 #pragma unroll
         for (int k = 0; k < NCH; ++k) {
 #pragma unroll
-            for (int t = 0; t < TMAX; ++t) {
-                if (t < T) {                                 // uniform
-                    const u32x4 xv = *reinterpret_cast<const u32x4 *>(xl + t * XR + k * 512);
-                    ag[t] = dot2_bf16(r.g[k].x, xv.x, ag[t]);
-                    au[t] = dot2_bf16(r.u[k].x, xv.x, au[t]);
-                    ag[t] = dot2_bf16(r.g[k].y, xv.y, ag[t]);
-                    au[t] = dot2_bf16(r.u[k].y, xv.y, au[t]);
-                    ag[t] = dot2_bf16(r.g[k].z, xv.z, ag[t]);
-                    au[t] = dot2_bf16(r.u[k].z, xv.z, au[t]);
-                    ag[t] = dot2_bf16(r.g[k].w, xv.w, ag[t]);
-                    au[t] = dot2_bf16(r.u[k].w, xv.w, au[t]);
-                }
+            for (int t = 0; t < T; ++t) {
+                const u32x4 xv = *reinterpret_cast<const u32x4 *>(xl + t * XR + k * 512);
+                ag[t] = dot2_bf16(r.g[k].x, xv.x, ag[t]);
+                au[t] = dot2_bf16(r.u[k].x, xv.x, au[t]);
+                ag[t] = dot2_bf16(r.g[k].y, xv.y, ag[t]);
+                au[t] = dot2_bf16(r.u[k].y, xv.y, au[t]);
+                ag[t] = dot2_bf16(r.g[k].z, xv.z, ag[t]);
+                au[t] = dot2_bf16(r.u[k].z, xv.z, au[t]);
+                ag[t] = dot2_bf16(r.g[k].w, xv.w, ag[t]);
+                au[t] = dot2_bf16(r.u[k].w, xv.w, au[t]);
             }
         }
         const unsigned keep = (n / gs == u_first) ? keep_first : keep_last;
         float mine = 0.0f;
 #pragma unroll
-        for (int t = 0; t < TMAX; ++t) {
-            if (t < T) {
-                const float v = silu_mul(wave_sum_fast(ag[t]), wave_sum_fast(au[t]));
-                if (lane == t) mine = ((keep >> t) & 1u) ? v : 0.0f;
-            }
+        for (int t = 0; t < T; ++t) {
+            const float v = silu_mul(wave_sum_fast(ag[t]), wave_sum_fast(au[t]));
+            if (lane == t) mine = ((keep >> t) & 1u) ? v : 0.0f;
         }
         if (lane < T) act[(size_t)lane * act_stride + n] = f32_to_bf16(mine);
     };
@@ -109,31 +106,42 @@ __global__ __launch_bounds__(256) void gate_up_ft(
 bool few_path_supported(int T, int d, int G, int gs)
 {
     // up to 4 tokens: beyond that the 2*T multiply-adds per weight element no longer hide behind its
-    // memory time (8 tokens at the 70B shape: 250 us against 150 us for the matrix-core kernel)
+    // memory time (8 tokens at the 70B shape: 258 us against 150 us for the matrix-core kernel)
     return T >= 2 && T <= 4 && gs == 128 && G <= 256 && (d == 4096 || d == 5120 || d == 8192);
 }
 
-template <int NCH, int TMAX>
+template <int NCH, int T>
+static hipError_t launch_exact(const bf16_t *x, int G, int gs, const bf16_t *Wg, const bf16_t *Wu,
+                               const uint8_t *mask, bf16_t *act, int act_stride, hipStream_t s)
+{
+    constexpr size_t lds = (size_t)T * (NCH * 512 + 8) * sizeof(bf16_t);
+    static const hipError_t lds_ok = hipFuncSetAttribute(reinterpret_cast<const void *>(gate_up_ft<NCH, T>),
+                                                         hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (lds_ok != hipSuccess) return lds_ok;
+    launch_timed_lds("gate_up_ft", gate_up_ft<NCH, T>, dim3(256), dim3(256), lds, s, x, G, gs, Wg, Wu, mask, act,
+                     act_stride);
+    return hipGetLastError();
+}
+
+template <int NCH>
 static hipError_t launch_one(const bf16_t *x, int T, int G, int gs, const bf16_t *Wg, const bf16_t *Wu,
                              const uint8_t *mask, bf16_t *act, int act_stride, hipStream_t s)
 {
-    constexpr size_t kMaxLds = 144 * 1024;
-    static const hipError_t lds_ok = hipFuncSetAttribute(reinterpret_cast<const void *>(gate_up_ft<NCH, TMAX>),
-                                                         hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLds);
-    if (lds_ok != hipSuccess) return lds_ok;
-    const size_t lds = (size_t)T * (NCH * 512 + 8) * sizeof(bf16_t);
-    launch_timed_lds("gate_up_ft", gate_up_ft<NCH, TMAX>, dim3(256), dim3(256), lds, s, x, T, G, gs, Wg, Wu, mask,
-                     act, act_stride);
-    return hipGetLastError();
+    switch (T) {
+    case 2: return launch_exact<NCH, 2>(x, G, gs, Wg, Wu, mask, act, act_stride, s);
+    case 3: return launch_exact<NCH, 3>(x, G, gs, Wg, Wu, mask, act, act_stride, s);
+    case 4: return launch_exact<NCH, 4>(x, G, gs, Wg, Wu, mask, act, act_stride, s);
+    default: return hipErrorInvalidValue;
+    }
 }
 
 hipError_t launch_gate_up_few(const bf16_t *x, int T, int d, int G, int gs, const bf16_t *Wg, const bf16_t *Wu,
                               const uint8_t *mask, bf16_t *act, int act_stride, hipStream_t s)
 {
     switch (d) {
-    case 4096: return launch_one<8, 4>(x, T, G, gs, Wg, Wu, mask, act, act_stride, s);
-    case 5120: return launch_one<10, 4>(x, T, G, gs, Wg, Wu, mask, act, act_stride, s);
-    case 8192: return launch_one<16, 4>(x, T, G, gs, Wg, Wu, mask, act, act_stride, s);
+    case 4096: return launch_one<8>(x, T, G, gs, Wg, Wu, mask, act, act_stride, s);
+    case 5120: return launch_one<10>(x, T, G, gs, Wg, Wu, mask, act, act_stride, s);
+    case 8192: return launch_one<16>(x, T, G, gs, Wg, Wu, mask, act, act_stride, s);
     default: return hipErrorInvalidValue;
     }
 }
