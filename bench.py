@@ -398,7 +398,7 @@ def main():
     gate_up_bytes = float(timed_union.sum()) * 2 * group_bytes
     achieved = gate_up_bytes / (kern_ms * 1e-3) / 1e9 if kern_ms > 0 else 0.0
     traffic = read_traffic(kern_name, w.name + ("_q4" if args.q4 else ""))
-    if kern_name.endswith("_pf"):
+    if "_pf" in kern_name:
         # many tokens: the dominant kernel is a dense contraction on the matrix cores
         flops = float(n_surv[::args.time_every][:kern_n].sum()) * w.group_size * d * 2 * 2   # gate and up, 2 flop per MAC
         roof = {"bound": "mfma", "kernel": kern_name, "achieved": flops / (kern_ms * 1e-3) / 1e12,

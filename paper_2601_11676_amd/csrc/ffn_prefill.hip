@@ -730,9 +730,8 @@ hipError_t launch_ffn_prefill(const bf16_t *x, int T, int d, int G, int gs, cons
     if (lds_ok2 != hipSuccess) return lds_ok2;
     const int items = (d / 128) * ((T + kRingTok - 1) / kRingTok) * splits;
     float *partial = splits > 1 ? ws.partial : nullptr;
-    launch_timed_lds("down_pf_ring", down_pf_ring, dim3((items + 7) / 8 * 8), dim3(256), kRingBytes + kDownSlotBytes, s, T,
-                     d, G, splits, Wd, (const int32_t *)ws.slot, (const int32_t *)ws.tok_cnt, (const bf16_t *)act,
-                     partial, y);
+    down_pf_ring<<<dim3((items + 7) / 8 * 8), dim3(256), kRingBytes + kDownSlotBytes, s>>>(
+        T, d, G, splits, Wd, (const int32_t *)ws.slot, (const int32_t *)ws.tok_cnt, (const bf16_t *)act, partial, y);
     if (splits > 1) {
         const size_t n = (size_t)T * d;
         reduce_partials<<<dim3((unsigned)((n / 8 + 255) / 256)), dim3(256), 0, s>>>(partial, splits, n, y);
