@@ -12,8 +12,8 @@ Form of the pass.  By default each step calls halo_ffn_forward_ahead: the FFN of
 the mask predicted one step earlier, and beside it -- in spare workgroups of the same two
 launches -- predictor + mask of step s+1 (the paper's Pred || Load/Comp overlap, one layer
 ahead).  Every step therefore runs the predictor, the mask and the FFN once.  `--serial` uses
-halo_ffn_forward (predictor, mask, FFN back to back) instead; workloads with more than one
-token always do.
+halo_ffn_forward (predictor, mask, FFN back to back) instead; workloads with more than 16
+tokens per step always do.
 
 Weights: the layer is replicated into --copies independent copies visited round-robin, so
 that consecutive steps read different HBM (a real decode walks 32 different layers per token;
@@ -315,8 +315,8 @@ def main():
         H.halo_ffn_forward_ahead(shape, xs[s], Wg, Wu, Wd, masks[s], ys[s], xs[s + 1], At, Bt, k_keep,
                                  prio_dev, w.n_dev, drops[s + 1], masks[s + 1], ws, stream=st)
 
-    if T != 1:
-        args.serial = True      # the overlap rides in spare workgroups of the one-token kernels only
+    if T > 16:
+        args.serial = True      # the overlap rides in spare workgroups of the one- and few-token kernels only
     # marshal every step's call once: the timed and the profiled loops then cost a few
     # microseconds of host time per step, so the GPU is never left waiting for Python
     make = step_serial if args.serial else step_ahead

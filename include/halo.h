@@ -191,9 +191,10 @@ int halo_ffn_forward(const halo_shape *shape, const void *x, const void *x_pred,
  *   - predictor + group mask of the next block from x_pred_next with that block's
  *     predictor weights -> mask_next (and the optional outputs, same meaning as in
  *     halo_build_group_mask; NULL = not produced).
- * For one token (bf16, d in {4096, 5120, 8192}, n_groups <= 256) the prediction occupies
- * spare workgroups of the FFN's own two launches (first predictor layer beside gate/up,
- * second layer + ranking + mask beside the down projection), so it costs no launch and no
+ * For one token (bf16, d in {4096, 5120, 8192}, n_groups <= 256) and for 2..16 tokens (bf16,
+ * d a multiple of 128, group size 128, n_groups <= 256) the prediction occupies spare
+ * workgroups of the FFN's own two launches (first predictor layer beside gate/up, second
+ * layer + ranking + mask beside the down projection), so it costs no launch and little or no
  * time on the critical path; for other shapes it is enqueued after the FFN.  Results are
  * identical to the separate calls either way.  x_pred_next may be x (predicting from this
  * block's input, as the paper does) but must not be y; mask_next must not alias mask_cur.

@@ -181,6 +181,24 @@ __device__ __forceinline__ float dot_order64_fixed(const bf16_t *__restrict__ xp
     return wave_sum(p);
 }
 
+// One row of the predictor's first layer for T tokens (paper Sec. III-B.2), in the fixed order:
+// h[t][j] = ReLU(x[t] . At[j]), this wave's row j.  D = row length when it is one of the tuned ones
+// (every piece requested before the first multiply), 0 = any length d.
+template <int D>
+__device__ __forceinline__ void predictor_row_tokens(const bf16_t *__restrict__ x, const bf16_t *__restrict__ At,
+                                                     float *__restrict__ h, int T, int d, int r, int j, int lane)
+{
+    if (j >= r) return;
+    for (int t = 0; t < T; ++t) {
+        float p;
+        if constexpr (D > 0)
+            p = dot_order64_fixed<(D > 0 ? D : 512)>(x + (size_t)t * D, At + (size_t)j * D, lane);
+        else
+            p = dot_order64(x + (size_t)t * d, At + (size_t)j * d, d, lane);
+        if (lane == 0) h[(size_t)t * r + j] = p > 0.0f ? p : 0.0f;
+    }
+}
+
 // Wave-wide sum through the DPP cross-lane paths (no LDS traffic); result is uniform.
 // Used where the summation order is free (FFN dot products), not by the predictor.
 __device__ __forceinline__ float wave_sum_fast(float v)

@@ -429,8 +429,9 @@ hipError_t launch_down_generic_bf16(const float *act, int act_stride, int d, int
 }
 
 // ahead != nullptr asks for the next block's prediction to ride along with this block's
-// kernels.  Only the one-token path can do that; *ahead_fused tells the caller whether it did
-// (if not, the caller enqueues the prediction itself).
+// kernels.  The one-token path and the few-token paths (up to 16 tokens, up to 256 groups) can do
+// that; *ahead_fused tells the caller whether it happened (if not, the caller enqueues the
+// prediction itself).
 hipError_t launch_ffn_decode(int dtype, const void *x, int T, int d, int G, int gs, const void *Wg,
                              const void *Wu, const void *Wd, const uint8_t *mask, void *y,
                              const DecodeScratch &ws, hipStream_t s, const AheadArgs *ahead,
@@ -452,7 +453,7 @@ hipError_t launch_ffn_decode(int dtype, const void *x, int T, int d, int G, int 
         }
     }
     if (mfma_path_supported(T, d, gs))
-        return launch_ffn_mfma(bx, T, d, G, gs, bg, bu, bd, mask, (bf16_t *)y, ws, s);
+        return launch_ffn_mfma(bx, T, d, G, gs, bg, bu, bd, mask, (bf16_t *)y, ws, s, ahead, ahead_fused);
     if (prefill_path_supported(T, d, gs))
         return launch_ffn_prefill(bx, T, d, G, gs, bg, bu, bd, mask, (bf16_t *)y, ws, s);
     return decode_generic<bf16_t>(bx, T, d, G, gs, bg, bu, bd, mask, (bf16_t *)y, ws, s);

@@ -22,12 +22,18 @@ namespace halo {
 template <int NCH, int T>
 __global__ __launch_bounds__(256) void gate_up_ft(
     const bf16_t *__restrict__ x, int G, int gs, const bf16_t *__restrict__ Wg,
-    const bf16_t *__restrict__ Wu, const uint8_t *__restrict__ mask, bf16_t *__restrict__ act, int act_stride)
+    const bf16_t *__restrict__ Wu, const uint8_t *__restrict__ mask, bf16_t *__restrict__ act, int act_stride,
+    AheadPredDev ap)
 {
     constexpr int TMAX = T;
     constexpr int d = NCH * 512, XR = d + 8;                 // LDS row of x, elements (16-byte aligned)
     extern __shared__ __attribute__((aligned(16))) bf16_t sx[];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    if ((int)blockIdx.x < ap.n_pred) {
+        // paper Sec. III-B.3, Pred beside Load/Comp, one layer ahead: the next block's first layer
+        predictor_row_tokens<d>(ap.x_next, ap.At, ap.h, T, d, ap.r, blockIdx.x * 4 + wave, lane);
+        return;
+    }
     // the union of the tokens' surviving groups, built by every wave from the T*G mask bytes
     // (no separate launch, no list in memory between the mask and the first weight load)
     const MaskWords uw = load_union_words<TMAX>(mask, T, G, lane);
@@ -37,7 +43,7 @@ __global__ __launch_bounds__(256) void gate_up_ft(
     }
     __syncthreads();
     const long long total = (long long)uw.count * gs;
-    const int nw = gridDim.x * 4, w = blockIdx.x * 4 + wave;
+    const int nw = (gridDim.x - ap.n_pred) * 4, w = (blockIdx.x - ap.n_pred) * 4 + wave;
     const int n0 = (int)(total * w / nw), n1 = (int)(total * (w + 1) / nw);
     if (n0 >= n1) return;                                    // no barrier below
     // a run is shorter than a group (total / nw <= gs), so it touches at most two groups: their ids
@@ -112,36 +118,39 @@ bool few_path_supported(int T, int d, int G, int gs)
 
 template <int NCH, int T>
 static hipError_t launch_exact(const bf16_t *x, int G, int gs, const bf16_t *Wg, const bf16_t *Wu,
-                               const uint8_t *mask, bf16_t *act, int act_stride, hipStream_t s)
+                               const uint8_t *mask, bf16_t *act, int act_stride, hipStream_t s,
+                               const AheadPredDev &ap)
 {
     constexpr size_t lds = (size_t)T * (NCH * 512 + 8) * sizeof(bf16_t);
     static const hipError_t lds_ok = hipFuncSetAttribute(reinterpret_cast<const void *>(gate_up_ft<NCH, T>),
                                                          hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (lds_ok != hipSuccess) return lds_ok;
-    launch_timed_lds("gate_up_ft", gate_up_ft<NCH, T>, dim3(256), dim3(256), lds, s, x, G, gs, Wg, Wu, mask, act,
-                     act_stride);
+    launch_timed_lds("gate_up_ft", gate_up_ft<NCH, T>, dim3(256 + ap.n_pred), dim3(256), lds, s, x, G, gs, Wg, Wu,
+                     mask, act, act_stride, ap);
     return hipGetLastError();
 }
 
 template <int NCH>
 static hipError_t launch_one(const bf16_t *x, int T, int G, int gs, const bf16_t *Wg, const bf16_t *Wu,
-                             const uint8_t *mask, bf16_t *act, int act_stride, hipStream_t s)
+                             const uint8_t *mask, bf16_t *act, int act_stride, hipStream_t s,
+                             const AheadPredDev &ap)
 {
     switch (T) {
-    case 2: return launch_exact<NCH, 2>(x, G, gs, Wg, Wu, mask, act, act_stride, s);
-    case 3: return launch_exact<NCH, 3>(x, G, gs, Wg, Wu, mask, act, act_stride, s);
-    case 4: return launch_exact<NCH, 4>(x, G, gs, Wg, Wu, mask, act, act_stride, s);
+    case 2: return launch_exact<NCH, 2>(x, G, gs, Wg, Wu, mask, act, act_stride, s, ap);
+    case 3: return launch_exact<NCH, 3>(x, G, gs, Wg, Wu, mask, act, act_stride, s, ap);
+    case 4: return launch_exact<NCH, 4>(x, G, gs, Wg, Wu, mask, act, act_stride, s, ap);
     default: return hipErrorInvalidValue;
     }
 }
 
 hipError_t launch_gate_up_few(const bf16_t *x, int T, int d, int G, int gs, const bf16_t *Wg, const bf16_t *Wu,
-                              const uint8_t *mask, bf16_t *act, int act_stride, hipStream_t s)
+                              const uint8_t *mask, bf16_t *act, int act_stride, hipStream_t s,
+                              const AheadPredDev &ap)
 {
     switch (d) {
-    case 4096: return launch_one<8>(x, T, G, gs, Wg, Wu, mask, act, act_stride, s);
-    case 5120: return launch_one<10>(x, T, G, gs, Wg, Wu, mask, act, act_stride, s);
-    case 8192: return launch_one<16>(x, T, G, gs, Wg, Wu, mask, act, act_stride, s);
+    case 4096: return launch_one<8>(x, T, G, gs, Wg, Wu, mask, act, act_stride, s, ap);
+    case 5120: return launch_one<10>(x, T, G, gs, Wg, Wu, mask, act, act_stride, s, ap);
+    case 8192: return launch_one<16>(x, T, G, gs, Wg, Wu, mask, act, act_stride, s, ap);
     default: return hipErrorInvalidValue;
     }
 }

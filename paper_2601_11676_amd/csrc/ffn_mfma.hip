@@ -16,6 +16,7 @@
 // 8*(l/16)..+7 of the 32; B lane l holds column l%16, same elements; D lane l holds
 // column l%16, rows 4*(l/16)..+3.  Rows are neurons (or outputs j), columns are tokens.
 #include "kernels.hpp"
+#include "mask_device.hpp"
 #include "mask_words.hpp"
 
 namespace halo {
@@ -52,11 +53,22 @@ template <bool UNION_IN_KERNEL>
 __global__ __launch_bounds__(256) void gate_up_mt(
     const bf16_t *__restrict__ x, int T, int d, int G, int gs, const bf16_t *__restrict__ Wg,
     const bf16_t *__restrict__ Wu, const uint8_t *__restrict__ mask, const int32_t *__restrict__ ulist_mem,
-    const int32_t *__restrict__ meta, bf16_t *__restrict__ act, int act_stride)
+    const int32_t *__restrict__ meta, bf16_t *__restrict__ act, int act_stride, AheadPredDev ap)
 {
     __shared__ __attribute__((aligned(16))) bf16_t sW[4][16 * kChunkRow];
     __shared__ int s_list[256];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    if ((int)blockIdx.x < ap.n_pred) {
+        // paper Sec. III-B.3, Pred beside Load/Comp, one layer ahead: the next block's first layer
+        const int j = blockIdx.x * 4 + wave;
+        switch (d) {
+        case 4096: predictor_row_tokens<4096>(ap.x_next, ap.At, ap.h, T, d, ap.r, j, lane); break;
+        case 5120: predictor_row_tokens<5120>(ap.x_next, ap.At, ap.h, T, d, ap.r, j, lane); break;
+        case 8192: predictor_row_tokens<8192>(ap.x_next, ap.At, ap.h, T, d, ap.r, j, lane); break;
+        default: predictor_row_tokens<0>(ap.x_next, ap.At, ap.h, T, d, ap.r, j, lane); break;
+        }
+        return;
+    }
     bf16_t *my = sW[wave];
     const int32_t *ulist = ulist_mem;
     long long total;
@@ -69,10 +81,10 @@ __global__ __launch_bounds__(256) void gate_up_mt(
     } else {
         total = (long long)meta[0] * gs;
     }
-    int nw = gridDim.x * 4;
+    int nw = (gridDim.x - ap.n_pred) * 4;
     const long long want = (total + 11) / 12;
     if (want < nw) nw = want < 1 ? 1 : (int)want;
-    const int w = blockIdx.x * 4 + wave;
+    const int w = (blockIdx.x - ap.n_pred) * 4 + wave;
     if (w >= nw) return;
     const int n0 = (int)(total * w / nw), n1 = (int)(total * (w + 1) / nw);
     const int L = n1 - n0;
@@ -159,20 +171,44 @@ __global__ __launch_bounds__(256) void gate_up_mt(
 constexpr int kDownGroups = 4;              // groups in flight per wave
 constexpr int kTileRow = 128 + 8;           // padded LDS row, elements
 
-// UNION_IN_KERNEL: as in gate_up_mt.
+struct DownMtShared {
+    __attribute__((aligned(16))) bf16_t sT[4][kDownGroups][16 * kTileRow];
+    float red[4][64][4];
+    int s_list[256];
+};
+
+// UNION_IN_KERNEL: as in gate_up_mt.  The first n_mask workgroups do not project: each computes the
+// next block's scores, ranking and mask for one token (n_mask = 0: nobody does).
 template <bool UNION_IN_KERNEL>
 __global__ __launch_bounds__(256) void down_mt(
     int T, int d, int G, const bf16_t *__restrict__ Wd, const uint8_t *__restrict__ mask,
     const int32_t *__restrict__ ulist_mem, const int32_t *__restrict__ meta,
-    const bf16_t *__restrict__ act, int act_stride, bf16_t *__restrict__ y)
+    const bf16_t *__restrict__ act, int act_stride, bf16_t *__restrict__ y, int n_mask, AheadDev nx)
 {
     constexpr int gs = 128;
-    __shared__ __attribute__((aligned(16))) bf16_t sT[4][kDownGroups][16 * kTileRow];
-    __shared__ float red[4][64][4];
-    __shared__ int s_list[256];
+    constexpr size_t kLds = sizeof(DownMtShared) > sizeof(MaskShared) ? sizeof(DownMtShared) : sizeof(MaskShared);
+    __shared__ __attribute__((aligned(16))) unsigned char lds[kLds];
+    if ((int)blockIdx.x < n_mask) {
+        // paper Sec. III-B.3, one layer ahead: second predictor layer, ranking and mask of the next
+        // block for token blockIdx.x (dispatched first: it is the longest dependent chain)
+        const int t = blockIdx.x;
+        mask_scores_block<256, bf16_t, true>(*reinterpret_cast<MaskShared *>(lds), threadIdx.x, nx.h + (size_t)t * nx.r,
+                                             nx.Bt, nx.r, nx.scores + (size_t)t * G, G, nx.K, nx.prio_dev, nx.n_dev,
+                                             nx.drop ? nx.drop + (size_t)t * nx.n_dev : nullptr,
+                                             nx.order ? nx.order + (size_t)t * G : nullptr,
+                                             nx.group_dev ? nx.group_dev + (size_t)t * G : nullptr,
+                                             nx.mask + (size_t)t * G,
+                                             nx.surv_idx ? nx.surv_idx + (size_t)t * nx.K : nullptr,
+                                             nx.n_surv ? nx.n_surv + t : nullptr);
+        return;
+    }
+    DownMtShared &sh = *reinterpret_cast<DownMtShared *>(lds);
+    auto &sT = sh.sT;
+    auto &red = sh.red;
+    auto &s_list = sh.s_list;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int i = lane & 15, q = lane >> 4;
-    const int j0 = blockIdx.x * 16;
+    const int j0 = (blockIdx.x - n_mask) * 16;
     int n_u;
     const int32_t *ulist = ulist_mem;
     if (UNION_IN_KERNEL) {
@@ -242,30 +278,39 @@ bool mfma_path_supported(int T, int d, int gs)
 
 hipError_t launch_ffn_mfma(const bf16_t *x, int T, int d, int G, int gs, const bf16_t *Wg,
                            const bf16_t *Wu, const bf16_t *Wd, const uint8_t *mask, bf16_t *y,
-                           const DecodeScratch &ws, hipStream_t s)
+                           const DecodeScratch &ws, hipStream_t s, const AheadArgs *ahead, bool *ahead_fused)
 {
     const int ffn = G * gs;
     bf16_t *act = reinterpret_cast<bf16_t *>(ws.act);
-    if (few_path_supported(T, d, G, gs)) {
-        // up to four tokens: rows streamed as in the one-token path, union built inside the kernels
-        hipError_t e = launch_gate_up_few(x, T, d, G, gs, Wg, Wu, mask, act, ffn, s);
-        if (e != hipSuccess) return e;
-        down_mt<true><<<dim3(d / 16), dim3(256), 0, s>>>(T, d, G, Wd, mask, nullptr, nullptr, act, ffn, y);
-        return hipGetLastError();
-    }
+    if (ahead_fused) *ahead_fused = false;
     if (G <= 256) {
-        // the union of the tokens' groups is built inside the kernels: no union launch, no list in memory
-        launch_timed("gate_up_mt", gate_up_mt<true>, dim3(256), dim3(256), s, x, T, d, G, gs, Wg, Wu, mask,
-                     (const int32_t *)nullptr, (const int32_t *)nullptr, act, ffn);
-        down_mt<true><<<dim3(d / 16), dim3(256), 0, s>>>(T, d, G, Wd, mask, nullptr, nullptr, act, ffn, y);
+        // The union of the tokens' groups is built inside the kernels: no union launch, no list in
+        // memory.  The next block's prediction can ride along: its first layer in spare workgroups
+        // of the gate/up launch, its second layer + ranking + mask (a workgroup per token) in the
+        // down-projection launch.
+        const AheadArgs *ah = (ahead && ahead_fused) ? ahead : nullptr;
+        if (ah) *ahead_fused = true;
+        const AheadPredDev ap = ahead_pred_dev(ah);
+        const int n_mask = ah ? T : 0;
+        const AheadDev nx = ah ? ahead_dev(*ah) : AheadDev{};
+        if (few_path_supported(T, d, G, gs)) {
+            // up to four tokens: rows streamed as in the one-token path
+            hipError_t e = launch_gate_up_few(x, T, d, G, gs, Wg, Wu, mask, act, ffn, s, ap);
+            if (e != hipSuccess) return e;
+        } else {
+            launch_timed("gate_up_mt", gate_up_mt<true>, dim3(256 + ap.n_pred), dim3(256), s, x, T, d, G, gs, Wg, Wu,
+                         mask, (const int32_t *)nullptr, (const int32_t *)nullptr, act, ffn, ap);
+        }
+        down_mt<true><<<dim3(d / 16 + n_mask), dim3(256), 0, s>>>(T, d, G, Wd, mask, nullptr, nullptr, act, ffn, y,
+                                                                 n_mask, nx);
         return hipGetLastError();
     }
     hipError_t e = launch_union(mask, T, G, ws.ulist, ws.meta, s);
     if (e != hipSuccess) return e;
     // one workgroup per compute unit (the kernel holds two row batches in registers, one wave per SIMD)
     launch_timed("gate_up_mt", gate_up_mt<false>, dim3(256), dim3(256), s, x, T, d, G, gs, Wg, Wu, mask,
-                 (const int32_t *)ws.ulist, (const int32_t *)ws.meta, act, ffn);
-    down_mt<false><<<dim3(d / 16), dim3(256), 0, s>>>(T, d, G, Wd, mask, ws.ulist, ws.meta, act, ffn, y);
+                 (const int32_t *)ws.ulist, (const int32_t *)ws.meta, act, ffn, AheadPredDev{nullptr, nullptr, nullptr, 0, 0});
+    down_mt<false><<<dim3(d / 16), dim3(256), 0, s>>>(T, d, G, Wd, mask, ws.ulist, ws.meta, act, ffn, y, 0, AheadDev{});
     return hipGetLastError();
 }
 

@@ -57,6 +57,18 @@ struct AheadDev {
     int32_t *surv_idx;
     int32_t *n_surv;
 };
+// The first predictor layer of the next block for T tokens, riding in the first n_pred workgroups of
+// a gate/up launch (four rows of At per workgroup): h[t][j] = ReLU(x_next[t] . At[j]).
+struct AheadPredDev {
+    const bf16_t *x_next, *At;
+    float *h;
+    int r, n_pred;       // n_pred == 0: nothing rides along
+};
+inline AheadPredDev ahead_pred_dev(const AheadArgs *a)
+{
+    if (!a) return AheadPredDev{nullptr, nullptr, nullptr, 0, 0};
+    return AheadPredDev{(const bf16_t *)a->x_next, (const bf16_t *)a->At, a->h, a->r, (a->r + 3) / 4};
+}
 inline AheadDev ahead_dev(const AheadArgs &a)
 {
     return AheadDev{a.h, (const bf16_t *)a.Bt, a.r, a.K, a.n_dev, a.prio_dev, a.drop, a.scores, a.order,
@@ -79,12 +91,14 @@ hipError_t launch_union(const uint8_t *mask, int T, int G, int32_t *ulist, int32
 bool mfma_path_supported(int T, int d, int gs);
 hipError_t launch_ffn_mfma(const bf16_t *x, int T, int d, int G, int gs, const bf16_t *Wg,
                            const bf16_t *Wu, const bf16_t *Wd, const uint8_t *mask, bf16_t *y,
-                           const DecodeScratch &ws, hipStream_t s);
+                           const DecodeScratch &ws, hipStream_t s, const AheadArgs *ahead = nullptr,
+                           bool *ahead_fused = nullptr);
 
 // ffn_few.hip : gate/up for 2..8 tokens on the float ALUs (rows streamed as in the one-token path)
 bool few_path_supported(int T, int d, int G, int gs);
 hipError_t launch_gate_up_few(const bf16_t *x, int T, int d, int G, int gs, const bf16_t *Wg, const bf16_t *Wu,
-                              const uint8_t *mask, bf16_t *act, int act_stride, hipStream_t s);
+                              const uint8_t *mask, bf16_t *act, int act_stride, hipStream_t s,
+                              const AheadPredDev &ap);
 
 // ffn_prefill.hip : bf16 matrix-core path for many tokens
 bool prefill_path_supported(int T, int d, int gs);

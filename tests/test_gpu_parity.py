@@ -201,16 +201,25 @@ def test_separate_entry_points_equal_the_fused_pass():
     assert np.array_equal(hz.to_np32(y).astype(np.float64), fused["y"])
 
 
-def test_one_step_ahead_overlap_equals_the_serial_pass():
+@pytest.mark.parametrize("T,d,G,r,K", [
+    (1, 4096, 20, 256, 10),      # one token: the prediction rides in the one-token kernels
+    (4, 5120, 9, 256, 4),        # float-ALU gate/up for a few tokens + matrix-core down projection
+    (2, 8192, 6, 512, 3),
+    (8, 8192, 7, 512, 4),        # matrix-core kernels, 70B row length
+    (16, 4096, 6, 256, 3),
+    (3, 640, 5, 40, 2),          # a row length without a tuned predictor row: generic fixed-order dot
+    (20, 256, 5, 64, 2),         # many tokens: no spare workgroups, the prediction follows on the stream
+])
+def test_one_step_ahead_overlap_equals_the_serial_pass(T, d, G, r, K):
     # predictor + mask of step s+1 beside the FFN of step s
-    w = dataclasses.replace(hs.LLAMA7B_DECODE, name="case", ffn=20 * 128, seed=8)
-    _say("halo_ffn_forward_ahead vs halo_ffn_forward")
+    w = dataclasses.replace(hs.LLAMA7B_DECODE, name="case", d=d, ffn=G * 128, rank=r, T=T, seed=8)
+    _say(f"halo_ffn_forward_ahead vs halo_ffn_forward, T={T} d={d} G={G}")
     s = hz.shape_of(w)
     L = hz.Layer(w)
-    T, G, K, n = w.T, w.n_groups, 10, 6
+    n = 6
     pd = H.halo_build_schedule(K, w.device_plr())
     xs = [hs.hidden_states(w, i, hz.DEV) for i in range(n + 1)]
-    drops = [hs.drop_outcomes(w, 0, i) for i in range(n + 1)]
+    drops = [hs.drop_outcomes(w, 0, i, T=T) for i in range(n + 1)]
     serial = [hz.gpu_forward(w, L, xs[i], K, pd, drops[i]) for i in range(n)]
     ws = torch.empty(H.halo_workspace_bytes(s, T, K), dtype=torch.uint8, device=hz.DEV)
     pdd = torch.from_numpy(pd).to(hz.DEV)
