@@ -168,12 +168,11 @@ __global__ __launch_bounds__(256) void gate_up_mt(
 
 // grid: d/16 workgroups of 256 threads; group size 128.  A workgroup owns 16 output rows; a
 // group's 16 x 128 tile of Wd is 4 KiB of consecutive bytes, fetched by four instructions.
-constexpr int kDownGroups = 4;              // groups in flight per wave
+constexpr int kDownGroups = 3;              // groups in flight per wave (LDS: three workgroups per compute unit)
 constexpr int kTileRow = 128 + 8;           // padded LDS row, elements
 
 struct DownMtShared {
     __attribute__((aligned(16))) bf16_t sT[4][kDownGroups][16 * kTileRow];
-    float red[4][64][4];
     int s_list[256];
 };
 
@@ -204,8 +203,10 @@ __global__ __launch_bounds__(256) void down_mt(
     }
     DownMtShared &sh = *reinterpret_cast<DownMtShared *>(lds);
     auto &sT = sh.sT;
-    auto &red = sh.red;
     auto &s_list = sh.s_list;
+    // the waves' partial sums meet in LDS at the end; each wave parks its own in the first KiB of its
+    // own tile region, which it has finished reading by then
+    auto red = [&](int w) { return reinterpret_cast<float(*)[4]>(&sT[w][0][0]); };
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int i = lane & 15, q = lane >> 4;
     const int j0 = (blockIdx.x - n_mask) * 16;
@@ -257,12 +258,12 @@ __global__ __launch_bounds__(256) void down_mt(
         }
     }
 #pragma unroll
-    for (int rr = 0; rr < 4; ++rr) red[wave][lane][rr] = c[rr];
+    for (int rr = 0; rr < 4; ++rr) red(wave)[lane][rr] = c[rr];
     __syncthreads();
     if (wave == 0 && i < T) {
 #pragma unroll
         for (int rr = 0; rr < 4; ++rr) {
-            const float v = ((red[0][lane][rr] + red[1][lane][rr]) + red[2][lane][rr]) + red[3][lane][rr];
+            const float v = ((red(0)[lane][rr] + red(1)[lane][rr]) + red(2)[lane][rr]) + red(3)[lane][rr];
             y[(size_t)i * d + j0 + 4 * q + rr] = f32_to_bf16(v);
         }
     }
