@@ -2,18 +2,22 @@
 //
 // With hundreds of tokens the block is a dense contraction per neuron group, but only over
 // the tokens that keep the group (paper Sec. II-A: groups are independent until the merge;
-// Sec. III-B.3: each token has its own surviving set).  Three kernels:
+// Sec. III-B.3: each token has its own surviving set).  Kernels:
 //
 //   group_tokens : for every group, the ascending list of tokens that keep it, and for
-//                  every (token, group) the token's slot in that list (-1 = not kept).
+//                  every (token, group) the token's slot in that list (-1 = not kept); also
+//                  keeps one zero row per group in the activation buffer.
 //   gate_up_pf_ring : one workgroup = 64 neurons of one group (64 gate + 64 up rows) x up to 256
 //                  of the group's tokens (x rows gathered by the token list); both operands
 //                  travel straight from memory into a ring of K stages in LDS.
 //                  act[g][slot][m] = SiLU(gate) * up in bf16.
-//   down_pf      : output-stationary: one workgroup = 128 tokens x 64 outputs, walking all
-//                  groups (Wd tiles through LDS, activation rows gathered into registers); a
-//                  token that does not keep a group feeds zeros, so it contributes exactly
-//                  nothing, and every y element has exactly one writer (no atomics).
+//   down_pf_ring : one workgroup = 128 outputs x 256 tokens over a range of groups, same ring;
+//                  a token that does not keep a group reads the group's zero row, so it
+//                  contributes exactly nothing.  With several ranges the fp32 partial sums are
+//                  added by reduce_partials in fixed order; every element has one writer.
+//   down_pf      : the earlier output-stationary form (128 tokens x 64 outputs per workgroup,
+//                  walking all groups), kept for shapes the ring form does not take (more
+//                  than 256 groups, more than 32767 tokens).
 //
 // v_mfma_f32_16x16x32_bf16 operand layout as in ffn_mfma.hip: A lane l = row l%16, elements
 // 8*(l/16)..+7; B lane l = column l%16, same elements; D lane l = column l%16, rows 4*(l/16)..+3.
