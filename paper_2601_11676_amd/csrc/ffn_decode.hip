@@ -171,21 +171,21 @@ __device__ __forceinline__ void gate_up_t1_body(
     const bf16_t *__restrict__ Wu, const uint8_t *__restrict__ mask, bf16_t *__restrict__ act,
     int vblock, int nblocks)
 {
+    constexpr int kGs = 128;                                       // the group size of this path
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const MaskWords mw = load_mask_words(mask, G, lane);
-    const long long total = (long long)mw.count * gs;
+    const int total = mw.count * kGs;
     const int nw = nblocks * 4, w = vblock * 4 + wave;
-    const int n0 = (int)(total * w / nw), n1 = (int)(total * (w + 1) / nw);
+    const int n0 = (int)((long long)total * w / nw), n1 = (int)((long long)total * (w + 1) / nw);
     if (n0 >= n1) return;
-    int cur_u = n0 / gs;
-    int cur_g = nth_group(mw, cur_u, lane);
+    // a run is shorter than a group (at most 256 groups over 1024 waves), so it touches at most two
+    // groups; their ids are found once, and the row of a neuron is then a shift and a select (with
+    // the lookup inside the loop, a hundred instructions stood between a reduction and the next loads)
+    const int u_first = n0 / kGs, u_last = (n1 - 1) / kGs;
+    const int g_first = nth_group(mw, u_first, lane), g_last = nth_group(mw, u_last, lane);
     auto row_of = [&](int n) -> size_t {
-        const int u = n / gs;
-        if (u != cur_u) {
-            cur_u = u;
-            cur_g = nth_group(mw, u, lane);
-        }
-        return (size_t)cur_g * gs + (n - u * gs);
+        const int u = n / kGs;
+        return (size_t)(u == u_first ? g_first : g_last) * kGs + (n - u * kGs);
     };
     RowPair<NCH> A, B;
     load_rows<NCH>(A, Wg, Wu, row_of(n0), lane);
@@ -195,9 +195,11 @@ __device__ __forceinline__ void gate_up_t1_body(
     int n = n0;
     while (n + 2 < n1) {
         load_rows<NCH>(B, Wg, Wu, row_of(n + 1), lane);
+        __builtin_amdgcn_sched_barrier(0);      // the requests go out before anything waits for the rows in flight
         const float va = gate_up_dot<NCH>(A, xr);
         if (lane == 0) act[n] = f32_to_bf16(va);
         load_rows<NCH>(A, Wg, Wu, row_of(n + 2), lane);
+        __builtin_amdgcn_sched_barrier(0);
         const float vb = gate_up_dot<NCH>(B, xr);
         if (lane == 0) act[n + 1] = f32_to_bf16(vb);
         n += 2;
