@@ -60,11 +60,21 @@ struct Workspace {
         dec.tok_list = reinterpret_cast<int32_t *>(take(G * t * sizeof(int32_t)));
         dec.tok_cnt = reinterpret_cast<int32_t *>(take(G * sizeof(int32_t)));
         dec.slot = reinterpret_cast<int32_t *>(take(G * t * sizeof(int32_t)));
-        const int splits = s.dtype == HALO_BF16 && prefill_path_supported(T, s.d, s.group_size) &&
-                                   !mfma_path_supported(T, s.d, s.group_size) && T > 1
-                               ? prefill_down_splits(T, s.d, s.n_groups)
-                               : 0;
-        dec.partial = reinterpret_cast<float *>(take(splits > 1 ? (size_t)splits * t * s.d * sizeof(float) : 0));
+        // partial sums of the prefill down projection: the number of ranges falls as T grows, so the
+        // size is taken as the largest need of any token count up to T (a workspace sized for T then
+        // also serves every smaller call); the need is largest at the upper end of a token tile
+        size_t partial_elems = 0;
+        if (s.dtype == HALO_BF16) {
+            for (int t1 = 256; t1 - 256 < T; t1 += 256) {
+                const int tt = t1 < T ? t1 : T;
+                if (!prefill_path_supported(tt, s.d, s.group_size) || mfma_path_supported(tt, s.d, s.group_size))
+                    continue;
+                const int splits = prefill_down_splits(tt, s.d, s.n_groups);
+                const size_t need = splits > 1 ? (size_t)splits * tt * s.d : 0;
+                partial_elems = need > partial_elems ? need : partial_elems;
+            }
+        }
+        dec.partial = reinterpret_cast<float *>(take(partial_elems * sizeof(float)));
         bytes = off;
     }
 };

@@ -73,11 +73,13 @@ def gpu_forward_q4(w, layer: Q4Layer, x, K, prio_dev_np, drop_np):
                 mask=mask.cpu().numpy(), surv_idx=surv_idx.cpu().numpy(), n_surv=n_surv.cpu().numpy())
 
 
-def gpu_forward(w, layer: Layer, x, K, prio_dev_np, drop_np, x_pred=None):
-    """halo_ffn_forward through the C boundary; returns numpy outputs."""
+def gpu_forward(w, layer: Layer, x, K, prio_dev_np, drop_np, x_pred=None, ws_tokens=None):
+    """halo_ffn_forward through the C boundary; returns numpy outputs.  ws_tokens: size the
+    workspace for that many tokens instead of x's."""
     s = shape_of(w)
     T, G = x.shape[0], w.n_groups
-    ws = torch.empty(H.halo_workspace_bytes(s, T, K), dtype=torch.uint8, device=DEV)
+    ws = torch.empty(H.halo_workspace_bytes(s, T if ws_tokens is None else ws_tokens, K), dtype=torch.uint8,
+                     device=DEV)
     pd = torch.from_numpy(np.ascontiguousarray(prio_dev_np)).to(DEV)
     dr = None if drop_np is None else torch.from_numpy(np.ascontiguousarray(drop_np)).to(DEV)
     y = torch.full((T, w.d), float("nan"), dtype=w.torch_dtype, device=DEV)

@@ -72,6 +72,10 @@ def test_workspace_bytes():
     assert 0 < a < b
     assert H.halo_workspace_bytes(H.Shape(4096, 11000, 128, 256, "bf16", n_groups=86), 1, 43) == 0
     assert H.halo_workspace_bytes(s, 1, 87) == 0
+    # a workspace sized for T tokens serves every smaller call: the size never falls as T grows
+    # (the number of group ranges in the prefill down projection does)
+    sizes = [H.halo_workspace_bytes(s, T, 43) for T in range(1, 2200, 7)]
+    assert all(b >= a > 0 for a, b in zip(sizes, sizes[1:]))
     assert H.halo_workspace_bytes(H.Shape(4090, 11008, 128, 256), 1, 4) == 0
 
 

@@ -363,6 +363,22 @@ def test_many_tokens_matrix_core_path_all_tokens(T, d, G, r, keepall):
     assert np.array_equal(g["y"], g2["y"])
 
 
+def test_workspace_sized_for_more_tokens_serves_a_smaller_call():
+    # the prefill down projection uses more ranges of groups (more partial-sum space per token) for
+    # fewer tokens; a workspace sized for 2100 tokens must still do for 70 and for 300
+    w = dataclasses.replace(hs.LLAMA7B_PREFILL, name="case", d=256, ffn=6 * 128, rank=64, T=300, seed=29)
+    _say("workspace for 2100 tokens, calls with 70 and 300")
+    L = hz.Layer(w)
+    K = 3
+    pd = H.halo_build_schedule(K, w.device_plr())
+    for T in (70, 300):
+        x = hs.hidden_states(w, 0, hz.DEV, T=T)
+        drop = hs.drop_outcomes(w, T=T)
+        a = hz.gpu_forward(w, L, x, K, pd, drop)
+        b = hz.gpu_forward(w, L, x, K, pd, drop, ws_tokens=2100)
+        assert np.array_equal(a["y"], b["y"]) and np.array_equal(a["mask"], b["mask"])
+
+
 def test_edge_cases_through_the_boundary():
     _say("edge cases: T=0, K=0, K=G at the fast path's group limit, G=1024")
     # T == 0 is a no-op that touches nothing
