@@ -102,8 +102,10 @@ int halo_ratios_min_max(int32_t n_dev, const double *mem, const double *comp, do
                         double *ratios);
 
 /*
- * Upper bound, in bytes, of the scratch any entry point below needs for T tokens
- * of this shape with k_keep groups kept per token.  Returns 0 for invalid arguments.
+ * Upper bound, in bytes, of the scratch any entry point below needs for up to T tokens
+ * of this shape with k_keep groups kept per token: the value never falls as T grows, so a
+ * workspace sized for the largest call serves the smaller ones.  Returns 0 for invalid
+ * arguments.
  */
 size_t halo_workspace_bytes(const halo_shape *shape, int32_t T, int32_t k_keep);
 
