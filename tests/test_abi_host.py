@@ -122,3 +122,15 @@ def test_binding_refuses_host_tensors():
     x = torch.zeros(1, 256)
     with pytest.raises(ValueError):
         H.halo_predict_scores(s, x, x, x, x, x)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    # one GPU by design: the benchmark says so instead of starting ranks
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    p = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True,
+                       text=True, timeout=120)
+    assert p.returncode != 0
+    assert "single-GPU" in p.stderr and p.stdout.strip() == ""
