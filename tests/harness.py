@@ -112,23 +112,48 @@ def oracle_forward(w, layer: Layer, x, K, prio_dev_np, drop_np, x_pred=None):
 
 INT_KEYS = ("order", "group_dev", "mask", "surv_idx", "n_surv")
 
+# Element-wise bar beside the relative-L2 one: no single output may be off by more than this many
+# root-mean-squares of its token's reference row.  A relative L2 of 2e-2 alone would let one wholly
+# wrong element of a 4096-wide row through (1/sqrt(4096) = 1.6e-2); an element that is wrong by its
+# own size is about one rms off.  bf16: the output rounding is 2^-9 of the element (elements reach
+# ~4.5 rms) plus the rounded activation's share -- observed <= 1.9e-2 over every parity case, bar = three times that;
+# f32: accumulation order only.
+ELEM_TOL = {1e-5: 5e-5, 2e-2: 6e-2}
+WORST = {"l2": 0.0, "elem": 0.0}          # largest ratios seen in this process (printed by the tests)
 
-def assert_parity(gpu, cpu, tol, what=""):
-    """Bit-exact scores / ranking / masks / indices; y within relative L2 `tol`, per token and whole."""
-    assert np.array_equal(gpu["scores"].view(np.uint32), cpu["scores"].view(np.uint32)), what + " scores"
-    for k in INT_KEYS:
-        assert np.array_equal(gpu[k], cpu[k]), f"{what} {k}"
-    yg, yc = gpu["y"], cpu["y"]
+
+def check_y(yg, yc, n_surv, tol, what=""):
+    """y of the HIP path against the oracle's: per token relative L2 <= tol and every element within
+    ELEM_TOL[tol] of the token's reference rms; tokens with no surviving group exactly zero."""
+    yg = np.asarray(yg, dtype=np.float64)
+    yc = np.asarray(yc, dtype=np.float64)
+    assert yg.shape == yc.shape, what + " shape"
     assert np.isfinite(yg).all(), what + " y finite"
     for t in range(yc.shape[0]):
-        if cpu["n_surv"][t] == 0:
+        if n_surv[t] == 0:
             assert not yg[t].any(), f"{what} token {t}: no survivor must give exact zeros"
-        else:
-            err = np.linalg.norm(yg[t] - yc[t]) / np.linalg.norm(yc[t])
-            assert err <= tol, f"{what} token {t}: rel L2 {err:.3e} > {tol}"
+            continue
+        diff = yg[t] - yc[t]
+        err = np.linalg.norm(diff) / np.linalg.norm(yc[t])
+        assert err <= tol, f"{what} token {t}: rel L2 {err:.3e} > {tol}"
+        rms = np.sqrt(np.mean(yc[t] ** 2))
+        worst = np.abs(diff).max() / rms
+        assert worst <= ELEM_TOL[tol], f"{what} token {t}: element {int(np.abs(diff).argmax())} off by {worst:.3e} rms"
+        if tol > 1e-3:
+            WORST["l2"] = max(WORST["l2"], err)
+            WORST["elem"] = max(WORST["elem"], worst)
     den = np.linalg.norm(yc)
     if den > 0:
         assert np.linalg.norm(yg - yc) / den <= tol, what + " whole tensor"
+
+
+def assert_parity(gpu, cpu, tol, what=""):
+    """Bit-exact scores / ranking / masks / indices; y within `tol` (relative L2, per token and whole)
+    and within the element-wise bar."""
+    assert np.array_equal(gpu["scores"].view(np.uint32), cpu["scores"].view(np.uint32)), what + " scores"
+    for k in INT_KEYS:
+        assert np.array_equal(gpu[k], cpu[k]), f"{what} {k}"
+    check_y(gpu["y"], cpu["y"], cpu["n_surv"], tol, what)
 
 
 # --------------------------------------------------------------------------
@@ -140,11 +165,23 @@ def rms_norm(h: torch.Tensor) -> torch.Tensor:
     return h * torch.rsqrt(h.pow(2).mean(dim=-1, keepdim=True) + 1e-5)
 
 
-def run_stack_gpu(w, keep, layers=None, check_layers=()):
+def stack_check_layers(w, n_random):
+    """Layers whose output is compared with the oracle: the first three, the middle pair, the last
+    pair, and n_random more drawn from the workload's seed."""
+    L = w.layers
+    fixed = {0, 1, 2, L // 2 - 1, L // 2, L - 2, L - 1}
+    rest = [l for l in range(L) if l not in fixed]
+    u = hs.uniform01(len(rest), hs.stream_key(w.seed, hs.TID_MISC, 77))
+    picked = [rest[i] for i in np.argsort(u, kind="stable")[:n_random]]
+    return sorted(fixed | set(picked))
+
+
+def run_stack_gpu(w, keep, layers=None, check_layers=(), on_layer=None):
     """Free-running stack on the GPU with the predictor one layer ahead (layer l+1's mask is
     predicted from layer l's input, as in the paper); layer 0 runs dense and lossless.
-    Returns {layer: dict(x, x_prev, y, mask, drop)} for the layers to check (device tensors
-    already copied to the host) and the final residual stream."""
+    For each layer of check_layers, on_layer(l, rec, pd_np, K) is called with
+    rec = dict(x, x_prev, y, mask, drop, host) (host copies) while the run goes on -- records
+    are not kept, a 70B layer is 2.8 GB as float32.  Returns the final residual stream."""
     s = shape_of(w)
     n_layers = w.layers if layers is None else layers
     T, G = w.T, w.n_groups
@@ -154,7 +191,6 @@ def run_stack_gpu(w, keep, layers=None, check_layers=()):
     ws = torch.empty(H.halo_workspace_bytes(s, T, G), dtype=torch.uint8, device=DEV)
     h = hs.hidden_states(w, 0, DEV, dtype=torch.float32)
     mask = torch.ones((T, G), dtype=torch.uint8, device=DEV)          # layer 0: every group, no loss
-    keep_out = {}
     cur = Layer(w, 0)
     x_prev = None
     for l in range(n_layers):
@@ -169,17 +205,19 @@ def run_stack_gpu(w, keep, layers=None, check_layers=()):
         else:
             H.halo_group_sparse_ffn(s, x, cur.Wg, cur.Wu, cur.Wd, mask, y, ws)
         torch.cuda.synchronize()
-        if l in check_layers:
-            keep_out[l] = dict(x=to_np32(x), x_prev=None if x_prev is None else to_np32(x_prev),
-                               y=to_np32(y).astype(np.float64), mask=mask.cpu().numpy(),
-                               host=cur.host(), drop=None if l == 0 else hs.drop_outcomes(w, l, 0))
+        if l in check_layers and on_layer is not None:
+            rec = dict(x=to_np32(x), x_prev=None if x_prev is None else to_np32(x_prev),
+                       y=to_np32(y).astype(np.float64), mask=mask.cpu().numpy(),
+                       host=cur.host(), drop=None if l == 0 else hs.drop_outcomes(w, l, 0))
+            on_layer(l, rec, pd_np, K)
+            del rec
         h = h + y.float()
         x_prev = x
         if nxt is not None:
             mask = mask_next
         cur._host = None
         cur = nxt
-    return keep_out, pd_np, K, h
+    return h
 
 
 def check_stack_layer(w, l, rec, pd_np, K, tol):
@@ -193,9 +231,4 @@ def check_stack_layer(w, l, rec, pd_np, K, tol):
         mask_ref = ref.build_group_mask(sc, K, pd_np, w.n_dev, rec["drop"])["mask"]
     assert np.array_equal(rec["mask"], mask_ref), f"layer {l}: mask"
     y_ref = ref.group_sparse_ffn(rec["x"], Wg, Wu, WdT, w.group_size, mask_ref)
-    for t in range(w.T):
-        if not mask_ref[t].any():
-            assert not rec["y"][t].any()
-        else:
-            err = np.linalg.norm(rec["y"][t] - y_ref[t]) / np.linalg.norm(y_ref[t])
-            assert err <= tol, f"layer {l} token {t}: rel L2 {err:.3e}"
+    check_y(rec["y"], y_ref, mask_ref.sum(axis=1), tol, f"layer {l}")

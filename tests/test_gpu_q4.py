@@ -72,7 +72,7 @@ def test_q4_llama7b_decode_full_size_steps():
     L = hz.Q4Layer(w)
     K = w.k_keep()
     pd = H.halo_build_schedule(K, w.device_plr())
-    for step in (0, 1, 7, 1023):
+    for step in (0, 1, 2, 3, 7, 100, 500, 1023):
         x = hs.hidden_states(w, step, hz.DEV)
         drop = hs.drop_outcomes(w, 0, step)
         g = hz.gpu_forward_q4(w, L, x, K, pd, drop)
@@ -168,25 +168,14 @@ def test_q4_full_size_single_layer_of_the_stacks(wl):
     hz.assert_parity(g, c, TOL["bf16"], "q4 " + wl.name)
 
 
-def test_q4_llama7b_prefill_sampled_tokens():
+def test_q4_llama7b_prefill_all_tokens():
     w = hs.LLAMA7B_PREFILL
-    _say("q4 7B prefill, 512 tokens")
+    _say("q4 7B prefill, 512 tokens, every token")
     L = hz.Q4Layer(w)
     x = hs.hidden_states(w, 0, hz.DEV)
     K = w.k_keep()
     pd = H.halo_build_schedule(K, w.device_plr())
     drop = hs.drop_outcomes(w)
     g = hz.gpu_forward_q4(w, L, x, K, pd, drop)
-    At, Bt, Wg, Wu, WdT = L.host()
-    xn = hz.to_np32(x)
-    sc = ref.predict_scores(xn, At, Bt)
-    assert np.array_equal(g["scores"].view(np.uint32), sc.view(np.uint32))
-    m = ref.build_group_mask(sc, K, pd, w.n_dev, drop)
-    for k in hz.INT_KEYS:
-        assert np.array_equal(g[k], m[k]), k
-    sample = [0, 1, 255, 256, 511] + [int(t) for t in np.where(m["n_surv"] == m["n_surv"].min())[0][:1]]
-    y_ref = ref.group_sparse_ffn(xn[sample], Wg, Wu, WdT, w.group_size, m["mask"][sample])
-    for k, t in enumerate(sample):
-        err = np.linalg.norm(g["y"][t] - y_ref[k]) / np.linalg.norm(y_ref[k])
-        assert err <= TOL["bf16"], (t, err)
-    assert np.isfinite(g["y"]).all()
+    c = hz.oracle_forward(w, L, x, K, pd, drop)
+    hz.assert_parity(g, c, TOL["bf16"], "q4 7B prefill")
