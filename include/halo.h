@@ -324,6 +324,27 @@ int halo_mha_forward_ahead(const halo_mha_shape *shape, const void *x, const voi
 int halo_profile_begin(int32_t max_launches, int32_t every);
 int halo_profile_end(double *total_ms, int64_t *launches, char *kernel_name, int32_t name_cap);
 
+/*
+ * Benchmark aids (not part of the paper's method): what this GPU itself sustains for the two
+ * resources the path is priced against.  Both enqueue their kernels on `stream`, time them with a
+ * HIP event pair and WAIT for the result; results go to HOST pointers (each may be NULL).
+ *   halo_peak_read_stream  reads `launches` windows of window_bytes (rounded down to whole 16 KiB
+ *       runs) from the device buffer buf, one kernel launch per window, consecutive launches on
+ *       consecutive windows of the buffer (wrapping round), with the access pattern of the
+ *       one-token gate/up kernel.  gbps = bytes read / elapsed time, launch gaps included, so a
+ *       window of a kernel's own size gives what a launch of that size can reach, and a large
+ *       window the ceiling of the stream itself.  buf is only read; sink is 4 bytes of device
+ *       memory that are practically never written.
+ *   halo_peak_mfma_bf16    `launches` launches of a kernel that issues iters * 16 bf16 16x16x32
+ *       matrix instructions per wave (eight waves on every compute unit) on non-zero operands;
+ *       tflops = multiply-adds * 2 / elapsed time.  sink: 256 bytes of device memory.
+ * Errors: HALO_ERR_NULL, HALO_ERR_ARG (misaligned buf, window larger than the buffer or smaller
+ * than 16 KiB, counts out of range), HALO_ERR_HIP.
+ */
+int halo_peak_read_stream(const void *buf, size_t buf_bytes, size_t window_bytes, int32_t launches,
+                          void *sink, void *stream, double *gbps, double *us_per_launch);
+int halo_peak_mfma_bf16(int32_t iters, int32_t launches, void *sink, void *stream, double *tflops);
+
 #ifdef __cplusplus
 }
 #endif

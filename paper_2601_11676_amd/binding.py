@@ -117,6 +117,10 @@ def load_library():
     lib.halo_profile_begin.argtypes = [i32, i32]
     lib.halo_profile_end.restype = C.c_int
     lib.halo_profile_end.argtypes = [vp, vp, vp, i32]
+    lib.halo_peak_read_stream.restype = C.c_int
+    lib.halo_peak_read_stream.argtypes = [vp, sz, sz, i32, vp, vp, vp, vp]
+    lib.halo_peak_mfma_bf16.restype = C.c_int
+    lib.halo_peak_mfma_bf16.argtypes = [i32, i32, vp, vp, vp]
     _lib = lib
     return lib
 
@@ -361,3 +365,20 @@ def halo_profile_end():
     rc = load_library().halo_profile_end(C.byref(ms), C.byref(n), name, 64)
     _check("halo_profile_end", rc)
     return ms.value, n.value, name.value.decode()
+
+
+def halo_peak_read_stream(buf, window_bytes: int, launches: int, sink, stream=None):
+    """Returns (GB/s, microseconds per launch) of the read-stream aid over windows of `buf`."""
+    g, us = C.c_double(0.0), C.c_double(0.0)
+    rc = load_library().halo_peak_read_stream(_ptr(buf), buf.numel() * buf.element_size(), int(window_bytes),
+                                              int(launches), _ptr(sink), _stream(stream), C.byref(g), C.byref(us))
+    _check("halo_peak_read_stream", rc)
+    return g.value, us.value
+
+
+def halo_peak_mfma_bf16(iters: int, launches: int, sink, stream=None) -> float:
+    """Returns the bf16 matrix-instruction rate of the MFMA aid in TFLOP/s."""
+    t = C.c_double(0.0)
+    rc = load_library().halo_peak_mfma_bf16(int(iters), int(launches), _ptr(sink), _stream(stream), C.byref(t))
+    _check("halo_peak_mfma_bf16", rc)
+    return t.value
