@@ -185,6 +185,30 @@ int halo_ffn_forward(const halo_shape *shape, const void *x, const void *x_pred,
                      void *workspace, size_t ws_bytes, void *stream);
 
 /*
+ * halo_ffn_forward for callers that cannot allocate device memory or hand over a workspace
+ * (code running under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc):
+ * same arguments, results and errors as halo_ffn_forward, without `workspace` / `ws_bytes`.
+ * The scratch is a fixed array of halo_static_scratch_bytes() bytes (8 MiB) inside the
+ * library's code object; every GPU that runs the library holds its own copy until the process
+ * ends.  The call allocates and frees nothing.
+ *   - A call whose halo_workspace_bytes(shape, T, k_keep) exceeds that size returns
+ *     HALO_ERR_WORKSPACE and enqueues nothing (bf16, d = 4096, 86 groups: up to 47 tokens;
+ *     d = 8192, 224 groups: up to 23).
+ *   - The first call made with a given device current looks up that device's copy of the array
+ *     (a runtime query, no allocation); make that first call outside stream capture.
+ *   - All calls on one GPU share the array, which keeps the previous call's contents; nothing
+ *     in it has to be cleared (each kernel writes what it later reads).  Calls that overlap on
+ *     one GPU -- different streams, or different host threads -- race on it: serialise them.
+ */
+size_t halo_static_scratch_bytes(void);
+int halo_ffn_forward_static(const halo_shape *shape, const void *x, const void *x_pred, int32_t T,
+                            const void *At, const void *Bt, const void *Wg, const void *Wu,
+                            const void *Wd, int32_t k_keep, const int8_t *prio_dev, int32_t n_dev,
+                            const uint8_t *drop, void *y, float *scores, int32_t *order,
+                            int8_t *group_dev, uint8_t *mask, int32_t *surv_idx, int32_t *n_surv,
+                            void *stream);
+
+/*
  * Overlapped form of the whole pass (paper Sec. III-B.3 and its figure of the generation
  * phase with overlapped processes: the Pred process for the next block runs beside the
  * Load/Comp of the current one, one layer ahead).  On `stream`:

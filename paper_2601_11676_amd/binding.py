@@ -91,6 +91,11 @@ def load_library():
     lib.halo_ffn_forward.restype = C.c_int
     lib.halo_ffn_forward.argtypes = [ps, vp, vp, i32, vp, vp, vp, vp, vp, i32, vp, i32, vp, vp,
                                      vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.halo_static_scratch_bytes.restype = sz
+    lib.halo_static_scratch_bytes.argtypes = []
+    lib.halo_ffn_forward_static.restype = C.c_int
+    lib.halo_ffn_forward_static.argtypes = [ps, vp, vp, i32, vp, vp, vp, vp, vp, i32, vp, i32, vp, vp,
+                                            vp, vp, vp, vp, vp, vp, vp]
     lib.halo_ffn_forward_ahead.restype = C.c_int
     lib.halo_ffn_forward_ahead.argtypes = [ps, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, i32,
                                            vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -233,6 +238,23 @@ def halo_ffn_forward(shape: Shape, x, At, Bt, Wg, Wu, Wd, k_keep: int, prio_dev,
         _ptr(group_dev), _ptr(mask), _ptr(surv_idx), _ptr(n_surv), _ptr(workspace),
         workspace.numel(), _stream(stream))
     _check("halo_ffn_forward", rc)
+
+
+def halo_static_scratch_bytes() -> int:
+    return int(load_library().halo_static_scratch_bytes())
+
+
+def halo_ffn_forward_static(shape: Shape, x, At, Bt, Wg, Wu, Wd, k_keep: int, prio_dev, n_dev: int,
+                            drop, y, x_pred=None, scores=None, order=None, group_dev=None,
+                            mask=None, surv_idx=None, n_surv=None, stream=None) -> None:
+    """halo_ffn_forward over the library's own fixed scratch array: no workspace argument."""
+    T = x.shape[0]
+    xp = x if x_pred is None else x_pred
+    rc = load_library().halo_ffn_forward_static(
+        C.byref(shape.c), _ptr(x), _ptr(xp), T, _ptr(At), _ptr(Bt), _ptr(Wg), _ptr(Wu), _ptr(Wd),
+        int(k_keep), _ptr(prio_dev), int(n_dev), _ptr(drop), _ptr(y), _ptr(scores), _ptr(order),
+        _ptr(group_dev), _ptr(mask), _ptr(surv_idx), _ptr(n_surv), _stream(stream))
+    _check("halo_ffn_forward_static", rc)
 
 
 def halo_ffn_forward_ahead(shape: Shape, x, Wg, Wu, Wd, mask_cur, y, x_pred_next, At_next, Bt_next,

@@ -3,8 +3,15 @@
 #include "../../include/halo.h"
 
 #include <cmath>
+#include <mutex>
 
 #include "kernels.hpp"
+
+// Scratch of halo_ffn_forward_static: one array per GPU the library's code object is loaded on,
+// held until the process ends.  The name is only a host-side handle: host code never passes it to
+// a kernel, it asks the runtime for the array's device address once per device (scratch_of).
+constexpr size_t kStaticScratchBytes = (size_t)8 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace {
 
@@ -125,6 +132,26 @@ struct MhaWorkspace {
         bytes = off;
     }
 };
+
+// Device address of `scratch` on the current device (each GPU has its own copy at its own
+// address), resolved on the first call made with that device current.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+int scratch_of(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return HALO_ERR_HIP;
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return HALO_ERR_HIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return HALO_OK;
+}
 
 }  // namespace
 
@@ -345,6 +372,30 @@ int halo_ffn_forward(const halo_shape *shape, const void *x, const void *x_pred,
     e = launch_ffn_decode(shape->dtype, x, T, shape->d, shape->n_groups, shape->group_size, Wg, Wu,
                           Wd, mk, y, ws.dec, s);
     return e == hipSuccess ? HALO_OK : HALO_ERR_HIP;
+}
+
+size_t halo_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int halo_ffn_forward_static(const halo_shape *shape, const void *x, const void *x_pred, int32_t T,
+                            const void *At, const void *Bt, const void *Wg, const void *Wu,
+                            const void *Wd, int32_t k_keep, const int8_t *prio_dev, int32_t n_dev,
+                            const uint8_t *drop, void *y, float *scores, int32_t *order,
+                            int8_t *group_dev, uint8_t *mask, int32_t *surv_idx, int32_t *n_surv,
+                            void *stream)
+{
+    int rc = check_shape(shape);
+    if (rc) return rc;
+    if (T < 0 || k_keep < 0 || k_keep > shape->n_groups || n_dev < 1 || n_dev > 127) return HALO_ERR_ARG;
+    // the need is known from the arguments alone: a call that does not fit is refused before anything runs
+    if (Workspace(*shape, T, k_keep, nullptr).bytes > kStaticScratchBytes) return HALO_ERR_WORKSPACE;
+    if (T == 0) return HALO_OK;
+    void *ws = nullptr;
+    rc = scratch_of(&ws);
+    if (rc) return rc;
+    // every kernel of the pass writes the part of the scratch it later reads, so nothing has to be
+    // cleared between calls; the kernels take the address like any caller's workspace
+    return halo_ffn_forward(shape, x, x_pred, T, At, Bt, Wg, Wu, Wd, k_keep, prio_dev, n_dev, drop, y, scores,
+                            order, group_dev, mask, surv_idx, n_surv, ws, kStaticScratchBytes, stream);
 }
 
 int halo_group_sparse_ffn_q4(const halo_shape *shape, const void *x, int32_t T, const void *Wg_codes,
