@@ -349,6 +349,15 @@ int halo_profile_begin(int32_t max_launches, int32_t every);
 int halo_profile_end(double *total_ms, int64_t *launches, char *kernel_name, int32_t name_cap);
 
 /*
+ * Harness aid (not part of the paper's method): the glue between the blocks of an FFN-only stack,
+ * one launch per layer:  h[t] += y[t] (skipped if y is NULL);  x[t] = h[t] / sqrt(mean(h[t]^2) + eps).
+ *   h [T][d] float (in/out, the residual stream), y [T][d] (dtype) or NULL, x [T][d] (dtype) out.
+ * Errors: HALO_ERR_NULL, HALO_ERR_DTYPE, HALO_ERR_ARG (T < 0, d < 1, eps < 0), HALO_ERR_HIP.
+ */
+int halo_stack_residual_norm(float *h, const void *y, void *x, int32_t T, int32_t d, int32_t dtype,
+                             float eps, void *stream);
+
+/*
  * Benchmark aids (not part of the paper's method): what this GPU itself sustains for the two
  * resources the path is priced against.  Both enqueue their kernels on `stream`, time them with a
  * HIP event pair and WAIT for the result; results go to HOST pointers (each may be NULL).

@@ -9,6 +9,6 @@ from .binding import (  # noqa: F401
     halo_build_group_mask, halo_group_sparse_ffn, halo_ffn_forward, halo_ffn_forward_ahead,
     halo_ffn_forward_static, halo_static_scratch_bytes,
     halo_group_sparse_ffn_q4, halo_ffn_forward_q4, halo_ffn_forward_ahead_q4,
-    halo_profile_begin, halo_peak_read_stream, halo_peak_mfma_bf16,
+    halo_profile_begin, halo_peak_read_stream, halo_peak_mfma_bf16, halo_stack_residual_norm,
     halo_profile_end, halo_ratios_comp_greedy, halo_ratios_min_max, library_path, load_library, pack_down_proj, prepared,
 )

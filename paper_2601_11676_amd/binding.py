@@ -122,6 +122,8 @@ def load_library():
     lib.halo_profile_begin.argtypes = [i32, i32]
     lib.halo_profile_end.restype = C.c_int
     lib.halo_profile_end.argtypes = [vp, vp, vp, i32]
+    lib.halo_stack_residual_norm.restype = C.c_int
+    lib.halo_stack_residual_norm.argtypes = [vp, vp, vp, i32, i32, i32, C.c_float, vp]
     lib.halo_peak_read_stream.restype = C.c_int
     lib.halo_peak_read_stream.argtypes = [vp, sz, sz, i32, vp, vp, vp, vp]
     lib.halo_peak_mfma_bf16.restype = C.c_int
@@ -404,3 +406,14 @@ def halo_peak_mfma_bf16(iters: int, launches: int, sink, stream=None) -> float:
     rc = load_library().halo_peak_mfma_bf16(int(iters), int(launches), _ptr(sink), _stream(stream), C.byref(t))
     _check("halo_peak_mfma_bf16", rc)
     return t.value
+
+
+def halo_stack_residual_norm(h, y, x, eps: float = 1e-5, stream=None) -> None:
+    """h += y (y may be None); x = h / sqrt(mean(h^2) + eps), row by row.  h float32, x/y float32 or bf16."""
+    T, d = h.shape
+    if h.dtype != torch.float32:
+        raise ValueError("h must be float32")
+    code = HALO_F32 if x.dtype == torch.float32 else HALO_BF16
+    rc = load_library().halo_stack_residual_norm(_ptr(h), _ptr(y), _ptr(x), int(T), int(d), code, float(eps),
+                                                 _stream(stream))
+    _check("halo_stack_residual_norm", rc)

@@ -516,3 +516,35 @@ def test_drop_strategies_low_norm_ordering_loses_less_than_random_ordering():
     e_rand = error_with(rnd.view(T, G))
     e_worst = error_with(-norms)                          # losing the high-norm groups instead
     assert e_norm < 0.6 * e_rand < e_worst, (e_norm, e_rand, e_worst)
+
+
+def test_stack_glue_and_ceiling_aids():
+    # harness / benchmark aids of the library: residual + norm between the blocks of a stack against
+    # the same formula in float64, and the two ceiling probes returning plausible figures for this GPU
+    _say("stack glue kernel, read-stream and matrix-instruction probes")
+    for dt in (torch.float32, torch.bfloat16):
+        for T, d in [(1, 4096), (4, 5120), (8, 8192), (3, 520)]:
+            g = torch.Generator().manual_seed(T * 1000 + d)
+            h = torch.randn((T, d), generator=g, dtype=torch.float32)
+            y = torch.randn((T, d), generator=g, dtype=torch.float32).to(dt)
+            hd, yd = h.to(hz.DEV), y.to(hz.DEV)
+            x = torch.empty((T, d), dtype=dt, device=hz.DEV)
+            H.halo_stack_residual_norm(hd, yd, x)
+            torch.cuda.synchronize()
+            h64 = h.double() + y.double()
+            x64 = h64 / torch.sqrt((h64 ** 2).mean(dim=1, keepdim=True) + 1e-5)
+            assert torch.allclose(hd.cpu().double(), h64, rtol=0, atol=1e-6)
+            tol = 1e-5 if dt == torch.float32 else 2.0 ** -8
+            assert (x.cpu().double() - x64).abs().max() <= tol * x64.abs().max()
+            h2 = hd.clone()
+            H.halo_stack_residual_norm(h2, None, x)           # no y: h unchanged
+            torch.cuda.synchronize()
+            assert torch.equal(h2, hd)
+    buf = torch.full((1 << 30,), 3, dtype=torch.uint8, device=hz.DEV)
+    sink = torch.zeros(256, dtype=torch.uint8, device=hz.DEV)
+    gbps, us = H.halo_peak_read_stream(buf, 256 << 20, 8, sink)
+    assert 2000.0 < gbps < 8000.0 and us > 0, gbps
+    tf = H.halo_peak_mfma_bf16(2000, 2, sink)
+    assert 500.0 < tf < 2600.0, tf
+    assert not sink.any()
+    _say(f"read stream {gbps:.0f} GB/s, bf16 matrix instructions {tf:.0f} TFLOP/s")
