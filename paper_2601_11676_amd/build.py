@@ -16,6 +16,10 @@ FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-fno-fast-math", "-Wall", "-Wextra", "-Wno-unused-parameter",
+    # the first kernel arguments arrive in scalar registers with the wave instead of through a load
+    # of the argument block: one memory round trip less at the head of every kernel (7B decode step
+    # 25.4 -> 24.9 us); kernels keep a prologue that loads them where the dispatcher does not preload
+    "-mllvm", "-amdgpu-kernarg-preload-count=16",
 ]
 
 
@@ -24,6 +28,7 @@ def sources():
 
 
 def build(verbose: bool = False, extra=()) -> str:
+    extra = list(extra) + os.environ.get("HALO_EXTRA_FLAGS", "").split()
     cmd = ["hipcc", *FLAGS, *extra, "-o", OUT, *sources()]
     if verbose:
         print(" ".join(cmd), flush=True)
