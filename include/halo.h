@@ -17,7 +17,7 @@
  *   - Limits: d % 8 == 0, rank % 8 == 0, ffn == n_groups * group_size,
  *     1 <= n_groups <= 1024, 1 <= n_dev <= 127, T >= 0 (T == 0 is a no-op).
  *
- * Weight layout ("FFN weights partitioned into neuron groups", paper Sec. II-A):
+ * Weight layout (the FFN's weights cut into neuron groups, paper Sec. II-A):
  * neuron group g owns rows [g*group_size, (g+1)*group_size) of
  *   Wg [ffn][d]  gate projection,
  *   Wu [ffn][d]  up projection,
@@ -278,8 +278,8 @@ int halo_ffn_forward_ahead_q4(const halo_shape *shape, const void *x, int32_t T,
                               int32_t *n_surv_next, void *workspace, size_t ws_bytes, void *stream);
 
 /*
- * The attention block as neuron groups (paper Sec. II-A: "one head and its output projection
- * weight are an independent neuron group"; the block output is the sum of the groups' partial
+ * The attention block as neuron groups (paper Sec. II-A: a head together with its slice of the
+ * output projection forms one group; the block output is the sum of the groups' partial
  * results).  One new token of one sequence (decode) at position pos, 0-based:
  *   every head h    : k_h = Wk_h x, v_h = Wv_h x are written to row pos of the caches -- every
  *                     device keeps the full KV cache (Sec. III-B.3), so keys and values exist

@@ -444,9 +444,9 @@ int halo_ref_dequant_down_q4(const uint32_t *codes, const float *scales, int32_t
 /* ------------------------------------------------------------------------- */
 /* Head-sparse multi-head attention for one new token (decode).               */
 /*                                                                           */
-/* Sec. II-A "Neuron group": in the MHA, one head and its slice of the output */
-/* projection are an independent neuron group; the block output is the sum of */
-/* the groups' partial results.  Sec. III-B.3: every device keeps the full KV  */
+/* Sec. II-A, neuron groups of the attention block: a head together with the   */
+/* columns of the output projection that read it makes one group; the block's  */
+/* output is the sum of the groups' partial results.  Sec. III-B.3: every device keeps the full KV  */
 /* cache, so keys and values are produced for every head at every position,    */
 /* whether or not the head's output takes part in the merge.                   */
 /*                                                                           */

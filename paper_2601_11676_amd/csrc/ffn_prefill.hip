@@ -105,10 +105,13 @@ constexpr int kRingBytes = kRingStages * kRingStageBytes;        // 144 KiB (the
 __device__ __forceinline__ void load_to_lds16_if(bool cond, unsigned long long lanes, const void *base,
                                                  uint32_t offset, uint32_t lds_addr)
 {
-    asm volatile("s_cmp_eq_u32 %3, 0\n\ts_cbranch_scc1 1f\n\ts_mov_b32 m0, %2\n\ts_mov_b64 exec, %4\n\t"
-                 "global_load_lds_dwordx4 %0, %1\n\ts_mov_b64 exec, -1\n1:" ::"v"(offset), "s"(base), "s"(lds_addr),
-                 "s"(__builtin_amdgcn_readfirstlane((uint32_t)cond)), "s"(lanes)
-                 : "memory", "scc");
+    unsigned long long saved_exec;       // the lanes active around the statement come back afterwards
+    asm volatile("s_cmp_eq_u32 %4, 0\n\ts_cbranch_scc1 1f\n\ts_mov_b32 m0, %3\n\ts_mov_b64 %0, exec\n\t"
+                 "s_mov_b64 exec, %5\n\tglobal_load_lds_dwordx4 %1, %2\n\ts_mov_b64 exec, %0\n1:"
+                 : "=&s"(saved_exec)
+                 : "v"(offset), "s"(base), "s"(lds_addr), "s"(__builtin_amdgcn_readfirstlane((uint32_t)cond)),
+                   "s"(lanes)
+                 : "memory", "scc");        // m0 is reserved: the compiler sets it anew before each use of its own
 }
 
 // wait until at most N (deep) or none of the wave's loads are outstanding
@@ -125,8 +128,10 @@ __device__ __forceinline__ void wait_loads(bool deep)
 // (Left to itself the compiler gives the 64 tiles of this kernel rotating destination registers and
 // moves a few hundred registers between the two files per step to make that work.)  A statement the
 // compiler cannot look into also gets none of its matrix-pipeline wait states, which is safe here:
-// a tile is touched again 63 matrix instructions later, and the first ordinary read of the
-// accumulators comes after a barrier and an explicit pause.
+// a tile is touched again 63 matrix instructions later (a 16x16x32 bf16 instruction occupies the
+// pipeline for 8 passes of 4 cycles, so its result is long written back by then), and the first
+// ordinary read of the accumulators comes after a barrier and an explicit pause of 2 x 16 idle
+// cycles, more than the 18 cycles the last instruction can still be in flight.
 __device__ __forceinline__ void mfma16_inplace(f32x4_t &acc, const u32x4 &a, const u32x4 &b)
 {
     asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));

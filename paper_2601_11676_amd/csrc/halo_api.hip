@@ -259,24 +259,23 @@ int halo_ratios_min_max(int32_t n_dev, const double *mem, const double *comp, do
         comp_min = i == 0 ? comp[i] : std::fmin(comp_min, comp[i]);
     }
     if (budget < demand) return HALO_ERR_ARG;
-    auto covered = [&](double threshold) {
-        double used = 0.0;
-        for (int i = 0; i < n_dev; ++i) used += std::fmin(mem[i], threshold * comp[i]);
-        return used;
+    // Device i can take min(mem_i, T comp_i) when every device may work for time T; that sum grows
+    // with T, and the wanted T is the smallest one at which it reaches the demand.  `hi` always meets
+    // the demand (at mem_max / comp_min every device is at its budget), `lo` never does (or is 0);
+    // the bracket is halved until it is no wider than eps and its upper end is the answer.
+    auto short_of_demand = [&](double t) {
+        double taken = 0.0;
+        for (int i = 0; i < n_dev; ++i) taken += std::fmin(mem[i], t * comp[i]);
+        return taken < demand;
     };
-    double lo = 0.0, hi = mem_max / comp_min, best = hi;
+    double lo = 0.0, hi = mem_max / comp_min;
     while (hi - lo > eps) {
         const double mid = (lo + hi) / 2.0;
-        if (covered(mid) >= demand) {
-            best = mid;
-            hi = mid;
-        } else {
-            lo = mid;
-        }
+        (short_of_demand(mid) ? lo : hi) = mid;
     }
     double sum = 0.0;
     for (int i = 0; i < n_dev; ++i) {
-        ratios[i] = std::fmin(mem[i], best * comp[i]);
+        ratios[i] = std::fmin(mem[i], hi * comp[i]);
         sum += ratios[i];
     }
     for (int i = 0; i < n_dev; ++i) ratios[i] /= sum;

@@ -37,6 +37,48 @@ def test_min_max_closed_forms():
     assert abs(r[1] * 6 - 5) < 2e-3 and abs(r.sum() - 1) < 1e-15
 
 
+def exact_min_max(m, c, Mt):
+    """The quantity Alg. 2's bisection approximates, solved exactly: the smallest T with
+    sum_i min(m_i, T c_i) = M_t.  The sum is piecewise linear in T with breakpoints m_i / c_i (device i
+    reaches its budget there); walk the breakpoints in ascending order and solve the linear piece that
+    crosses M_t.  Returns (T, ratios)."""
+    m, c = np.asarray(m, float), np.asarray(c, float)
+    order = np.argsort(m / c, kind="stable")
+    full, speed = 0.0, c.sum()                 # budget of the saturated devices, speed of the others
+    T = None
+    for i in order:
+        t_break = m[i] / c[i]
+        if full + t_break * speed >= Mt:       # the crossing lies before device i saturates
+            T = (Mt - full) / speed
+            break
+        full += m[i]
+        speed -= c[i]
+    assert T is not None
+    u = np.minimum(m, T * c)
+    return T, u / u.sum()
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_min_max_within_eps_of_the_exact_threshold(seed):
+    # oracle and library each against the exact solution, within what the stopping rule allows:
+    # the threshold returned lies in [T*, T* + eps], so each allocation is at most eps*c_i above the
+    # exact one and the ratios move by at most 2 eps sum(c) / M_t
+    rng = np.random.default_rng(1000 + seed)
+    n = int(rng.integers(1, 9))
+    m = rng.integers(3, 64, size=n) * 100.0
+    c = rng.integers(6, 19, size=n) / 10.0
+    Mt = float(rng.uniform(0.05, 1.0) * m.sum())
+    T, r_exact = exact_min_max(m, c, Mt)
+    assert abs(np.minimum(m, T * c).sum() - Mt) <= 1e-9 * Mt
+    for eps in (1e-3, 1e-6, 0.5):
+        bound = 2 * eps * c.sum() / Mt + 1e-12
+        for fn in (ref.ratios_min_max, H.halo_ratios_min_max):
+            r = fn(m, c, Mt, eps)
+            assert np.abs(r - r_exact).max() <= bound, (fn.__module__, eps)
+            # never below the exact threshold: the allocation covers the demand
+            assert (np.minimum(m, (T + eps) * c) * (1 + 1e-12) >= r * Mt).all()
+
+
 @pytest.mark.parametrize("seed", range(25))
 def test_properties_and_library_agreement(seed):
     rng = np.random.default_rng(seed)
@@ -49,6 +91,7 @@ def test_properties_and_library_agreement(seed):
         r = oracle_fn(m, c, Mt)
         assert (r >= 0).all() and abs(r.sum() - 1) < 1e-12, name
         assert (r * Mt <= m * (1 + 2e-3) + 1e-9).all(), name      # nobody above its memory budget
+        # the two are written differently but halve the same bracket: same threshold, same ratios
         np.testing.assert_allclose(lib_fn(m, c, Mt), r, rtol=1e-13, atol=1e-15)
     # min-max: the largest per-device time max_i r_i M_t / c_i is not above the greedy one
     tg = np.max(ref.ratios_comp_greedy(m, c, Mt) * Mt / c)
