@@ -249,8 +249,10 @@ int halo_ffn_forward_ahead(const halo_shape *shape, const void *x, int32_t T, co
  * Needs group_size == 128 and d % 128 == 0 (HALO_ERR_SHAPE otherwise); shape->dtype is the type
  * of x, y and the predictor weights.  All pointers are device pointers, 16-byte aligned.
  * Everything else -- mask semantics, workspace, stream, errors -- is as in
- * halo_group_sparse_ffn / halo_ffn_forward.  One bf16 token with d in {4096, 8192} and
- * n_groups <= 256 streams each surviving code byte once; other shapes take a plain path.
+ * halo_group_sparse_ffn / halo_ffn_forward.  Tuned paths (bf16 activations, n_groups <= 256): one
+ * token with d in {4096, 8192} (every surviving code byte streamed once, float ALUs), and 2..16
+ * tokens with d a multiple of 1024 up to 8192 (matrix cores, codes expanded in registers); other
+ * shapes and float32 activations take a plain path that dequantises element by element.
  */
 int halo_group_sparse_ffn_q4(const halo_shape *shape, const void *x, int32_t T, const void *Wg_codes,
                              const void *Wg_scales, const void *Wu_codes, const void *Wu_scales,
@@ -266,8 +268,8 @@ int halo_ffn_forward_q4(const halo_shape *shape, const void *x, const void *x_pr
                         void *stream);
 
 /* halo_ffn_forward_ahead over 4-bit weights: same contract, same weight arguments as
- * halo_group_sparse_ffn_q4.  The prediction rides in spare workgroups for one bf16 token with
- * d in {4096, 8192} and n_groups <= 256; otherwise it is enqueued after the FFN. */
+ * halo_group_sparse_ffn_q4.  The prediction rides in spare workgroups on the tuned paths named
+ * there; otherwise it is enqueued after the FFN. */
 int halo_ffn_forward_ahead_q4(const halo_shape *shape, const void *x, int32_t T, const void *Wg_codes,
                               const void *Wg_scales, const void *Wu_codes, const void *Wu_scales,
                               const void *Wd_codes, const void *Wd_scales, const uint8_t *mask_cur, void *y,

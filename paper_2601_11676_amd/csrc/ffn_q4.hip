@@ -18,22 +18,9 @@
 #include "kernels.hpp"
 #include "mask_device.hpp"
 #include "mask_words.hpp"
+#include "q4_codes.hpp"
 
 namespace halo {
-
-constexpr int kQ4Block = 128;
-
-// codes 2i and 2i+1 of a word as the packed bf16 pair (128 + c, 128 + c): a shift and one
-// and-or.  The three-operand form is written out because the compiler otherwise emits the
-// "and" and the "or" separately (its two constants cannot both be literals of one instruction;
-// here they sit in registers).
-__device__ __forceinline__ uint32_t q4_pair(uint32_t w, int i)
-{
-    uint32_t r;
-    const uint32_t sh = i ? w >> (4 * i) : w;
-    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(sh), "v"(0x000F000Fu), "v"(0x43004300u));
-    return r;
-}
 
 // sum over the 32 elements of one 16-byte code piece of (128 + c) * x, x as 16 packed bf16 pairs
 __device__ __forceinline__ float q4_dot32(const u32x4 &c, const u32x4 (&x)[4])
@@ -63,8 +50,6 @@ __device__ __forceinline__ float sum32(const u32x4 (&x)[4])
     }
     return a;
 }
-
-__device__ __forceinline__ float bf16_bits_to_float(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
 
 // ---------------------------------------------------------------------------
 // one token, bf16 activations, d = NH * 2048, group size 128, G <= 256
@@ -404,6 +389,8 @@ hipError_t launch_ffn_q4(int dtype, const void *x, int T, int d, int G, int gs, 
                                                                      by, ah ? 1 : 0, nx);
         return hipGetLastError();
     }
+    if (q4_mfma_path_supported(T, d, G, gs))
+        return launch_ffn_q4_mfma(bx, T, d, G, w, mask, by, ws, s, ahead, ahead_fused);
     return q4_generic<bf16_t>(bx, T, d, G, gs, w, mask, by, ws, s);
 }
 

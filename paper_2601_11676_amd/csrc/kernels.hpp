@@ -121,6 +121,12 @@ hipError_t launch_ffn_q4(int dtype, const void *x, int T, int d, int G, int gs, 
                          const uint8_t *mask, void *y, const DecodeScratch &ws, hipStream_t s,
                          const AheadArgs *ahead = nullptr, bool *ahead_fused = nullptr);
 
+// ffn_q4_mt.hip : 4-bit weights, 2..16 tokens, matrix cores
+bool q4_mfma_path_supported(int T, int d, int G, int gs);
+hipError_t launch_ffn_q4_mfma(const bf16_t *x, int T, int d, int G, const Q4Weights &w, const uint8_t *mask,
+                              bf16_t *y, const DecodeScratch &ws, hipStream_t s, const AheadArgs *ahead = nullptr,
+                              bool *ahead_fused = nullptr);
+
 // mha_decode.hip : head-sparse attention for one new token (bf16, head dimension 128)
 struct MhaScratch {
     float *q;            // [H][128] queries of the surviving heads, compact by slot

@@ -66,6 +66,29 @@ def test_q4_one_token_streaming_path(d, G, K):
         hz.assert_parity(g, c, TOL["bf16"], f"q4 t1 d={d} step {step}")
 
 
+@pytest.mark.parametrize("T,d,G,r", [
+    (2, 1024, 5, 64),
+    (4, 5120, 9, 256),       # LLaMA-13B row length (ten 512-element chunks: the last code buffer is half full)
+    (8, 8192, 7, 512),       # LLaMA-2-70B row length
+    (16, 4096, 6, 256),
+    (5, 4096, 20, 256),      # union larger than any token's set; ragged neuron runs per wave
+    (3, 512, 3, 40),         # a single chunk per row
+])
+def test_q4_few_tokens_matrix_core_path(T, d, G, r):
+    w = dataclasses.replace(hs.LLAMA13B_STACK, name="case", d=d, ffn=G * 128, rank=r, T=T, layers=1, seed=18)
+    _say(f"q4 few tokens T={T} d={d} G={G}")
+    L = hz.Q4Layer(w)
+    x = hs.hidden_states(w, 0, hz.DEV)
+    for K in (max(1, G // 2), G):
+        pd = H.halo_build_schedule(K, w.device_plr())
+        drop = hs.drop_outcomes(w, T=T)
+        if K < G:
+            drop[T - 1] = 1                    # one token loses every device: exact zeros expected
+        g = hz.gpu_forward_q4(w, L, x, K, pd, drop)
+        c = hz.oracle_forward(w, L, x, K, pd, drop)
+        hz.assert_parity(g, c, TOL["bf16"], f"q4 few tokens K={K}")
+
+
 def test_q4_llama7b_decode_full_size_steps():
     w = hs.LLAMA7B_DECODE
     _say("q4 llama7b decode full size")
@@ -110,7 +133,7 @@ def test_q4_ffn_entry_point_with_handmade_masks_and_errors():
     torch.cuda.synchronize()
 
 
-@pytest.mark.parametrize("d,T", [(4096, 1), (8192, 1), (512, 3)])
+@pytest.mark.parametrize("d,T", [(4096, 1), (8192, 1), (512, 3), (5120, 4), (8192, 8), (384, 3)])
 def test_q4_one_step_ahead_overlap_equals_the_serial_pass(d, T):
     # predictor + mask of step s+1 beside (or, for shapes without spare workgroups, after) the FFN of step s
     w = dataclasses.replace(hs.LLAMA7B_DECODE, name="case", d=d, ffn=20 * 128, T=T, seed=9)
@@ -120,7 +143,7 @@ def test_q4_one_step_ahead_overlap_equals_the_serial_pass(d, T):
     G, K, n = w.n_groups, 10, 5
     pd = H.halo_build_schedule(K, w.device_plr())
     xs = [hs.hidden_states(w, i, hz.DEV) for i in range(n + 1)]
-    drops = [hs.drop_outcomes(w, 0, i) for i in range(n + 1)]
+    drops = [hs.drop_outcomes(w, 0, i, T=T) for i in range(n + 1)]
     serial = [hz.gpu_forward_q4(w, L, xs[i], K, pd, drops[i]) for i in range(n)]
     ws = torch.empty(H.halo_workspace_bytes(s, T, K), dtype=torch.uint8, device=hz.DEV)
     pdd = torch.from_numpy(pd).to(hz.DEV)
