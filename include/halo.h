@@ -161,8 +161,16 @@ int halo_build_group_mask(const float *scores, int32_t T, int32_t G, int32_t k_k
  * group gets y[t] = 0.
  *   x [T][d], Wg/Wu [ffn][d], Wd [n_groups][d][group_size], mask [T][n_groups] uint8,
  *   y [T][d] out (dtype).
- * Accumulation is float32; for bf16 with more than one token the matrix-core path rounds
- * the activation SiLU(gate)*up to bf16 before the down projection.
+ * Accumulation is float32; the tuned bf16 paths round the activation SiLU(gate)*up to bf16 before
+ * the down projection.
+ * Which kernels run (results are the same to the stated tolerance either way; throughput is not):
+ *   bf16, group size 128, n_groups <= 256, one token, d = 5120 or a multiple of 1024 in [2048, 8192]:
+ *       the streaming one-token kernels;
+ *   bf16, group size 128, 2..16 tokens, d a multiple of 128: the few-token kernels (2..4 tokens with
+ *       d in {4096, 5120, 8192} and n_groups <= 256 on the float ALUs, otherwise matrix cores);
+ *   bf16, group size 128, more than 16 tokens, d a multiple of 128: the many-token matrix-core kernels;
+ *   anything else (float32, other group sizes or row lengths): plain wave-per-row kernels, several
+ *       times slower per byte.
  */
 int halo_group_sparse_ffn(const halo_shape *shape, const void *x, int32_t T, const void *Wg,
                           const void *Wu, const void *Wd, const uint8_t *mask, void *y,
@@ -217,8 +225,9 @@ int halo_ffn_forward_static(const halo_shape *shape, const void *x, const void *
  *   - predictor + group mask of the next block from x_pred_next with that block's
  *     predictor weights -> mask_next (and the optional outputs, same meaning as in
  *     halo_build_group_mask; NULL = not produced).
- * For one token (bf16, d in {4096, 5120, 8192}, n_groups <= 256) and for 2..16 tokens (bf16,
- * d a multiple of 128, group size 128, n_groups <= 256) the prediction occupies spare
+ * For one token (bf16, group size 128, n_groups <= 256, d = 5120 or a multiple of 1024 from 2048 to
+ * 8192) and for 2..16 tokens (bf16, d a multiple of 128, group size 128, n_groups <= 256) the
+ * prediction occupies spare
  * workgroups of the FFN's own two launches (first predictor layer beside gate/up, second
  * layer + ranking + mask beside the down projection), so it costs no launch and little or no
  * time on the critical path; for other shapes it is enqueued after the FFN.  Results are

@@ -3,6 +3,7 @@ from __future__ import annotations
 
 import ctypes as C
 import os
+import threading
 from typing import Optional, Sequence
 
 import numpy as np
@@ -11,6 +12,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libhalo.so")
 _lib = None
+_tls = threading.local()      # prepared(): the recorder standing in for the library in this thread, if any
 
 HALO_F32, HALO_BF16 = 0, 1
 
@@ -65,6 +67,9 @@ def load_library():
     """Load libhalo.so (built in-tree by paper_2601_11676_amd.build).  There is no fallback:
     a missing library is an error."""
     global _lib
+    stack = getattr(_tls, "recorders", None)
+    if stack:
+        return stack[-1]
     if _lib is not None:
         return _lib
     if not os.path.exists(_LIB_PATH):
@@ -345,31 +350,42 @@ def halo_mha_forward_ahead(shape: MhaShape, x, Wq, Wk, Wv, Wo, k_cache, v_cache,
     _check("halo_mha_forward_ahead", rc)
 
 
+class _Recorder:
+    """Stands in for the library inside prepared(): notes the one C call a wrapper makes instead of
+    making it."""
+
+    def __init__(self, lib):
+        self._lib = lib
+        self.calls = []
+
+    def __getattr__(self, name):
+        cfn = getattr(self._lib, name)
+
+        def rec(*cargs):
+            self.calls.append((cfn, cargs, name))
+            return 0
+        return rec
+
+
 def prepared(fn, *args, **kwargs):
     """Marshal the arguments of one of the halo_* calls above once and return a zero-argument
     callable that repeats exactly that call (same pointers, same stream).  For launch-bound
-    loops where per-call Python marshalling would dominate; the caller keeps the tensors alive."""
-    lib = load_library()
-    captured = []
-
-    class _Recorder:
-        def __getattr__(self, name):
-            cfn = getattr(lib, name)
-
-            def rec(*cargs):
-                captured.append((cfn, cargs, name))
-                return 0
-            return rec
-
-    global _lib
-    real, _lib = _lib, _Recorder()
+    loops where per-call Python marshalling would dominate; the caller keeps the tensors alive.
+    The recording is local to the calling thread (other threads keep calling the real library)
+    and nests."""
+    rec = _Recorder(load_library())
+    stack = getattr(_tls, "recorders", None)
+    if stack is None:
+        stack = _tls.recorders = []
+    stack.append(rec)
     try:
         fn(*args, **kwargs)
     finally:
-        _lib = real
-    if len(captured) != 1:
+        popped = stack.pop()
+        assert popped is rec
+    if len(rec.calls) != 1:
         raise RuntimeError("prepared() expects a function that makes exactly one library call")
-    cfn, cargs, name = captured[0]
+    cfn, cargs, name = rec.calls[0]
 
     def call():
         rc = cfn(*cargs)

@@ -384,42 +384,47 @@ static hipError_t decode_t1(const bf16_t *x, int G, int gs, const bf16_t *Wg, co
                             const DecodeScratch &ws, const AheadArgs *ah, hipStream_t s)
 {
     constexpr int d = NCH * 512;
-    constexpr int RQ = d / 1024;         // 256 workgroups x RQ row quads cover the d/4 quads
     bf16_t *act = reinterpret_cast<bf16_t *>(ws.act);
     if (!ah) {
         launch_timed("gate_up_t1", gate_up_t1<NCH>, dim3(kGateUpBlocks), dim3(256), s, x, G, gs, Wg, Wu,
                      mask, act);
-        down_t1<RQ><<<dim3(256), dim3(RQ * 128), 0, s>>>(d, G, Wd, mask, act, y);
-        return hipGetLastError();
+    } else {
+        const int n_pred = (ah->r + 3) / 4;
+        launch_timed("gate_up_pred_t1", gate_up_pred_t1<NCH>, dim3(kGateUpBlocks + n_pred), dim3(256), s, x, G,
+                     gs, Wg, Wu, mask, act, (const bf16_t *)ah->x_next, (const bf16_t *)ah->At, ah->r, ah->h,
+                     n_pred);
     }
-    const int n_pred = (ah->r + 3) / 4;
-    launch_timed("gate_up_pred_t1", gate_up_pred_t1<NCH>, dim3(kGateUpBlocks + n_pred), dim3(256), s, x, G,
-                 gs, Wg, Wu, mask, act, (const bf16_t *)ah->x_next, (const bf16_t *)ah->At, ah->r, ah->h,
-                 n_pred);
-    const AheadDev nx = ahead_dev(*ah);
-    down_mask_t1<RQ><<<dim3(257), dim3(RQ * 128), 0, s>>>(d, G, Wd, mask, act, y, nx);
-    return hipGetLastError();
+    return launch_down_t1(Wd, d, G, mask, act, y, s, ah);
+}
+
+// Row lengths of the one-token path: d = 1024 k, k = 2..8, and 5120 (LLaMA-family hidden sizes).
+bool t1_shape_supported(int d)
+{
+    return d == 5120 || (d % 1024 == 0 && d >= 2048 && d <= 8192);
 }
 
 hipError_t launch_down_t1(const bf16_t *Wd, int d, int G, const uint8_t *mask, const bf16_t *act, bf16_t *y,
                           hipStream_t s, const AheadArgs *ahead)
 {
-    if (ahead) {
-        const AheadDev nx = ahead_dev(*ahead);
-        switch (d) {
-        case 4096: down_mask_t1<4><<<dim3(257), dim3(512), 0, s>>>(d, G, Wd, mask, act, y, nx); break;
-        case 5120: down_mask_t1<5><<<dim3(257), dim3(640), 0, s>>>(d, G, Wd, mask, act, y, nx); break;
-        case 8192: down_mask_t1<8><<<dim3(257), dim3(1024), 0, s>>>(d, G, Wd, mask, act, y, nx); break;
-        default: return hipErrorInvalidValue;
-        }
-        return hipGetLastError();
-    }
+    const AheadDev nx = ahead ? ahead_dev(*ahead) : AheadDev{};
+#define HALO_DOWN_CASE(D)                                                                                  \
+    case D:                                                                                                \
+        if (ahead)                                                                                         \
+            down_mask_t1<D / 1024><<<dim3(257), dim3(D / 1024 * 128), 0, s>>>(d, G, Wd, mask, act, y, nx); \
+        else                                                                                               \
+            down_t1<D / 1024><<<dim3(256), dim3(D / 1024 * 128), 0, s>>>(d, G, Wd, mask, act, y);          \
+        break;
     switch (d) {
-    case 4096: down_t1<4><<<dim3(256), dim3(512), 0, s>>>(d, G, Wd, mask, act, y); break;
-    case 5120: down_t1<5><<<dim3(256), dim3(640), 0, s>>>(d, G, Wd, mask, act, y); break;
-    case 8192: down_t1<8><<<dim3(256), dim3(1024), 0, s>>>(d, G, Wd, mask, act, y); break;
+        HALO_DOWN_CASE(2048)
+        HALO_DOWN_CASE(3072)
+        HALO_DOWN_CASE(4096)
+        HALO_DOWN_CASE(5120)
+        HALO_DOWN_CASE(6144)
+        HALO_DOWN_CASE(7168)
+        HALO_DOWN_CASE(8192)
     default: return hipErrorInvalidValue;
     }
+#undef HALO_DOWN_CASE
     return hipGetLastError();
 }
 
@@ -445,12 +450,16 @@ hipError_t launch_ffn_decode(int dtype, const void *x, int T, int d, int G, int 
                                      (const float *)Wd, mask, (float *)y, ws, s);
     const bf16_t *bx = (const bf16_t *)x, *bg = (const bf16_t *)Wg, *bu = (const bf16_t *)Wu,
                  *bd = (const bf16_t *)Wd;
-    if (T == 1 && G <= 256 && gs == 128 && (d == 4096 || d == 5120 || d == 8192)) {
+    if (T == 1 && G <= 256 && gs == 128 && t1_shape_supported(d)) {
         const AheadArgs *ah = (ahead && ahead_fused) ? ahead : nullptr;
         if (ah) *ahead_fused = true;
         switch (d) {
+        case 2048: return decode_t1<4>(bx, G, gs, bg, bu, bd, mask, (bf16_t *)y, ws, ah, s);
+        case 3072: return decode_t1<6>(bx, G, gs, bg, bu, bd, mask, (bf16_t *)y, ws, ah, s);
         case 4096: return decode_t1<8>(bx, G, gs, bg, bu, bd, mask, (bf16_t *)y, ws, ah, s);
         case 5120: return decode_t1<10>(bx, G, gs, bg, bu, bd, mask, (bf16_t *)y, ws, ah, s);
+        case 6144: return decode_t1<12>(bx, G, gs, bg, bu, bd, mask, (bf16_t *)y, ws, ah, s);
+        case 7168: return decode_t1<14>(bx, G, gs, bg, bu, bd, mask, (bf16_t *)y, ws, ah, s);
         default: return decode_t1<16>(bx, G, gs, bg, bu, bd, mask, (bf16_t *)y, ws, ah, s);
         }
     }

@@ -134,3 +134,33 @@ def test_bench_refuses_more_than_one_gpu():
                        text=True, timeout=120)
     assert p.returncode != 0
     assert "single-GPU" in p.stderr and p.stdout.strip() == ""
+
+
+def test_prepared_records_in_its_own_thread_and_nests():
+    # prepared() marshals a call once; while it records, other threads still reach the real library
+    import threading
+    seen = {}
+
+    def inner():
+        return H.halo_build_schedule(4, [0.0, 0.1])
+
+    def outer():
+        seen["nested"] = H.prepared(inner)           # a prepared() inside the recorded function
+        return H.halo_build_schedule(6, [0.0, 0.1, 0.2])
+
+    def other_thread():
+        seen["other"] = H.halo_build_schedule(4, [0.0, 0.1]).tolist()
+
+    def recorded():
+        t = threading.Thread(target=other_thread)
+        t.start()
+        t.join()
+        return outer()
+
+    call = H.prepared(recorded)
+    assert seen["other"] == [0, 0, 1, 1]                 # the real library answered the other thread
+    call()
+    seen["nested"]()
+    assert H.halo_build_schedule(4, [0.0, 0.1]).tolist() == [0, 0, 1, 1]   # and this thread, afterwards
+    with pytest.raises(RuntimeError):
+        H.prepared(lambda: None)

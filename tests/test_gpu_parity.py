@@ -69,7 +69,7 @@ def test_generic_shapes_whole_pass(dtype, T, d, G, r):
     hz.assert_parity(g, c, TOL[dtype], "generic")
 
 
-@pytest.mark.parametrize("d", [4096, 5120, 8192])
+@pytest.mark.parametrize("d", [2048, 3072, 4096, 5120, 6144, 7168, 8192])
 def test_one_token_fast_path_small_group_count(d):
     w = dataclasses.replace(hs.LLAMA7B_DECODE, name="case", d=d, ffn=7 * 128, rank=256, seed=21)
     _say(f"one-token path d={d}")
@@ -223,6 +223,8 @@ def test_separate_entry_points_equal_the_fused_pass():
 
 @pytest.mark.parametrize("T,d,G,r,K", [
     (1, 4096, 20, 256, 10),      # one token: the prediction rides in the one-token kernels
+    (1, 3072, 11, 128, 5),       # one token, another row length of that path
+    (1, 7168, 9, 256, 5),
     (4, 5120, 9, 256, 4),        # float-ALU gate/up for a few tokens + matrix-core down projection
     (2, 8192, 6, 512, 3),
     (8, 8192, 7, 512, 4),        # matrix-core kernels, 70B row length
