@@ -445,6 +445,10 @@ def main():
                          "slow on the host; timing all of them starves the GPU and slows the kernel itself)")
     ap.add_argument("--min-timed", type=int, default=128,
                     help="the eager event pass is repeated until this many launches were timed")
+    ap.add_argument("--chains", type=int, default=1,
+                    help="also time the K steps as this many independent chains of steps on as many streams "
+                         "(each chain strictly sequential; reported beside the headline as `concurrent_chains`, "
+                         "never as `value`)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="instead of the benchmark, run 8 plain device-to-device copies of 256 MiB "
                          "(a kernel of known traffic) for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE")
@@ -524,23 +528,23 @@ def main():
 
     st = torch.cuda.Stream()               # every library call below goes to this stream (default priority)
 
-    def step_serial_q4(s):
+    def step_serial_q4(s, ws=ws, st=st, ys=ys):
         At, Bt, q4 = copies[s % NC]
         H.halo_ffn_forward_q4(shape, xs[s], At, Bt, q4, k_keep, prio_dev, w.n_dev, drops[s], ys[s], ws,
                               mask=masks[s], stream=st)
 
-    def step_ahead_q4(s):
+    def step_ahead_q4(s, ws=ws, st=st, ys=ys):
         q4 = copies[s % NC][2]
         At, Bt = copies[(s + 1) % NC][:2]
         H.halo_ffn_forward_ahead_q4(shape, xs[s], q4, masks[s], ys[s], xs[s + 1], At, Bt, k_keep, prio_dev,
                                     w.n_dev, drops[s + 1], masks[s + 1], ws, stream=st)
 
-    def step_serial(s):
+    def step_serial(s, ws=ws, st=st, ys=ys):
         At, Bt, Wg, Wu, Wd = copies[s % NC]
         H.halo_ffn_forward(shape, xs[s], At, Bt, Wg, Wu, Wd, k_keep, prio_dev, w.n_dev, drops[s],
                            ys[s], ws, mask=masks[s], stream=st)
 
-    def step_ahead(s):
+    def step_ahead(s, ws=ws, st=st, ys=ys):
         # FFN of step s with the mask predicted one step earlier; beside it, in spare workgroups
         # of the same launches, predictor + mask of step s+1 (the paper's Pred || Comp overlap)
         _, _, Wg, Wu, Wd = copies[s % NC]
@@ -579,6 +583,39 @@ def main():
     est_us = {1: 26.0, 4: 60.0, 8: 230.0, 512: 190.0}.get(T, 50.0)
     elapsed, times, reps = timed_graph(torch, st, enqueue, K, est_us, args.replays, use_graph)
     y_timed = ys[W:W + K].clone()
+
+    # ---- optional: the same K steps as several independent chains on as many streams -------
+    chains = None
+    if args.chains > 1 and use_graph and K >= 2 * args.chains:
+        C = args.chains
+        bounds = [W + K * c // C for c in range(C + 1)]
+        streams = [st] + [torch.cuda.Stream() for _ in range(C - 1)]
+        wss = [ws] + [torch.empty_like(ws) for _ in range(C - 1)]
+        ys2 = torch.zeros_like(ys)
+        ccalls = []
+        for c in range(C):
+            ccalls.append([H.prepared(make, s_, ws=wss[c], st=streams[c], ys=ys2) for s_ in range(bounds[c], bounds[c + 1])])
+        if not args.serial:
+            for c in range(1, C):                   # the mask of each chain's first step (chain 0's exists already)
+                At, Bt = copies[bounds[c] % NC][:2]
+                H.halo_predict_scores(shape, xs[bounds[c]], At, Bt, ws_scores, ws, stream=st)
+                H.halo_build_group_mask(ws_scores, k_keep, prio_dev, w.n_dev, drops[bounds[c]], masks[bounds[c]], stream=st)
+        torch.cuda.synchronize()
+
+        def enqueue_chains():
+            for c in range(1, C):
+                streams[c].wait_stream(st)          # fork
+            for c in range(C):
+                for call in ccalls[c]:
+                    call()
+            for c in range(1, C):
+                st.wait_stream(streams[c])          # join
+        c_elapsed, c_times, c_reps = timed_graph(torch, st, enqueue_chains, K, est_us / C, args.replays, True)
+        chains = {"chains": C, "us_per_step": c_elapsed / K * 1e6, "tokens_per_s": K * T / c_elapsed,
+                  "rounds_of_K_steps_per_replay": c_reps,
+                  "same_outputs_as_one_chain": bool(torch.equal(ys2[W:W + K], y_timed)),
+                  "note": "independent chains of steps overlap each other's launch boundaries; a single sequence "
+                          "cannot do this (its steps depend on each other): not the headline"}
 
     # ---- dominant kernel under HIP events (eager passes over the same steps) -------------
     passes = max(1, int(math.ceil(args.min_timed * args.time_every / K)))
@@ -619,6 +656,10 @@ def main():
         "event_pass_us_per_step": t_eager / (K * passes) * 1e6,
         "event_pass_host_us_per_step": t_enq / (K * passes) * 1e6,
     }
+    if chains is not None:
+        chains["weight_GBps"] = ffn_bytes / (chains["us_per_step"] * 1e-6 * K) / 1e9
+        chains["frac_of_hbm_peak"] = chains["weight_GBps"] / HBM_PEAK_GBPS
+        whole["concurrent_chains"] = chains
     if many:
         # many tokens: the dominant kernel is a dense contraction on the matrix cores
         flops = float(n_surv[timed].sum()) * w.group_size * d * 2 * 2      # gate and up, 2 flop per MAC
