@@ -363,7 +363,8 @@ int halo_profile_end(double *total_ms, int64_t *launches, char *kernel_name, int
  * Harness aid (not part of the paper's method): the glue between the blocks of an FFN-only stack,
  * one launch per layer:  h[t] += y[t] (skipped if y is NULL);  x[t] = h[t] / sqrt(mean(h[t]^2) + eps).
  *   h [T][d] float (in/out, the residual stream), y [T][d] (dtype) or NULL, x [T][d] (dtype) out.
- * Errors: HALO_ERR_NULL, HALO_ERR_DTYPE, HALO_ERR_ARG (T < 0, d < 1, eps < 0), HALO_ERR_HIP.
+ * d must be a multiple of 4, at most 8192; rows 16-byte aligned.
+ * Errors: HALO_ERR_NULL, HALO_ERR_DTYPE, HALO_ERR_ARG (T < 0, d outside those limits, eps < 0), HALO_ERR_HIP.
  */
 int halo_stack_residual_norm(float *h, const void *y, void *x, int32_t T, int32_t d, int32_t dtype,
                              float eps, void *stream);
