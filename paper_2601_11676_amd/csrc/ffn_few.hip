@@ -37,19 +37,43 @@ __global__ __launch_bounds__(256) void gate_up_ft(
     // the union of the tokens' surviving groups, built by every wave from the T*G mask bytes
     // (no separate launch, no list in memory between the mask and the first weight load)
     const MaskWords uw = load_union_words<TMAX>(mask, T, G, lane);
-    for (int p = tid; p < T * (d / 8); p += 256) {
-        const int t = p / (d / 8), e = (p - t * (d / 8)) * 8;
-        *reinterpret_cast<u32x4 *>(sx + t * XR + e) = *reinterpret_cast<const u32x4 *>(x + (size_t)t * d + e);
-    }
-    __syncthreads();
     const long long total = (long long)uw.count * gs;
     const int nw = (gridDim.x - ap.n_pred) * 4, w = (blockIdx.x - ap.n_pred) * 4 + wave;
     const int n0 = (int)(total * w / nw), n1 = (int)(total * (w + 1) / nw);
-    if (n0 >= n1) return;                                    // no barrier below
+    const bool busy = n0 < n1;
     // a run is shorter than a group (total / nw <= gs), so it touches at most two groups: their ids
     // and the tokens' mask bits for them are fetched up front
-    const int u_first = n0 / gs, u_last = (n1 - 1) / gs;
-    const int g_first = nth_group(uw, u_first, lane), g_last = nth_group(uw, u_last, lane);
+    const int u_first = busy ? n0 / gs : 0, u_last = busy ? (n1 - 1) / gs : 0;
+    const int g_first = uw.count ? nth_group(uw, u_first, lane) : 0, g_last = uw.count ? nth_group(uw, u_last, lane) : 0;
+    auto row_of = [&](int n) -> size_t {
+        const int u = n / gs;
+        return (size_t)(u == u_first ? g_first : g_last) * gs + (n - u * gs);
+    };
+    // the first neuron's rows are requested before x is staged: the weight stream does not wait for it
+    RowPair<NCH> A, B;
+    if (busy) load_rows<NCH>(A, Wg, Wu, row_of(n0), lane);
+    {
+        // x into LDS, eight 16-byte pieces per thread requested before the first is stored (one memory
+        // round trip per eight pieces, not one per piece)
+        constexpr int kPieces = T * (d / 8);
+        for (int base = tid; base < kPieces; base += 256 * 8) {
+            u32x4 v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int p = base + 256 * j < kPieces ? base + 256 * j : tid;
+                const int t = p / (d / 8), e = (p - t * (d / 8)) * 8;
+                v[j] = *reinterpret_cast<const u32x4 *>(x + (size_t)t * d + e);
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int p = base + 256 * j;
+                const int t = p / (d / 8), e = (p - t * (d / 8)) * 8;
+                if (p < kPieces) *reinterpret_cast<u32x4 *>(sx + t * XR + e) = v[j];
+            }
+        }
+    }
+    __syncthreads();
+    if (!busy) return;                                       // no barrier below
     unsigned keep_first = 0, keep_last = 0;
 #pragma unroll
     for (int t = 0; t < T; ++t) {
@@ -57,10 +81,6 @@ __global__ __launch_bounds__(256) void gate_up_ft(
         keep_first |= (a ? 1u : 0u) << t;
         keep_last |= (b ? 1u : 0u) << t;
     }
-    auto row_of = [&](int n) -> size_t {
-        const int u = n / gs;
-        return (size_t)(u == u_first ? g_first : g_last) * gs + (n - u * gs);
-    };
     const bf16_t *xl = sx + lane * 8;
     auto finish = [&](const RowPair<NCH> &r, int n) {
         float ag[TMAX], au[TMAX];
@@ -90,8 +110,6 @@ __global__ __launch_bounds__(256) void gate_up_ft(
         }
         if (lane < T) act[(size_t)lane * act_stride + n] = f32_to_bf16(mine);
     };
-    RowPair<NCH> A, B;
-    load_rows<NCH>(A, Wg, Wu, row_of(n0), lane);
     int n = n0;
     while (n + 2 < n1) {
         load_rows<NCH>(B, Wg, Wu, row_of(n + 1), lane);
