@@ -181,20 +181,10 @@ __global__ __launch_bounds__(512, 4) void down_q4_t1(int d, int G, const uint32_
         if (wave == 0 && p == 0) y[j] = 0;
         return;
     }
-    // stage the activation (count * 16 pieces of 16 bytes) and build the group list
-    {
-        const u32x4 *asrc = reinterpret_cast<const u32x4 *>(act);
-        u32x4 *adst = reinterpret_cast<u32x4 *>(sh.act);
-        for (int i = tid; i < count * 16; i += 512) adst[i] = asrc[i];
-    }
+    // the group list first, then the first batch of codes: the weight stream does not depend on the
+    // activation, so its first round trip runs beside the activation's
     if (wave == 0) write_group_list(mw, lane, sh.list);
     __syncthreads();
-    for (int i = tid; i < count * 4; i += 512) {
-        u32x4 a[4];
-#pragma unroll
-        for (int k = 0; k < 4; ++k) a[k] = *reinterpret_cast<const u32x4 *>(sh.act + i * 32 + k * 8);
-        sh.asum[i] = 136.0f * sum32(a);
-    }
     float acc = 0.0f;
     const size_t gstride = (size_t)d * 16;                         // words per group
     u32x4 c[kB];
@@ -210,6 +200,24 @@ __global__ __launch_bounds__(512, 4) void down_q4_t1(int d, int G, const uint32_
         }
     };
     load_batch(wave);                                              // every wave, also one with no group
+    // stage the activation (count * 16 pieces of 16 bytes), all of a thread's pieces requested at once
+    {
+        const u32x4 *asrc = reinterpret_cast<const u32x4 *>(act);
+        u32x4 *adst = reinterpret_cast<u32x4 *>(sh.act);
+        u32x4 v[8];                                                // 256 groups * 16 pieces / 512 threads
+#pragma unroll
+        for (int k = 0; k < 8; ++k) v[k] = asrc[tid + 512 * k < count * 16 ? tid + 512 * k : 0];
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            if (tid + 512 * k < count * 16) adst[tid + 512 * k] = v[k];
+    }
+    __syncthreads();
+    for (int i = tid; i < count * 4; i += 512) {
+        u32x4 a[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) a[k] = *reinterpret_cast<const u32x4 *>(sh.act + i * 32 + k * 8);
+        sh.asum[i] = 136.0f * sum32(a);
+    }
     __syncthreads();                                               // asum complete
     for (int u0 = wave; u0 < count; u0 += 8 * kB) {
         if (u0 != wave) load_batch(u0);
