@@ -101,9 +101,10 @@ def timed_graph(torch, st, enqueue, k_steps, est_us_per_step, replays, use_graph
     return float(np.median(times)), times, reps
 
 
-def measured_ceilings(torch, H, st, window_bytes, want_mfma):
+def measured_ceilings(torch, H, st, window_bytes, want_mfma, second_window_bytes=None):
     """The GPU's own read-stream rate (for launches of window_bytes, and for 1 GiB launches) and,
-    if asked, its bf16 matrix-instruction rate."""
+    if asked, its bf16 matrix-instruction rate.  second_window_bytes: also time plain reads in
+    launches of that size (the step's other streaming kernel)."""
     buf = torch.empty(2 << 30, dtype=torch.uint8, device="cuda:0")
     buf.fill_(0x5a)
     sink = torch.zeros(256, dtype=torch.uint8, device="cuda:0")
@@ -112,6 +113,10 @@ def measured_ceilings(torch, H, st, window_bytes, want_mfma):
     win = max(1 << 20, int(window_bytes))
     g, us = H.halo_peak_read_stream(buf, win, 64, sink, stream=st)
     out["read_stream_same_size"] = {"GBps": g, "us_per_launch": us, "bytes_per_launch": win // 16384 * 16384}
+    if second_window_bytes:
+        win2 = max(1 << 20, int(second_window_bytes))
+        g, us = H.halo_peak_read_stream(buf, win2, 64, sink, stream=st)
+        out["read_stream_second_size"] = {"GBps": g, "us_per_launch": us, "bytes_per_launch": win2 // 16384 * 16384}
     g, us = H.halo_peak_read_stream(buf, 1 << 30, 8, sink, stream=st)
     out["read_stream_GBps"] = g
     if want_mfma:
@@ -645,7 +650,8 @@ def main():
     achieved = gate_up_bytes / (kern_ms * 1e-3) / 1e9 if kern_ms > 0 else 0.0
     traffic = read_traffic(kern_name, w.name + ("_q4" if args.q4 else ""))
     many = "_pf" in kern_name
-    ceil = measured_ceilings(torch, H, st, float(union.mean()) * 2 * group_bytes, many)
+    ceil = measured_ceilings(torch, H, st, float(union.mean()) * 2 * group_bytes, many,
+                             None if many else float(union.mean()) * group_bytes)
     whole = {
         "mean_n_surv": float(n_surv.mean()), "mean_union": float(union.mean()),
         "weight_GBps": ffn_bytes / elapsed / 1e9,
@@ -656,6 +662,13 @@ def main():
         "event_pass_us_per_step": t_eager / (K * passes) * 1e6,
         "event_pass_host_us_per_step": t_enq / (K * passes) * 1e6,
     }
+    if "read_stream_second_size" in ceil:
+        # what two plain read-only launches of the step's two weight streams cost back to back: no mask,
+        # no arithmetic, no dependency between them -- the floor of any two-launch form of the step
+        floor_us = ceil["read_stream_same_size"]["us_per_launch"] + ceil["read_stream_second_size"]["us_per_launch"]
+        whole["plain_read_two_launches_us"] = floor_us
+        whole["plain_read_two_launches_frac_of_hbm_peak"] = ffn_bytes / K / (floor_us * 1e-6) / 1e9 / HBM_PEAK_GBPS
+        whole["step_over_plain_read_two_launches"] = elapsed / K * 1e6 / floor_us
     if chains is not None:
         chains["weight_GBps"] = ffn_bytes / (chains["us_per_step"] * 1e-6 * K) / 1e9
         chains["frac_of_hbm_peak"] = chains["weight_GBps"] / HBM_PEAK_GBPS
