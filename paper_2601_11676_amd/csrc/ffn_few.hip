@@ -10,6 +10,8 @@
 // re-shapes every weight tile through LDS and keeps fewer bytes in flight per row; it reached
 // 3.5 TB/s on a 63-group union of the 13B shape and 5.8 TB/s on the 70B shape.)
 // Output: act[t][n] = mask[t][group of n] ? SiLU(gate) * up : 0, bf16, n = position in the union.
+#include <type_traits>
+
 #include "kernels.hpp"
 #include "mask_words.hpp"
 #include "row_stream.hpp"
@@ -34,6 +36,16 @@ __global__ __launch_bounds__(256) void gate_up_ft(
         predictor_row_tokens<d>(ap.x_next, ap.At, ap.h, T, d, ap.r, blockIdx.x * 4 + wave, lane);
         return;
     }
+    // The token rows of x are requested first of all: they depend on nothing, so they travel beside the
+    // mask bytes, and the weight rows requested after them never wait behind a staging round trip.
+    constexpr int kPieces = T * (d / 8), kPer = (kPieces + 255) / 256;
+    u32x4 xp[kPer];
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) {
+        const int p = tid + 256 * j < kPieces ? tid + 256 * j : tid;
+        const int t = p / (d / 8), e = (p - t * (d / 8)) * 8;
+        xp[j] = *reinterpret_cast<const u32x4 *>(x + (size_t)t * d + e);
+    }
     // the union of the tokens' surviving groups, built by every wave from the T*G mask bytes
     // (no separate launch, no list in memory between the mask and the first weight load)
     const MaskWords uw = load_union_words<TMAX>(mask, T, G, lane);
@@ -49,31 +61,6 @@ __global__ __launch_bounds__(256) void gate_up_ft(
         const int u = n / gs;
         return (size_t)(u == u_first ? g_first : g_last) * gs + (n - u * gs);
     };
-    // the first neuron's rows are requested before x is staged: the weight stream does not wait for it
-    RowPair<NCH> A, B;
-    if (busy) load_rows<NCH>(A, Wg, Wu, row_of(n0), lane);
-    {
-        // x into LDS, eight 16-byte pieces per thread requested before the first is stored (one memory
-        // round trip per eight pieces, not one per piece)
-        constexpr int kPieces = T * (d / 8);
-        for (int base = tid; base < kPieces; base += 256 * 8) {
-            u32x4 v[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int p = base + 256 * j < kPieces ? base + 256 * j : tid;
-                const int t = p / (d / 8), e = (p - t * (d / 8)) * 8;
-                v[j] = *reinterpret_cast<const u32x4 *>(x + (size_t)t * d + e);
-            }
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int p = base + 256 * j;
-                const int t = p / (d / 8), e = (p - t * (d / 8)) * 8;
-                if (p < kPieces) *reinterpret_cast<u32x4 *>(sx + t * XR + e) = v[j];
-            }
-        }
-    }
-    __syncthreads();
-    if (!busy) return;                                       // no barrier below
     unsigned keep_first = 0, keep_last = 0;
 #pragma unroll
     for (int t = 0; t < T; ++t) {
@@ -81,25 +68,57 @@ __global__ __launch_bounds__(256) void gate_up_ft(
         keep_first |= (a ? 1u : 0u) << t;
         keep_last |= (b ? 1u : 0u) << t;
     }
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) {
+        const int p = tid + 256 * j;
+        const int t = p / (d / 8), e = (p - t * (d / 8)) * 8;
+        if (p < kPieces) *reinterpret_cast<u32x4 *>(sx + t * XR + e) = xp[j];
+    }
+    // the first two neurons' rows are on their way while the workgroup meets at the barrier
+    RowPair<NCH> A, B;
+    if (busy) load_rows<NCH>(A, Wg, Wu, row_of(n0), lane);
+    if (n0 + 1 < n1) load_rows<NCH>(B, Wg, Wu, row_of(n0 + 1), lane);
+    __syncthreads();
+    if (!busy) return;                                       // no barrier below
     const bf16_t *xl = sx + lane * 8;
-    auto finish = [&](const RowPair<NCH> &r, int n) {
+    // Reduces neuron n from the registers of r.  With `reload`, chunk k of row `next` is requested
+    // into r as soon as the tokens have used chunk k of row n: the wave keeps close to two rows of
+    // loads outstanding all the time, instead of one while it multiplies.
+    auto finish = [&](RowPair<NCH> &r, int n, auto reload, size_t next) {
         float ag[TMAX], au[TMAX];
 #pragma unroll
         for (int t = 0; t < TMAX; ++t) ag[t] = au[t] = 0.0f;
+        const u32x4 *pg = reinterpret_cast<const u32x4 *>(Wg + next * d) + lane;
+        const u32x4 *pu = reinterpret_cast<const u32x4 *>(Wu + next * d) + lane;
+        // the tokens' pieces of chunk k + 1 are read from LDS while chunk k is multiplied
+        u32x4 xv[2][T];
+#pragma unroll
+        for (int t = 0; t < T; ++t) xv[0][t] = *reinterpret_cast<const u32x4 *>(xl + t * XR);
 #pragma unroll
         for (int k = 0; k < NCH; ++k) {
+            if (k + 1 < NCH) {
+#pragma unroll
+                for (int t = 0; t < T; ++t)
+                    xv[(k + 1) & 1][t] = *reinterpret_cast<const u32x4 *>(xl + t * XR + (k + 1) * 512);
+                __builtin_amdgcn_sched_barrier(0);          // the reads go out before the multiply-adds
+            }
 #pragma unroll
             for (int t = 0; t < T; ++t) {
-                const u32x4 xv = *reinterpret_cast<const u32x4 *>(xl + t * XR + k * 512);
-                ag[t] = dot2_bf16(r.g[k].x, xv.x, ag[t]);
-                au[t] = dot2_bf16(r.u[k].x, xv.x, au[t]);
-                ag[t] = dot2_bf16(r.g[k].y, xv.y, ag[t]);
-                au[t] = dot2_bf16(r.u[k].y, xv.y, au[t]);
-                ag[t] = dot2_bf16(r.g[k].z, xv.z, ag[t]);
-                au[t] = dot2_bf16(r.u[k].z, xv.z, au[t]);
-                ag[t] = dot2_bf16(r.g[k].w, xv.w, ag[t]);
-                au[t] = dot2_bf16(r.u[k].w, xv.w, au[t]);
+                const u32x4 &xk = xv[k & 1][t];
+                ag[t] = dot2_bf16(r.g[k].x, xk.x, ag[t]);
+                au[t] = dot2_bf16(r.u[k].x, xk.x, au[t]);
+                ag[t] = dot2_bf16(r.g[k].y, xk.y, ag[t]);
+                au[t] = dot2_bf16(r.u[k].y, xk.y, au[t]);
+                ag[t] = dot2_bf16(r.g[k].z, xk.z, ag[t]);
+                au[t] = dot2_bf16(r.u[k].z, xk.z, au[t]);
+                ag[t] = dot2_bf16(r.g[k].w, xk.w, ag[t]);
+                au[t] = dot2_bf16(r.u[k].w, xk.w, au[t]);
             }
+            if constexpr (decltype(reload)::value) {
+                r.g[k] = __builtin_nontemporal_load(pg + k * kWave);
+                r.u[k] = __builtin_nontemporal_load(pu + k * kWave);
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
         const unsigned keep = (n / gs == u_first) ? keep_first : keep_last;
         float mine = 0.0f;
@@ -111,19 +130,21 @@ __global__ __launch_bounds__(256) void gate_up_ft(
         if (lane < T) act[(size_t)lane * act_stride + n] = f32_to_bf16(mine);
     };
     int n = n0;
-    while (n + 2 < n1) {
-        load_rows<NCH>(B, Wg, Wu, row_of(n + 1), lane);
-        finish(A, n);
-        load_rows<NCH>(A, Wg, Wu, row_of(n + 2), lane);
-        finish(B, n + 1);
+    while (n + 3 < n1) {
+        finish(A, n, std::true_type{}, row_of(n + 2));
+        finish(B, n + 1, std::true_type{}, row_of(n + 3));
         n += 2;
     }
-    if (n + 1 < n1) {
-        load_rows<NCH>(B, Wg, Wu, row_of(n + 1), lane);
-        finish(A, n);
-        finish(B, n + 1);
+    // one, two or three neurons left; A holds n, B holds n + 1
+    if (n + 2 < n1) {
+        finish(A, n, std::true_type{}, row_of(n + 2));
+        finish(B, n + 1, std::false_type{}, 0);
+        finish(A, n + 2, std::false_type{}, 0);
+    } else if (n + 1 < n1) {
+        finish(A, n, std::false_type{}, 0);
+        finish(B, n + 1, std::false_type{}, 0);
     } else {
-        finish(A, n);
+        finish(A, n, std::false_type{}, 0);
     }
 }
 

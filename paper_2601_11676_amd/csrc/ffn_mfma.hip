@@ -166,26 +166,34 @@ __global__ __launch_bounds__(256) void gate_up_mt(
     }
 }
 
-// grid: d/16 workgroups of 256 threads; group size 128.  A workgroup owns 16 output rows; a
-// group's 16 x 128 tile of Wd is 4 KiB of consecutive bytes, fetched by four instructions.
-constexpr int kDownGroups = 3;              // groups in flight per wave (LDS: three workgroups per compute unit)
+// grid: d / (4 LD) workgroups of 256 threads; group size 128.  A workgroup owns 4 LD consecutive output
+// rows; a group's tile of Wd for them is LD KiB of consecutive bytes, fetched by LD instructions.
+// LD is chosen by the host so that the grid is one workgroup per compute unit where the row count
+// allows it (d a multiple of 1024: LD = d / 1024, 256 workgroups).  A compute unit draws from memory at
+// a bounded rate whatever the number of workgroups on it, so a grid of 320 workgroups (d = 5120 in
+// 16-row tiles) runs as long as the compute units that hold two of them: 19 us against 12.
 constexpr int kTileRow = 128 + 8;           // padded LDS row, elements
 
+template <int LD>
 struct DownMtShared {
-    __attribute__((aligned(16))) bf16_t sT[4][kDownGroups][16 * kTileRow];
+    static constexpr int kTiles = (LD + 3) / 4;             // 16-row tiles of the matrix instruction
+    static constexpr int kGroups = LD <= 4 ? 3 : 2;         // groups per batch of registers
+    __attribute__((aligned(16))) bf16_t sT[4][kGroups][16 * kTiles * kTileRow];
     int s_list[256];
 };
 
 // UNION_IN_KERNEL: as in gate_up_mt.  The first n_mask workgroups do not project: each computes the
 // next block's scores, ranking and mask for one token (n_mask = 0: nobody does).
-template <bool UNION_IN_KERNEL>
+template <bool UNION_IN_KERNEL, int LD>
 __global__ __launch_bounds__(256) void down_mt(
     int T, int d, int G, const bf16_t *__restrict__ Wd, const uint8_t *__restrict__ mask,
     const int32_t *__restrict__ ulist_mem, const int32_t *__restrict__ meta,
     const bf16_t *__restrict__ act, int act_stride, bf16_t *__restrict__ y, int n_mask, AheadDev nx)
 {
     constexpr int gs = 128;
-    constexpr size_t kLds = sizeof(DownMtShared) > sizeof(MaskShared) ? sizeof(DownMtShared) : sizeof(MaskShared);
+    using Shared = DownMtShared<LD>;
+    constexpr int kTiles = Shared::kTiles, kGroups = Shared::kGroups;
+    constexpr size_t kLds = sizeof(Shared) > sizeof(MaskShared) ? sizeof(Shared) : sizeof(MaskShared);
     __shared__ __attribute__((aligned(16))) unsigned char lds[kLds];
     if ((int)blockIdx.x < n_mask) {
         // paper Sec. III-B.3, one layer ahead: second predictor layer, ranking and mask of the next
@@ -201,15 +209,15 @@ __global__ __launch_bounds__(256) void down_mt(
                                              nx.n_surv ? nx.n_surv + t : nullptr);
         return;
     }
-    DownMtShared &sh = *reinterpret_cast<DownMtShared *>(lds);
+    Shared &sh = *reinterpret_cast<Shared *>(lds);
     auto &sT = sh.sT;
     auto &s_list = sh.s_list;
-    // the waves' partial sums meet in LDS at the end; each wave parks its own in the first KiB of its
-    // own tile region, which it has finished reading by then
-    auto red = [&](int w) { return reinterpret_cast<float(*)[4]>(&sT[w][0][0]); };
+    // the waves' partial sums meet in LDS at the end; each wave parks its own at the start of its own
+    // tile region, which it has finished reading by then
+    auto red = [&](int w) { return reinterpret_cast<float(*)[64][4]>(&sT[w][0][0]); };
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int i = lane & 15, q = lane >> 4;
-    const int j0 = (blockIdx.x - n_mask) * 16;
+    const int j0 = (blockIdx.x - n_mask) * (4 * LD);
     int n_u;
     const int32_t *ulist = ulist_mem;
     if (UNION_IN_KERNEL) {
@@ -226,47 +234,113 @@ __global__ __launch_bounds__(256) void down_mt(
     const bf16_t *arow = act + (size_t)tok * act_stride + q * 8;
     const size_t gstride = (size_t)d * gs;
     const bf16_t *wtile = Wd + (size_t)j0 * gs + lane * 8;          // + n*512 elements for instruction n
-    f32x4_t c = {0.f, 0.f, 0.f, 0.f};
-    for (int ub = u0; ub < u1; ub += kDownGroups) {
-        u32x4 r[kDownGroups][4], b[kDownGroups][4];
+    f32x4_t c[kTiles];
 #pragma unroll
-        for (int k = 0; k < kDownGroups; ++k) {
-            const int u = ub + k < u1 ? ub + k : ub;                 // past the end: in-range duplicate
+    for (int tt = 0; tt < kTiles; ++tt) c[tt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    // Two batches of registers: the next batch of groups is requested before the current one is
+    // re-shaped and multiplied, so the wave always has loads outstanding (with one batch, every
+    // batch was a memory round trip of its own).
+    struct Batch {
+        u32x4 r[kGroups][LD], b[kGroups][4];
+    };
+    auto request = [&](Batch &t, int ub) {
+#pragma unroll
+        for (int k = 0; k < kGroups; ++k) {
+            const int u = ub + k < u1 ? ub + k : u1 - 1;             // past the end: in-range duplicate
             const bf16_t *pw = wtile + ulist[u] * gstride;
             const bf16_t *pa = arow + (size_t)u * gs;
 #pragma unroll
-            for (int n = 0; n < 4; ++n) {
-                r[k][n] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(pw + n * 512));
-                b[k][n] = *reinterpret_cast<const u32x4 *>(pa + n * 32);
-            }
+            for (int n = 0; n < LD; ++n)
+                t.r[k][n] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(pw + n * 512));
+#pragma unroll
+            for (int s = 0; s < 4; ++s) t.b[k][s] = *reinterpret_cast<const u32x4 *>(pa + s * 32);
         }
+    };
+    auto consume = [&](const Batch &t, int ub) {
         // instruction n, lane l holds row 4n + l/16, elements (l%16)*8..+7
 #pragma unroll
-        for (int k = 0; k < kDownGroups; ++k)
+        for (int k = 0; k < kGroups; ++k)
 #pragma unroll
-            for (int n = 0; n < 4; ++n)
-                *reinterpret_cast<u32x4 *>(&sT[wave][k][(4 * n + q) * kTileRow + i * 8]) = r[k][n];
+            for (int n = 0; n < LD; ++n)
+                *reinterpret_cast<u32x4 *>(&sT[wave][k][(4 * n + q) * kTileRow + i * 8]) = t.r[k][n];
+        // rows of the last tile past 4 LD hold whatever LDS held: a row of the product depends on its
+        // own row of the operand only, and those rows are never stored
 #pragma unroll
-        for (int k = 0; k < kDownGroups; ++k) {
+        for (int k = 0; k < kGroups; ++k) {
             if (ub + k < u1) {
 #pragma unroll
-                for (int s = 0; s < 4; ++s) {
-                    const u32x4 a = *reinterpret_cast<const u32x4 *>(&sT[wave][k][i * kTileRow + s * 32 + q * 8]);
-                    c = mfma16(a, b[k][s], c);
-                }
+                for (int tt = 0; tt < kTiles; ++tt)
+#pragma unroll
+                    for (int s = 0; s < 4; ++s) {
+                        const u32x4 a = *reinterpret_cast<const u32x4 *>(
+                            &sT[wave][k][(16 * tt + i) * kTileRow + s * 32 + q * 8]);
+                        c[tt] = mfma16(a, t.b[k][s], c[tt]);
+                    }
             }
+        }
+    };
+    if (u0 < u1) {
+        Batch P, Q;
+        request(P, u0);
+        int ub = u0;
+        while (ub + 2 * kGroups < u1) {
+            request(Q, ub + kGroups);
+            consume(P, ub);
+            request(P, ub + 2 * kGroups);
+            consume(Q, ub + kGroups);
+            ub += 2 * kGroups;
+        }
+        if (ub + kGroups < u1) {
+            request(Q, ub + kGroups);
+            consume(P, ub);
+            consume(Q, ub + kGroups);
+        } else {
+            consume(P, ub);
         }
     }
 #pragma unroll
-    for (int rr = 0; rr < 4; ++rr) red(wave)[lane][rr] = c[rr];
+    for (int tt = 0; tt < kTiles; ++tt)
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) red(wave)[tt][lane][rr] = c[tt][rr];
     __syncthreads();
     if (wave == 0 && i < T) {
 #pragma unroll
-        for (int rr = 0; rr < 4; ++rr) {
-            const float v = ((red(0)[lane][rr] + red(1)[lane][rr]) + red(2)[lane][rr]) + red(3)[lane][rr];
-            y[(size_t)i * d + j0 + 4 * q + rr] = f32_to_bf16(v);
-        }
+        for (int tt = 0; tt < kTiles; ++tt)
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) {
+                const int row = 16 * tt + 4 * q + rr;
+                if (row < 4 * LD) {
+                    const float v = ((red(0)[tt][lane][rr] + red(1)[tt][lane][rr]) + red(2)[tt][lane][rr]) +
+                                    red(3)[tt][lane][rr];
+                    y[(size_t)i * d + j0 + row] = f32_to_bf16(v);
+                }
+            }
     }
+}
+
+// LD = d / 1024 where d is a multiple of 1024 up to 8192 (one workgroup per compute unit), else 16-row
+// workgroups
+template <bool UNION_IN_KERNEL>
+static void launch_down_mt(int T, int d, int G, const bf16_t *Wd, const uint8_t *mask, const int32_t *ulist,
+                           const int32_t *meta, const bf16_t *act, int act_stride, bf16_t *y, int n_mask,
+                           const AheadDev &nx, hipStream_t s)
+{
+#define HALO_DOWN_MT_CASE(LD_)                                                                                    \
+    case LD_:                                                                                                     \
+        down_mt<UNION_IN_KERNEL, LD_><<<dim3(d / (4 * LD_) + n_mask), dim3(256), 0, s>>>(T, d, G, Wd, mask, ulist, \
+                                                                                         meta, act, act_stride, y, \
+                                                                                         n_mask, nx);              \
+        break;
+    switch ((d % 1024 == 0 && d >= 2048 && d <= 8192) ? d / 1024 : 4) {
+        HALO_DOWN_MT_CASE(2)
+        HALO_DOWN_MT_CASE(3)
+        HALO_DOWN_MT_CASE(4)
+        HALO_DOWN_MT_CASE(5)
+        HALO_DOWN_MT_CASE(6)
+        HALO_DOWN_MT_CASE(7)
+        HALO_DOWN_MT_CASE(8)
+    }
+#undef HALO_DOWN_MT_CASE
 }
 
 // ---------------------------------------------------------------------------
@@ -302,8 +376,7 @@ hipError_t launch_ffn_mfma(const bf16_t *x, int T, int d, int G, int gs, const b
             launch_timed("gate_up_mt", gate_up_mt<true>, dim3(256 + ap.n_pred), dim3(256), s, x, T, d, G, gs, Wg, Wu,
                          mask, (const int32_t *)nullptr, (const int32_t *)nullptr, act, ffn, ap);
         }
-        down_mt<true><<<dim3(d / 16 + n_mask), dim3(256), 0, s>>>(T, d, G, Wd, mask, nullptr, nullptr, act, ffn, y,
-                                                                 n_mask, nx);
+        launch_down_mt<true>(T, d, G, Wd, mask, nullptr, nullptr, act, ffn, y, n_mask, nx, s);
         return hipGetLastError();
     }
     hipError_t e = launch_union(mask, T, G, ws.ulist, ws.meta, s);
@@ -311,7 +384,7 @@ hipError_t launch_ffn_mfma(const bf16_t *x, int T, int d, int G, int gs, const b
     // one workgroup per compute unit (the kernel holds two row batches in registers, one wave per SIMD)
     launch_timed("gate_up_mt", gate_up_mt<false>, dim3(256), dim3(256), s, x, T, d, G, gs, Wg, Wu, mask,
                  (const int32_t *)ws.ulist, (const int32_t *)ws.meta, act, ffn, AheadPredDev{nullptr, nullptr, nullptr, 0, 0});
-    down_mt<false><<<dim3(d / 16), dim3(256), 0, s>>>(T, d, G, Wd, mask, ws.ulist, ws.meta, act, ffn, y, 0, AheadDev{});
+    launch_down_mt<false>(T, d, G, Wd, mask, ws.ulist, ws.meta, act, ffn, y, 0, AheadDev{}, s);
     return hipGetLastError();
 }
 
