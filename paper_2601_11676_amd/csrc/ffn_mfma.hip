@@ -9,7 +9,8 @@
 //             most one), cut into tiles of <= 16 rows, and sweeps the rows in 512-element
 //             chunks; the token fragments are read from x directly (it is small and stays
 //             in cache).  act[t][n] = mask ? SiLU(gate)*up : 0 is stored in bf16.
-//   down    : Wd is group-blocked, Wd[g][j][m]; a workgroup owns 16 output rows j, its four
+//   down    : Wd is group-blocked, Wd[g][j][m]; a workgroup owns a run of consecutive output
+//             rows j (one workgroup per compute unit where the row count allows), its four
 //             waves split the union's groups, partial tiles are added through LDS and y is
 //             written directly.
 // Operand layout of the instruction (wave64): A lane l holds row l%16, elements

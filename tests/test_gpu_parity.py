@@ -281,6 +281,10 @@ def test_one_step_ahead_overlap_equals_the_serial_pass(T, d, G, r, K):
     (16, 4096, 6, 256),
     (5, 4096, 20, 256),      # union larger than any token's set; ragged neuron runs per wave
     (3, 640, 3, 40),         # d a multiple of 128 but not of 256
+    (3, 2048, 6, 128),       # the other row counts per workgroup of the down projection (d / 256 rows):
+    (6, 3072, 5, 128),       #   8, 12, 24 and 28 rows, the last 16-row tile of a workgroup partly empty
+    (2, 6144, 5, 256),
+    (9, 7168, 4, 256),
 ])
 def test_few_tokens_matrix_core_path(T, d, G, r):
     w = dataclasses.replace(hs.LLAMA13B_STACK, name="case", d=d, ffn=G * 128, rank=r, T=T, layers=1, seed=17)
