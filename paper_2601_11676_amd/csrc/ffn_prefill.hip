@@ -102,16 +102,27 @@ constexpr int kRingBytes = kRingStages * kRingStageBytes;        // 144 KiB (the
 // and only for the lanes of `lanes` (all 64 lanes of the wave are active around it).  The branch is
 // inside the statement on purpose: a branch the compiler can see splits the step into basic blocks,
 // and it then shuffles the accumulators between register files at the joins.
+// STREAM: the bytes are used once by this die (weight rows): the load carries the non-temporal hint, so
+// that they do not push the rows that are used again (x, act) out of the die's L2.
+template <bool STREAM = false>
 __device__ __forceinline__ void load_to_lds16_if(bool cond, unsigned long long lanes, const void *base,
                                                  uint32_t offset, uint32_t lds_addr)
 {
     unsigned long long saved_exec;       // the lanes active around the statement come back afterwards
-    asm volatile("s_cmp_eq_u32 %4, 0\n\ts_cbranch_scc1 1f\n\ts_mov_b32 m0, %3\n\ts_mov_b64 %0, exec\n\t"
-                 "s_mov_b64 exec, %5\n\tglobal_load_lds_dwordx4 %1, %2\n\ts_mov_b64 exec, %0\n1:"
-                 : "=&s"(saved_exec)
-                 : "v"(offset), "s"(base), "s"(lds_addr), "s"(__builtin_amdgcn_readfirstlane((uint32_t)cond)),
-                   "s"(lanes)
-                 : "memory", "scc");        // m0 is reserved: the compiler sets it anew before each use of its own
+    if (STREAM)
+        asm volatile("s_cmp_eq_u32 %4, 0\n\ts_cbranch_scc1 1f\n\ts_mov_b32 m0, %3\n\ts_mov_b64 %0, exec\n\t"
+                     "s_mov_b64 exec, %5\n\tglobal_load_lds_dwordx4 %1, %2 nt\n\ts_mov_b64 exec, %0\n1:"
+                     : "=&s"(saved_exec)
+                     : "v"(offset), "s"(base), "s"(lds_addr), "s"(__builtin_amdgcn_readfirstlane((uint32_t)cond)),
+                       "s"(lanes)
+                     : "memory", "scc");    // m0 is reserved: the compiler sets it anew before each use of its own
+    else
+        asm volatile("s_cmp_eq_u32 %4, 0\n\ts_cbranch_scc1 1f\n\ts_mov_b32 m0, %3\n\ts_mov_b64 %0, exec\n\t"
+                     "s_mov_b64 exec, %5\n\tglobal_load_lds_dwordx4 %1, %2\n\ts_mov_b64 exec, %0\n1:"
+                     : "=&s"(saved_exec)
+                     : "v"(offset), "s"(base), "s"(lds_addr), "s"(__builtin_amdgcn_readfirstlane((uint32_t)cond)),
+                       "s"(lanes)
+                     : "memory", "scc");
 }
 
 // wait until at most N (deep) or none of the wave's loads are outstanding
@@ -299,7 +310,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     for (int i = 0; i < kRingStages && i < ns; ++i) {
         const uint32_t dst = wdst0 + i * kRingStageBytes;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) load_to_lds16_if(true, ~0ull, j < 2 ? src_g : src_u, off_w[j], dst + j * 4096);
+        for (int j = 0; j < 4; ++j) load_to_lds16_if<true>(true, ~0ull, j < 2 ? src_g : src_u, off_w[j], dst + j * 4096);
 #pragma unroll
         for (int j = 0; j < 8; ++j) load_to_lds16_if(true, lanes_x[j], src_x, off_x[j], dst + 16384 + j * 4096);
         advance(true);
@@ -336,7 +347,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 #pragma unroll
         for (int c = 0; c < 8; ++c) {
             load_to_lds16_if(go, lanes_x[c], src_x, off_x[c], dst + 16384 + c * 4096);
-            if (c < 4) load_to_lds16_if(go, ~0ull, c < 2 ? src_g : src_u, off_w[c], dst + c * 4096);
+            if (c < 4) load_to_lds16_if<true>(go, ~0ull, c < 2 ? src_g : src_u, off_w[c], dst + c * 4096);
 #pragma unroll
             for (int tt = 0; tt < 8; ++tt) mfma16_inplace(acc[c][tt], cur.a[c], cur.b[tt]);
             __builtin_amdgcn_sched_barrier(0);
@@ -566,16 +577,30 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int ks = wave & 1, nh = wave >> 1;
     const int i16 = lane & 15, q = lane >> 4;
-    // work items: (token tile, group range) pairs, and within a pair the output tiles; a die gets a
-    // consecutive run of them, i.e. workgroups that share their act rows
+    // work items: (token tile, group range, output tile) triples; a die gets a consecutive run of them
     const int n_ot = d / 128;
     const int n_items = n_ot * ((T + kRingTok - 1) / kRingTok) * splits;
     const int per_die = (n_items + 7) >> 3;
     const int die = blockIdx.x & 7, dslot = blockIdx.x >> 3;
     const int item = die * per_die + dslot;
     if (dslot >= per_die || item >= n_items) return;             // uniform for the workgroup
-    const int pair = item / n_ot, j0 = (item - pair * n_ot) * 128;
-    const int ttile = pair / splits, split = pair - ttile * splits;
+    // Two numberings.  With one or two token tiles the items of a die are the token tiles of consecutive
+    // output tiles of one range: a tile of Wd is fetched from memory by the first and found in the die's
+    // L2 by the second, and the act rows of both token tiles fit beside it.  With more token tiles the
+    // items of a die share one token tile's act rows instead (they would not all fit).
+    const int n_tt = (T + kRingTok - 1) / kRingTok;
+    int ttile, split, j0;
+    if (n_tt <= 2) {
+        ttile = item % n_tt;
+        const int rest = item / n_tt;
+        split = rest / n_ot;
+        j0 = (rest - split * n_ot) * 128;
+    } else {
+        const int pair = item / n_ot;
+        j0 = (item - pair * n_ot) * 128;
+        ttile = pair / splits;
+        split = pair - ttile * splits;
+    }
     const int t0 = ttile * kRingTok;
     const int g_lo = (int)((long long)split * G / splits), g_hi = (int)((long long)(split + 1) * G / splits);
     const int ng = g_hi - g_lo;                                  // >= 1, <= kDownMaxGroups
@@ -583,14 +608,23 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 
     // rows of act for this thread's token and every group of the range
     {
+        // eight groups' slots and counts are requested together: one memory round trip per eight groups,
+        // not two per group
         const int t = t0 + tid;
-        for (int gi = 0; gi < ng; ++gi) {
-            int row = 0;                                         // a token past the end: any row, never stored
-            if (t < T) {
-                row = slot[(size_t)t * G + g_lo + gi];
-                row = row < 0 ? tok_cnt[g_lo + gi] : row;        // the group's row of zeros
+        const int32_t *my = slot + (size_t)(t < T ? t : T - 1) * G + g_lo;
+        for (int gi0 = 0; gi0 < ng; gi0 += 8) {
+            int row[8], zero_row[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int gi = gi0 + k < ng ? gi0 + k : ng - 1;
+                row[k] = my[gi];
+                zero_row[k] = tok_cnt[g_lo + gi];                // the group's row of zeros
             }
-            s_row[gi * kRingTok + tid] = (int16_t)row;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                // (a token past the end: any row, never stored)
+                if (gi0 + k < ng) s_row[(gi0 + k) * kRingTok + tid] = (int16_t)(t < T ? (row[k] < 0 ? zero_row[k] : row[k]) : 0);
+            }
         }
     }
     __syncthreads();
