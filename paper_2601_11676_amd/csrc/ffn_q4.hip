@@ -140,14 +140,15 @@ __global__ __launch_bounds__(kQ4GateUpThreads, (NH == 2 ? 4 : 2)) void gate_up_q
 
 // down: four lanes share an output row j (16 bytes each = 32 of the group's 128 neurons), a
 // wave covers 16 consecutive rows = 1 KiB of a group's codes, the workgroup's eight waves take
-// every eighth surviving group and meet in LDS.  The activation vector is staged in LDS once
-// per workgroup together with its 32-element sums (for the constant offset of the codes).
-constexpr int kDownQ4Batch = 8;
+// every eighth surviving group and meet in LDS.  A lane fetches what it multiplies straight from
+// memory -- its code piece, the row's scale and the 64 bytes of the activation that face the piece
+// (the same 64 bytes for the 16 rows of a wave: one request per wave instruction) -- for four groups
+// at a time, and takes the sum of those 32 activations itself (for the constant offset of the
+// codes): nothing is staged through LDS, so no barrier stands between the mask and the first codes
+// (with the activation staged once per workgroup the kernel spent 3.2 of its 5.3 us getting ready).
+constexpr int kDownQ4Batch = 4;
 
 struct DownQ4Shared {
-    int list[256];
-    __attribute__((aligned(16))) bf16_t act[256 * 128];
-    float asum[256 * 4];
     float part[8][16];
 };
 
@@ -177,60 +178,26 @@ __global__ __launch_bounds__(512, 4) void down_q4_t1(int d, int G, const uint32_
     const int count = mw.count;
     const int j = vblock * 16 + (lane >> 2);                       // output row of this lane
     const int p = lane & 3;                                        // which 32 neurons of the group
-    if (count == 0) {                                              // uniform
-        if (wave == 0 && p == 0) y[j] = 0;
-        return;
-    }
-    // the group list first, then the first batch of codes: the weight stream does not depend on the
-    // activation, so its first round trip runs beside the activation's
-    if (wave == 0) write_group_list(mw, lane, sh.list);
-    __syncthreads();
     float acc = 0.0f;
     const size_t gstride = (size_t)d * 16;                         // words per group
-    u32x4 c[kB];
-    uint16_t s[kB];
-    auto load_batch = [&](int u0) {
+    // this wave's groups: positions wave, wave + 8, ... of the surviving list (at most 32 of them)
+    for (int u0 = wave; u0 < count; u0 += 8 * kB) {
+        u32x4 c[kB], a[kB][4];
+        uint16_t s[kB];
 #pragma unroll
         for (int q = 0; q < kB; ++q) {
-            const int u = u0 + 8 * q < count ? u0 + 8 * q : count - 1;   // past the end: an in-range duplicate
-            const int g = sh.list[u];
+            const int u = u0 + 8 * q < count ? u0 + 8 * q : u0;      // past the end: an in-range duplicate
+            const int g = nth_group(mw, u, lane);
             c[q] = __builtin_nontemporal_load(
                 reinterpret_cast<const u32x4 *>(Dq + g * gstride + (size_t)j * 16) + p);
             s[q] = Ds[(size_t)g * d + j];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) a[q][k] = *reinterpret_cast<const u32x4 *>(act + u * gs + p * 32 + k * 8);
         }
-    };
-    load_batch(wave);                                              // every wave, also one with no group
-    // stage the activation (count * 16 pieces of 16 bytes), all of a thread's pieces requested at once
-    {
-        const u32x4 *asrc = reinterpret_cast<const u32x4 *>(act);
-        u32x4 *adst = reinterpret_cast<u32x4 *>(sh.act);
-        u32x4 v[8];                                                // 256 groups * 16 pieces / 512 threads
-#pragma unroll
-        for (int k = 0; k < 8; ++k) v[k] = asrc[tid + 512 * k < count * 16 ? tid + 512 * k : 0];
-#pragma unroll
-        for (int k = 0; k < 8; ++k)
-            if (tid + 512 * k < count * 16) adst[tid + 512 * k] = v[k];
-    }
-    __syncthreads();
-    for (int i = tid; i < count * 4; i += 512) {
-        u32x4 a[4];
-#pragma unroll
-        for (int k = 0; k < 4; ++k) a[k] = *reinterpret_cast<const u32x4 *>(sh.act + i * 32 + k * 8);
-        sh.asum[i] = 136.0f * sum32(a);
-    }
-    __syncthreads();                                               // asum complete
-    for (int u0 = wave; u0 < count; u0 += 8 * kB) {
-        if (u0 != wave) load_batch(u0);
 #pragma unroll
         for (int q = 0; q < kB; ++q) {
-            const int u = u0 + 8 * q;
-            if (u < count) {
-                u32x4 a[4];
-#pragma unroll
-                for (int k = 0; k < 4; ++k)
-                    a[k] = *reinterpret_cast<const u32x4 *>(sh.act + u * gs + p * 32 + k * 8);
-                acc = __builtin_fmaf(bf16_bits_to_float(s[q]), q4_dot32(c[q], a) - sh.asum[u * 4 + p], acc);
-            }
+            if (u0 + 8 * q < count)
+                acc = __builtin_fmaf(bf16_bits_to_float(s[q]), q4_dot32(c[q], a[q]) - 136.0f * sum32(a[q]), acc);
         }
     }
     // the four lanes of a row, then the eight waves
