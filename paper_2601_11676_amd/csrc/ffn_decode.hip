@@ -325,8 +325,10 @@ __device__ __forceinline__ void down_t1_body(DownShared<RQ> &sh, int d, int G,
     if (half == 0 && (lane & 15) == 0) y[row] = f32_to_bf16(v + sh.half[rq][lane]);
 }
 
+// (Both down kernels are held to 128 vector registers: two workgroups must fit a compute unit, or the
+// extra workgroup of the `_mask` form waits for a free one and the launch takes half as long again.)
 template <int RQ>
-__global__ __launch_bounds__(RQ * 128) void down_t1(int d, int G, const bf16_t *__restrict__ Wd,
+__global__ __launch_bounds__(RQ * 128, 4) void down_t1(int d, int G, const bf16_t *__restrict__ Wd,
                                                     const uint8_t *__restrict__ mask,
                                                     const bf16_t *__restrict__ act,
                                                     bf16_t *__restrict__ y)
@@ -338,7 +340,7 @@ __global__ __launch_bounds__(RQ * 128) void down_t1(int d, int G, const bf16_t *
 // The down projection, with the second predictor layer + ranking + mask of the NEXT block in
 // workgroup 0 (it is the longest dependent chain, so it is dispatched first).
 template <int RQ>
-__global__ __launch_bounds__(RQ * 128) void down_mask_t1(int d, int G, const bf16_t *__restrict__ Wd,
+__global__ __launch_bounds__(RQ * 128, 4) void down_mask_t1(int d, int G, const bf16_t *__restrict__ Wd,
                                                          const uint8_t *__restrict__ mask,
                                                          const bf16_t *__restrict__ act,
                                                          bf16_t *__restrict__ y, AheadDev nx)
