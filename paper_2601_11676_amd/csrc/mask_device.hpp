@@ -4,24 +4,33 @@
 // decode kernels that carry the next block's prediction in spare workgroups (ffn_decode.hip).
 //
 // Ranking by counting: rank(g) = number of groups that come before g under (score
-// descending, lower index first on equal scores, NaN after every number).  The G x G
-// comparisons are spread over all threads of the workgroup (each thread takes one group and
-// one slice of the opponents; slices are summed with LDS atomics), so the step costs a few
-// hundred cycles instead of a serial sweep.  Survivor positions come from wave ballots.
+// descending, lower index first on equal scores, NaN after every number).  Every score is
+// turned once into a 64-bit key whose unsigned order IS that order (rank_key below), so a
+// comparison is one instruction; the G x G comparisons are spread over all threads of the
+// workgroup (each thread takes one group and one slice of the opponents; slices are summed
+// with LDS atomics).  With float comparisons and the NaN / tie cases decided pair by pair the
+// sweep was 650 instructions per wave, a third of the workgroup's whole time.  Survivor
+// positions come from wave ballots.
 #pragma once
 #include "common.hpp"
 
 namespace halo {
 
-__device__ __forceinline__ bool ranks_before(float sh, int h, float sg, int g)
+// Key of (score s, group g), g < 1024: h comes before g in the ranking exactly when
+// rank_key(s_h, h) > rank_key(s_g, g).  High 32 bits: the float's bits made monotonic (sign flipped
+// for positives, all bits flipped for negatives), -0 taken as +0 so that the two tie, NaN taken as 0,
+// below -inf.  Low 10 bits: 1023 - g, so that among equal scores the lower index is the larger key.
+__device__ __forceinline__ unsigned long long rank_key(float s, int g)
 {
-    const bool nh = sh != sh, ng = sg != sg;
-    if (nh | ng) return (nh & ng) ? (h < g) : ng;
-    return (sh > sg) | ((sh == sg) & (h < g));
+    uint32_t u = __float_as_uint(s);
+    if ((u << 1) == 0u) u = 0u;                                   // -0 -> +0
+    uint32_t k = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+    if (s != s) k = 0u;                                           // NaN after every number
+    return ((unsigned long long)k << 10) | (unsigned)(1023 - g);
 }
 
 struct MaskShared {
-    __attribute__((aligned(16))) float score[1024];
+    __attribute__((aligned(16))) unsigned long long key[1024];
     int pos[1024];
     unsigned long long bits[16];
     int8_t prio[1024];
@@ -40,7 +49,7 @@ __device__ __forceinline__ void mask_scores_block(
     uint8_t *__restrict__ mask, int32_t *__restrict__ surv_idx, int32_t *__restrict__ n_surv)
 {
     constexpr int kWaves = NT / kWave;
-    constexpr int GB = NT >= 1024 ? 8 : 16;     // groups whose rows a wave fetches before reducing any
+    constexpr int GB = 8;                       // slots whose rows a wave fetches before reducing any
     const int wave = tid >> 6, lane = tid & 63;
     // Everything the head needs from memory -- schedule, loss outcomes, h, the first batch of
     // Bt rows -- is requested in one straight line (clamped addresses and selects, no branches),
@@ -51,25 +60,34 @@ __device__ __forceinline__ void mask_scores_block(
     const int8_t pv = *pp;
     const uint8_t dv = *dp;
     const bool fast = FUSED && r <= 512;        // one 8-element piece of h and of every row per lane
-    const bool on = lane * 8 < r;
+    // Rows of up to 256 elements occupy half a wave, so a wave takes two at a time: lanes 0..31 row
+    // 2s, lanes 32..63 row 2s + 1.  In the fixed order the partial sums of lanes 32..63 are then +0,
+    // and the butterfly's first step (distance 32) adds exactly that: here it is `+ 0.0f` in every
+    // lane, and the steps at distances 16..1 stay inside a half.  Same bits, half the instructions.
+    const bool paired = FUSED && r <= 256;
+    const int pl = paired ? (lane & 31) : lane, half = paired ? (lane >> 5) : 0;
+    const bool on = pl * 8 < r;
     float hx[8];
     Piece8<WT> w[GB];
-    auto load_batch = [&](int g0) {
+    // batch starting at slot s0 of this wave: slot s = s0 + kWaves * b holds row s (or rows 2s, 2s+1)
+    auto row_of_slot = [&](int s) { return paired ? 2 * s + half : s; };
+    auto load_batch = [&](int s0) {
 #pragma unroll
         for (int b = 0; b < GB; ++b) {
-            const int g = g0 + kWaves * b;
+            const int g = row_of_slot(s0 + kWaves * b);
             const bool ok = on && g < G;
-            w[b].load(Bt + (size_t)(g < G ? g : G - 1) * r + (on ? lane * 8 : 0));
+            w[b].load(Bt + (size_t)(g < G ? g : G - 1) * r + (on ? pl * 8 : 0));
             if (!ok) w[b].zero();
         }
     };
+    const int n_slots = paired ? (G + 1) / 2 : G;
     if (fast) {
-        load8(h + (on ? lane * 8 : 0), hx);
+        load8(h + (on ? pl * 8 : 0), hx);
         if (!on) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) hx[e] = 0.0f;
         }
-        load_batch(wave < G ? wave : 0);        // a wave beyond G loads (and later discards) batch 0
+        load_batch(wave < n_slots ? wave : 0);  // a wave beyond the last slot loads (and later discards) batch 0
     }
     if (tid < K) sh.prio[tid] = pv;
     for (int p = tid + NT; p < K; p += NT) sh.prio[p] = prio_dev[p];
@@ -77,27 +95,36 @@ __device__ __forceinline__ void mask_scores_block(
     for (int g = tid; g < 1024; g += NT) sh.pos[g] = 0;
     if (FUSED) {
         if (fast) {
-            for (int g0 = wave; g0 < G; g0 += kWaves * GB) {
-                if (g0 != wave) load_batch(g0);
+            for (int s0 = wave; s0 < n_slots; s0 += kWaves * GB) {
+                if (s0 != wave) load_batch(s0);
                 float p[GB];
 #pragma unroll
                 for (int b = 0; b < GB; ++b) {
                     p[b] = 0.0f;
-                    float wf[8];
-                    w[b].get(wf);
+                    if (s0 + kWaves * b < n_slots) {            // uniform: slots past the end cost nothing
+                        float wf[8];
+                        w[b].get(wf);
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) p[b] = __builtin_fmaf(hx[e], wf[e], p[b]);
+                        for (int e = 0; e < 8; ++e) p[b] = __builtin_fmaf(hx[e], wf[e], p[b]);
+                    }
                 }
                 // the butterflies advance together, distance by distance
 #define HALO_STEP(OFF)                                           \
-    _Pragma("unroll") for (int b = 0; b < GB; ++b) p[b] = xor_add<OFF>(p[b]);
-                HALO_STEP(32) HALO_STEP(16) HALO_STEP(8) HALO_STEP(4) HALO_STEP(2) HALO_STEP(1)
+    _Pragma("unroll") for (int b = 0; b < GB; ++b)               \
+        if (s0 + kWaves * b < n_slots) p[b] = xor_add<OFF>(p[b]);
+                if (paired) {
+#pragma unroll
+                    for (int b = 0; b < GB; ++b) p[b] = p[b] + 0.0f;
+                } else {
+                    HALO_STEP(32)
+                }
+                HALO_STEP(16) HALO_STEP(8) HALO_STEP(4) HALO_STEP(2) HALO_STEP(1)
 #undef HALO_STEP
 #pragma unroll
                 for (int b = 0; b < GB; ++b) {
-                    const int g = g0 + kWaves * b;
-                    if (g < G && lane == 0) {
-                        sh.score[g] = p[b];
+                    const int g = row_of_slot(s0 + kWaves * b);
+                    if (g < G && pl == 0) {
+                        sh.key[g] = rank_key(p[b], g);
                         scores[g] = p[b];
                     }
                 }
@@ -106,37 +133,42 @@ __device__ __forceinline__ void mask_scores_block(
             for (int g = wave; g < G; g += kWaves) {
                 const float v = dot_order64(h, Bt + (size_t)g * r, r, lane);
                 if (lane == 0) {
-                    sh.score[g] = v;
+                    sh.key[g] = rank_key(v, g);
                     scores[g] = v;
                 }
             }
         }
     } else {
-        for (int g = tid; g < G; g += NT) sh.score[g] = scores[g];
+        for (int g = tid; g < G; g += NT) sh.key[g] = rank_key(scores[g], g);
     }
-    // pad to a multiple of four with NaN: a NaN at an index >= G never ranks before anything
-    const int G4 = (G + 3) & ~3;
-    if (tid < G4 - G) sh.score[G + tid] = __uint_as_float(0x7fc00000u);
+    // pad to an even count with key 0, which comes before nothing
+    const int G2 = (G + 1) & ~1;
+    if (tid < G2 - G) sh.key[G + tid] = 0ull;
     __syncthreads();
 
-    // rank by counting; thread (g, part) sweeps opponents' float4 pieces q = part, part+P, ...
-    const float4 *s4 = reinterpret_cast<const float4 *>(sh.score);
-    const int n4 = G4 / 4;
+    // rank by counting; thread (g, part) sweeps the opponents' keys in pairs q = part, part+P, ...
+    const ulonglong2 *k2 = reinterpret_cast<const ulonglong2 *>(sh.key);
+    const int n2 = G2 / 2;
     int P = NT / G;                     // slices per group (>= 1 when G <= NT)
     if (P < 1) P = 1;
-    if (P > n4) P = n4;
+    if (P > n2) P = n2;
     for (int base = 0; base < G * P; base += NT) {
         const int idx = base + tid;
         if (idx < G * P) {
             const int g = idx % G, part = idx / G;
-            const float sg = sh.score[g];
+            const unsigned long long kg = sh.key[g];
             int cnt = 0;
-            for (int q = part; q < n4; q += P) {
-                const float4 v = s4[q];
-                cnt += ranks_before(v.x, 4 * q, sg, g) ? 1 : 0;
-                cnt += ranks_before(v.y, 4 * q + 1, sg, g) ? 1 : 0;
-                cnt += ranks_before(v.z, 4 * q + 2, sg, g) ? 1 : 0;
-                cnt += ranks_before(v.w, 4 * q + 3, sg, g) ? 1 : 0;
+            for (int q = part; q < n2; q += 4 * P) {            // four pairs requested before any is compared
+                ulonglong2 v[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) v[k] = k2[q + k * P < n2 ? q + k * P : q];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    if (q + k * P < n2) {
+                        cnt += v[k].x > kg ? 1 : 0;
+                        cnt += v[k].y > kg ? 1 : 0;
+                    }
+                }
             }
             if (cnt) atomicAdd(&sh.pos[g], cnt);
         }
