@@ -100,7 +100,9 @@ __device__ __forceinline__ float dpp_add(float v)
 // v + (v of lane ^ OFF) for every lane, OFF in {32, 16, 8, 4, 2, 1}: one step of the butterfly the
 // predictor's summation order is made of.  Each distance uses the cheapest exchange gfx950 has for
 // exactly that pairing: the half-wave and row swaps (the sum of the two swapped copies is the sum
-// of the pair in both lanes), a swizzle within 32 lanes, the quad permutations of the DPP path.
+// of the pair in both lanes), then the DPP path only (a rotation by 8 within a row, a half-row mirror
+// followed by a reversed quad, the quad permutations): nothing goes through the LDS crossbar, whose
+// round trip a chain of dependent steps would pay every time.
 template <int OFF>
 __device__ __forceinline__ float xor_add(float v)
 {
@@ -113,8 +115,12 @@ __device__ __forceinline__ float xor_add(float v)
         const unsigned u = __builtin_bit_cast(unsigned, v);
         const auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
         return __builtin_bit_cast(float, (unsigned)r[0]) + __builtin_bit_cast(float, (unsigned)r[1]);
-    } else if constexpr (OFF == 8 || OFF == 4) {
-        const int o = __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, v), (OFF << 10) | 0x1f);
+    } else if constexpr (OFF == 8) {
+        return dpp_add<0x128>(v);           // row_ror:8 -- in a row of 16 lanes, lane i reads lane i ^ 8
+    } else if constexpr (OFF == 4) {
+        // lane i ^ 4 = (lane i ^ 7) ^ 3: row_half_mirror, then quad_perm [3,2,1,0] folded into the add
+        const int m = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xf, 0xf, true);
+        const int o = __builtin_amdgcn_update_dpp(0, m, 0x1B, 0xf, 0xf, true);
         return v + __builtin_bit_cast(float, o);
     } else if constexpr (OFF == 2) {
         return dpp_add<0x4E>(v);            // quad_perm [2,3,0,1]

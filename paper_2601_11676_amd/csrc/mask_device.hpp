@@ -82,12 +82,14 @@ __device__ __forceinline__ void mask_scores_block(
     };
     const int n_slots = paired ? (G + 1) / 2 : G;
     if (fast) {
+        // rows first, h last: the lanes outside h are cleared once h has arrived, and a wait for h placed
+        // in front of the row requests would make two memory round trips of one
+        load_batch(wave < n_slots ? wave : 0);  // a wave beyond the last slot loads (and later discards) batch 0
         load8(h + (on ? pl * 8 : 0), hx);
         if (!on) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) hx[e] = 0.0f;
         }
-        load_batch(wave < n_slots ? wave : 0);  // a wave beyond the last slot loads (and later discards) batch 0
     }
     if (tid < K) sh.prio[tid] = pv;
     for (int p = tid + NT; p < K; p += NT) sh.prio[p] = prio_dev[p];
@@ -110,8 +112,7 @@ __device__ __forceinline__ void mask_scores_block(
                 }
                 // the butterflies advance together, distance by distance
 #define HALO_STEP(OFF)                                           \
-    _Pragma("unroll") for (int b = 0; b < GB; ++b)               \
-        if (s0 + kWaves * b < n_slots) p[b] = xor_add<OFF>(p[b]);
+    _Pragma("unroll") for (int b = 0; b < GB; ++b) p[b] = xor_add<OFF>(p[b]);
                 if (paired) {
 #pragma unroll
                     for (int b = 0; b < GB; ++b) p[b] = p[b] + 0.0f;
