@@ -225,6 +225,8 @@ def test_separate_entry_points_equal_the_fused_pass():
     (1, 4096, 20, 256, 10),      # one token: the prediction rides in the one-token kernels
     (1, 3072, 11, 128, 5),       # one token, another row length of that path
     (1, 7168, 9, 256, 5),
+    (1, 8192, 7, 512, 4),        # a predictor of rank 512 beside the one-token kernels
+    (1, 2048, 3, 256, 1),        # a single surviving group: fewer neurons than waves
     (4, 5120, 9, 256, 4),        # float-ALU gate/up for a few tokens + matrix-core down projection
     (2, 8192, 6, 512, 3),
     (8, 8192, 7, 512, 4),        # matrix-core kernels, 70B row length
