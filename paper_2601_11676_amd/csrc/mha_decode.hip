@@ -298,24 +298,32 @@ __global__ __launch_bounds__(256) void attn_partial(const float *__restrict__ q,
 }
 
 // grid = H workgroups of 128 threads: o_u = sum_c e^{m_c - M} o_c / sum_c e^{m_c - M} l_c.
-// The chunk statistics are fetched by one thread per chunk and the value sums in batches of
-// independent loads, so the kernel pays two memory latencies, not two per chunk.
+// Thread tid owns dimension tid of the head and chunk tid's statistics.  Everything the first 32 chunks
+// need -- the thread's chunk maximum and sum, and its 32 value sums -- is requested before anything is
+// waited for, so a cache of up to 4096 positions costs one memory round trip (with the maxima, the
+// sums and the values fetched in turn, in batches of eight, it was six).
 constexpr int kMaxChunks = 1024;     // 131072 cached positions
 
 template <typename OT>
 __global__ __launch_bounds__(128) void attn_combine(const float *__restrict__ part, const uint8_t *__restrict__ mask,
                                                     int H, int chunks, OT *__restrict__ act)
 {
-    constexpr int dh = kHeadDim, kBatch = 8;
+    constexpr int dh = kHeadDim, kBatch = 32;
     __shared__ float s_w[kMaxChunks];
     __shared__ float s_red[2][2];
     const int u = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const MaskWords mw = load_mask_words(mask, H, lane);
     if (u >= mw.count) return;
     const float *p = part + (size_t)u * chunks * kPartStride;
+    // the first batch of value sums and this thread's chunk statistics, all in flight together
+    float v[kBatch];
+#pragma unroll
+    for (int i = 0; i < kBatch; ++i) v[i] = p[(size_t)(i < chunks ? i : chunks - 1) * kPartStride + 2 + tid];
+    const int c_own = tid < chunks ? tid : chunks - 1;
+    const float m_own = p[(size_t)c_own * kPartStride], l_own = p[(size_t)c_own * kPartStride + 1];
     // pass 1: maximum of the chunk maxima
-    float m_loc = -INFINITY;
-    for (int c = tid; c < chunks; c += 128) m_loc = fmaxf(m_loc, p[(size_t)c * kPartStride]);
+    float m_loc = tid < chunks ? m_own : -INFINITY;
+    for (int c = tid + 128; c < chunks; c += 128) m_loc = fmaxf(m_loc, p[(size_t)c * kPartStride]);
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) m_loc = fmaxf(m_loc, __shfl_xor(m_loc, off, kWave));
     if (lane == 0) s_red[0][wave] = m_loc;
@@ -323,7 +331,12 @@ __global__ __launch_bounds__(128) void attn_combine(const float *__restrict__ pa
     const float M = fmaxf(s_red[0][0], s_red[0][1]);
     // pass 2: chunk weights and the denominator
     float l_loc = 0.0f;
-    for (int c = tid; c < chunks; c += 128) {
+    if (tid < chunks) {
+        const float w = __expf(m_own - M);
+        s_w[tid] = w;
+        l_loc = w * l_own;
+    }
+    for (int c = tid + 128; c < chunks; c += 128) {
         const float w = __expf(p[(size_t)c * kPartStride] - M);
         s_w[c] = w;
         l_loc = __builtin_fmaf(w, p[(size_t)c * kPartStride + 1], l_loc);
@@ -333,13 +346,12 @@ __global__ __launch_bounds__(128) void attn_combine(const float *__restrict__ pa
     __syncthreads();
     const float L = s_red[1][0] + s_red[1][1];
     float o = 0.0f;
-    for (int c0 = 0; c0 < chunks; c0 += kBatch) {
-        float v[kBatch];
 #pragma unroll
-        for (int i = 0; i < kBatch; ++i) {
-            const int c = c0 + i < chunks ? c0 + i : chunks - 1;
-            v[i] = p[(size_t)c * kPartStride + 2 + tid];
-        }
+    for (int i = 0; i < kBatch; ++i)
+        if (i < chunks) o = __builtin_fmaf(s_w[i], v[i], o);
+    for (int c0 = kBatch; c0 < chunks; c0 += kBatch) {
+#pragma unroll
+        for (int i = 0; i < kBatch; ++i) v[i] = p[(size_t)(c0 + i < chunks ? c0 + i : chunks - 1) * kPartStride + 2 + tid];
 #pragma unroll
         for (int i = 0; i < kBatch; ++i)
             if (c0 + i < chunks) o = __builtin_fmaf(s_w[c0 + i], v[i], o);

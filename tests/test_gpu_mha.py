@@ -87,6 +87,8 @@ def _check_step(L, x, kc, vc, pos, K, pd, drop):
     (4096, 9, 128, 129),
     (5120, 5, 300, 512),
     (8192, 4, 77, 128),
+    (4096, 4, 4500, 4608),   # 36 chunks: more than one batch of value sums in the merge
+    (4096, 2, 17000, 17024), # 133 chunks: more chunks than threads in the merge
 ])
 def test_mha_decode_step_whole_pass(d, Hh, ctx, max_len):
     w = dataclasses.replace(hs.LLAMA7B_MHA_DECODE, name="case", d=d, n_heads=Hh, rank=64, ctx=ctx,
