@@ -68,11 +68,20 @@ __global__ __launch_bounds__(kQ4GateUpThreads, (NH == 2 ? 4 : 2)) void gate_up_q
     const bf16_t *__restrict__ x, int G, const uint32_t *__restrict__ Gq, const bf16_t *__restrict__ Gs,
     const uint32_t *__restrict__ Uq, const bf16_t *__restrict__ Us, const uint8_t *__restrict__ mask,
     bf16_t *__restrict__ act, const bf16_t *__restrict__ x_next, const bf16_t *__restrict__ At_next, int r,
-    float *__restrict__ h_next, int n_pred)
+    float *__restrict__ h_next, int n_pred, int pred_rows)
 {
     constexpr int d = NH * 2048, gs = 128, NB = NH == 2 ? 3 : 2, WPB = kQ4GateUpThreads / 64;
     constexpr int kWords = d / 8, kBlocks = d / kQ4Block;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    // pred_rows > 0 (then n_pred == 0): the predictor's rows are dealt evenly, pred_rows of them to the last
+    // waves of every workgroup, row vblock + 256 k to wave 7 - k.  A row of At is as many bytes as two
+    // neurons' codes, and a workgroup of predictor rows alone carried three quarters more bytes than its
+    // neighbours' share of the codes: the compute units that held one finished 2 us after the others.
+    if (pred_rows > 0 && wave >= WPB - pred_rows) {
+        const int j = blockIdx.x + kQ4GateUpBlocks * (WPB - 1 - wave);
+        const float p = dot_order64_fixed<d>(x_next, At_next + (size_t)j * d, lane);
+        if (lane == 0) h_next[j] = p > 0.0f ? p : 0.0f;
+    }
     if ((int)blockIdx.x < n_pred) {
         // the first predictor layer of the NEXT block rides along (paper Sec. III-B.3, Pred beside
         // Load/Comp, one layer ahead): one row of At per wave, h_next = ReLU(x_next A)
@@ -89,7 +98,18 @@ __global__ __launch_bounds__(kQ4GateUpThreads, (NH == 2 ? 4 : 2)) void gate_up_q
     // touches at most two groups: the group ids are looked up twice, not once per neuron
     constexpr int nw = kQ4GateUpBlocks * WPB;
     const int total = mw.count * gs, w = (blockIdx.x - n_pred) * WPB + wave;
-    const int n0 = (int)((unsigned)total * (unsigned)w / nw), n1 = (int)((unsigned)total * (unsigned)(w + 1) / nw);
+    int n0 = (int)((unsigned)total * (unsigned)w / nw), n1 = (int)((unsigned)total * (unsigned)(w + 1) / nw);
+    const unsigned units = (unsigned)total + 2u * (unsigned)(pred_rows * kQ4GateUpBlocks);   // a row of At = two neurons
+    if (pred_rows > 0 && units >= 2u * nw) {
+        // runs cut by weight: a wave that has just done a predictor row gets two neurons fewer
+        auto cut = [&](int ww) {
+            const int v = ww / WPB, k = ww % WPB;
+            const int rows_before = v * pred_rows + (k > WPB - pred_rows ? k - (WPB - pred_rows) : 0);
+            return (int)(units * (unsigned)ww / nw) - 2 * rows_before;
+        };
+        n0 = cut(w);
+        n1 = cut(w + 1);
+    }
     if (n0 >= n1) return;
     const int u_first = n0 / gs, u_last = (n1 - 1) / gs;
     const int g_first = nth_group(mw, u_first, lane), g_last = nth_group(mw, u_last, lane);
@@ -348,16 +368,18 @@ hipError_t launch_ffn_q4(int dtype, const void *x, int T, int d, int G, int gs, 
         bf16_t *act = reinterpret_cast<bf16_t *>(ws.act);
         const AheadArgs *ah = (ahead && ahead_fused) ? ahead : nullptr;
         if (ah) *ahead_fused = true;
-        const int n_pred = ah ? (ah->r + 7) / 8 : 0;
+        // predictors of 256 or 512 rows: one or two rows in every gate/up workgroup; else workgroups of their own
+        const int pred_rows = (ah && (ah->r == kQ4GateUpBlocks || ah->r == 2 * kQ4GateUpBlocks)) ? ah->r / kQ4GateUpBlocks : 0;
+        const int n_pred = (ah && pred_rows == 0) ? (ah->r + 7) / 8 : 0;
         const bf16_t *xn = ah ? (const bf16_t *)ah->x_next : nullptr, *an = ah ? (const bf16_t *)ah->At : nullptr;
         float *hn = ah ? ah->h : nullptr;
         const int r = ah ? ah->r : 0;
         if (d == 4096)
             launch_timed("gate_up_q4_t1", gate_up_q4_t1<2>, dim3(kQ4GateUpBlocks + n_pred), dim3(kQ4GateUpThreads), s, bx, G, w.gate_codes,
-                         w.gate_scales, w.up_codes, w.up_scales, mask, act, xn, an, r, hn, n_pred);
+                         w.gate_scales, w.up_codes, w.up_scales, mask, act, xn, an, r, hn, n_pred, pred_rows);
         else
             launch_timed("gate_up_q4_t1", gate_up_q4_t1<4>, dim3(kQ4GateUpBlocks + n_pred), dim3(kQ4GateUpThreads), s, bx, G, w.gate_codes,
-                         w.gate_scales, w.up_codes, w.up_scales, mask, act, xn, an, r, hn, n_pred);
+                         w.gate_scales, w.up_codes, w.up_scales, mask, act, xn, an, r, hn, n_pred, pred_rows);
         AheadDev nx{};
         if (ah) nx = ahead_dev(*ah);
         down_q4_t1<<<dim3(d / 16 + (ah ? 1 : 0)), dim3(512), 0, s>>>(d, G, w.down_codes, w.down_scales, mask, act,

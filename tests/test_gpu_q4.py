@@ -133,14 +133,20 @@ def test_q4_ffn_entry_point_with_handmade_masks_and_errors():
     torch.cuda.synchronize()
 
 
-@pytest.mark.parametrize("d,T", [(4096, 1), (8192, 1), (512, 3), (5120, 4), (8192, 8), (384, 3)])
-def test_q4_one_step_ahead_overlap_equals_the_serial_pass(d, T):
+@pytest.mark.parametrize("d,T,r,G,K", [
+    (4096, 1, 256, 20, 10), (8192, 1, 256, 20, 10), (512, 3, 256, 20, 10), (5120, 4, 256, 20, 10),
+    (8192, 8, 256, 20, 10), (384, 3, 256, 20, 10),
+    (4096, 1, 256, 86, 43),      # enough surviving neurons for the runs to be cut by weight around the predictor rows
+    (4096, 1, 512, 86, 60),      # two predictor rows per gate/up workgroup
+    (4096, 1, 128, 20, 10),      # a predictor size that is not dealt evenly: workgroups of its own
+])
+def test_q4_one_step_ahead_overlap_equals_the_serial_pass(d, T, r, G, K):
     # predictor + mask of step s+1 beside (or, for shapes without spare workgroups, after) the FFN of step s
-    w = dataclasses.replace(hs.LLAMA7B_DECODE, name="case", d=d, ffn=20 * 128, T=T, seed=9)
-    _say(f"halo_ffn_forward_ahead_q4 vs halo_ffn_forward_q4 d={d} T={T}")
+    w = dataclasses.replace(hs.LLAMA7B_DECODE, name="case", d=d, ffn=G * 128, rank=r, T=T, seed=9)
+    _say(f"halo_ffn_forward_ahead_q4 vs halo_ffn_forward_q4 d={d} T={T} r={r} G={G} K={K}")
     s = hz.shape_of(w)
     L = hz.Q4Layer(w)
-    G, K, n = w.n_groups, 10, 5
+    n = 5
     pd = H.halo_build_schedule(K, w.device_plr())
     xs = [hs.hidden_states(w, i, hz.DEV) for i in range(n + 1)]
     drops = [hs.drop_outcomes(w, 0, i, T=T) for i in range(n + 1)]
