@@ -205,6 +205,57 @@ __device__ __forceinline__ void predictor_row_tokens(const bf16_t *__restrict__ 
     }
 }
 
+// The same rows (same order, same bits) with the row of At held in registers and the pieces of x for TB
+// tokens requested together: one memory round trip per TB tokens, where the loop above pays one per token.
+// (3 * TB * D / 512 + D / 128 registers: for rows of up to 5120 elements and four tokens.)
+template <int D, int TB>
+__device__ __forceinline__ void predictor_row_tokens_batched(const bf16_t *__restrict__ x, const bf16_t *__restrict__ At,
+                                                             float *__restrict__ h, int T, int r, int j, int lane)
+{
+    static_assert(D % 512 == 0, "whole 16-byte pieces for all 64 lanes");
+    if (j >= r) return;
+    constexpr int NC = D / 512;
+    u32x4 wv[NC];
+#pragma unroll
+    for (int k = 0; k < NC; ++k)
+        wv[k] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(At + (size_t)j * D + (k * kWave + lane) * 8));
+    for (int t0 = 0; t0 < T; t0 += TB) {
+        u32x4 xv[TB][NC];
+#pragma unroll
+        for (int b = 0; b < TB; ++b) {
+            const int t = t0 + b < T ? t0 + b : T - 1;
+#pragma unroll
+            for (int k = 0; k < NC; ++k)
+                xv[b][k] = *reinterpret_cast<const u32x4 *>(x + (size_t)t * D + (k * kWave + lane) * 8);
+        }
+#pragma unroll
+        for (int b = 0; b < TB; ++b) {
+            float p = 0.0f;
+#pragma unroll
+            for (int k = 0; k < NC; ++k) {
+                float xa[8], wa[8];
+                unpack8(xv[b][k], xa);
+                unpack8(wv[k], wa);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) p = __builtin_fmaf(xa[e], wa[e], p);
+            }
+            p = wave_sum(p);
+            if (t0 + b < T && lane == 0) h[(size_t)(t0 + b) * r + j] = p > 0.0f ? p : 0.0f;
+        }
+    }
+}
+
+// 16 bytes per lane from base + offset[lane] straight into LDS, at lds_addr + 16 * lane (no registers in
+// between; counted by vmcnt like any load).  All 64 lanes; lds_addr is the same for the whole wave.
+// The compiler does not see this load: wait for it with wait_all_loads() before reading the bytes.
+__device__ __forceinline__ void load_to_lds16_all(const void *base, uint32_t offset, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(offset), "s"(base),
+                 "s"(__builtin_amdgcn_readfirstlane(lds_addr))
+                 : "memory");               // m0 is reserved: the compiler sets it anew before each use of its own
+}
+__device__ __forceinline__ void wait_all_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
 // Wave-wide sum through the DPP cross-lane paths (no LDS traffic); result is uniform.
 // Used where the summation order is free (FFN dot products), not by the predictor.
 __device__ __forceinline__ float wave_sum_fast(float v)

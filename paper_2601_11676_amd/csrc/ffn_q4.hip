@@ -356,7 +356,7 @@ static hipError_t q4_generic(const XT *x, int T, int d, int G, int gs, const Q4W
 bool q4_shape_supported(int d, int gs) { return gs == kQ4Block && d % kQ4Block == 0; }
 
 hipError_t launch_ffn_q4(int dtype, const void *x, int T, int d, int G, int gs, const Q4Weights &w,
-                         const uint8_t *mask, void *y, const DecodeScratch &ws, hipStream_t s,
+                         const uint8_t *mask, void *y, const DecodeScratch &ws, hipStream_t s, int rank,
                          const AheadArgs *ahead, bool *ahead_fused)
 {
     if (ahead_fused) *ahead_fused = false;
@@ -387,7 +387,7 @@ hipError_t launch_ffn_q4(int dtype, const void *x, int T, int d, int G, int gs, 
         return hipGetLastError();
     }
     if (q4_mfma_path_supported(T, d, G, gs))
-        return launch_ffn_q4_mfma(bx, T, d, G, w, mask, by, ws, s, ahead, ahead_fused);
+        return launch_ffn_q4_mfma(bx, T, d, G, w, mask, by, ws, s, rank, ahead, ahead_fused);
     return q4_generic<bf16_t>(bx, T, d, G, gs, w, mask, by, ws, s);
 }
 

@@ -9,7 +9,9 @@
 // free as long as A and B agree.  So lane (i, q) = (l%16, l/16) takes the 16 bytes = 32 codes
 // 32q .. 32q+31 of a quantisation block of row i in one load, and step s of the block's four steps
 // multiplies elements 32q + 8s .. +7 of every lane group: one load per block and lane, 64
-// consecutive bytes per row, no LDS on the weight side.  A code becomes the bf16 value 128 + c with
+// consecutive bytes per row, no LDS on the weight side.  (The gate/up kernel fetches the same bytes
+// whole cache lines at a time, two blocks of eight rows per instruction, and gets to this layout with
+// lane-crossing moves: see CodeBatch.)  A code becomes the bf16 value 128 + c with
 // one and-or per pair; the block's result t = sum (128 + c) x meets the scale and the offset in float:
 //     acc += s * (t - 136 * sum x)         since  s * sum (c - 8) x = s * (sum (128 + c) x - 136 sum x).
 // The token side (x, or the activations) is staged in LDS with coalesced loads and read from there in
@@ -23,6 +25,22 @@ namespace halo {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+// From the loaded layout (a: tile rows r, b: rows 8 + r; lanes with bit 3 clear hold the pair's first
+// block, lanes with bit 3 set its second) to the operand layout (lane = 16q + row): c0 = first block, c1 =
+// second block of the pair.  Row i < 8 of c0 is a's own lane, row 8 + r is b's lane across bit 3; c1 the
+// other way round.  Crossing bit 3 is a rotation by 8 within a row of 16 lanes (DPP row_ror:8); the bank
+// mask writes lanes 8..15 (0xC) or 0..7 (0x3) and leaves the others as they were.
+__device__ __forceinline__ uint32_t cross8(uint32_t keep, uint32_t take, int banks_hi)
+{
+    return banks_hi ? (uint32_t)__builtin_amdgcn_update_dpp((int)keep, (int)take, 0x128, 0xf, 0xC, false)
+                    : (uint32_t)__builtin_amdgcn_update_dpp((int)keep, (int)take, 0x128, 0xf, 0x3, false);
+}
+__device__ __forceinline__ void operand_pair(const u32x4 &a, const u32x4 &b, u32x4 &c0, u32x4 &c1)
+{
+    c0 = u32x4{cross8(a.x, b.x, 1), cross8(a.y, b.y, 1), cross8(a.z, b.z, 1), cross8(a.w, b.w, 1)};
+    c1 = u32x4{cross8(b.x, a.x, 0), cross8(b.y, a.y, 0), cross8(b.z, a.z, 0), cross8(b.w, a.w, 0)};
+}
 
 __device__ __forceinline__ f32x4_t mfma16q(const u32x4 &a, const u32x4 &b, const f32x4_t &c)
 {
@@ -41,179 +59,362 @@ __device__ __forceinline__ float sum8(const u32x4 &v, float a)
 }
 
 // ---------------------------------------------------------------------------
-// gate/up.  grid: kQGateUpBlocks (+ n_pred) workgroups of 256 threads; a wave owns at most 16 of the
-// union's neurons (one tile) and walks the whole row.  x is staged in LDS a range of columns at a
-// time (all T tokens, up to 64 KiB); every wave multiplies its tile over that range, keeping the
-// next batch of codes in flight.
+// gate/up.  grid: one workgroup of eight waves, or two of four, per compute unit; every workgroup does the
+// same kind of work.  The union's neurons are cut into tiles of up to 16 rows and a workgroup owns a run
+// of consecutive tiles.  Its work is the run's (tile, pair of quantisation blocks) items in row-major
+// order, and its waves take equal runs of THOSE: a wave multiplies a stretch of the reduction range of at
+// most three tiles, keeps the partial sums in registers, and the partial sums of a tile meet in LDS once,
+// when all of the workgroup's streaming is done.  (A wave per tile walking the whole row left three
+// quarters of the waves idle on a 63-group union and all the work on a quarter of the compute units; a
+// reduction per tile cost two barriers and a row set-up per 3 us of multiplying.)
+// A wave always has one batch of gate codes and one of up codes in flight; x (all T tokens) is staged in
+// LDS, whole, or in two halves of the row when it is larger than the LDS.
+// The first predictor layer of the next block (paper Sec. III-B.3, Pred beside Load/Comp, one layer
+// ahead) is dealt over the same workgroups, a row of At to a wave, after the wave's stretch; such a wave
+// gets a shorter stretch, by the pairs of blocks a row costs.  Workgroups of predictor rows alone would
+// each hold a compute unit's slot (the LDS for x) while doing none of the streaming.
 // ---------------------------------------------------------------------------
-constexpr int kQGateUpBlocks = 512;         // 2048 waves x 16 rows cover 256 groups
 constexpr int kQBatch = 8;                  // quantisation blocks per code buffer (8 KiB per wave in flight)
-constexpr int kQXBytes = 65536;             // LDS for x
+// LDS for x: 64 KiB in a workgroup of four waves, two to a compute unit; when the T tokens' rows need more,
+// 128 KiB in a workgroup of eight waves, one to a compute unit.  Either way eight waves share the unit.
+constexpr int q_x_bytes(int waves) { return waves == 4 ? 65536 : 131072; }
+constexpr int q_gate_up_blocks(int waves) { return 2048 / waves; }
 
+// Codes as they are loaded: one instruction covers whole 128-byte lines -- a pair of blocks of eight rows --
+// because a load of 64 bytes of each of 16 rows (the operand layout itself) asks the cache for twice the
+// lines and streamed a third slower.  Lane l = (q, bk, r) = (l / 16, l / 8 % 2, l % 8): v[2p] holds 16 bytes
+// of tile row r, v[2p + 1] of tile row 8 + r, both the codes 32q..32q+31 of block 2p + bk of the batch.
+// operand_pair() turns the two into the operand layout with four lane-crossing moves each.
 struct CodeBatch {
-    u32x4 v[kQBatch];                       // codes of blocks b0 .. b0+7 of row i, elements 32q..32q+31
-    uint2 sc[kQBatch / 4][4];               // scales of those blocks for result rows 4q .. 4q+3
+    u32x4 v[kQBatch];
+    uint32_t sc[kQBatch / 2][4];            // scales of block pairs (b0+2p, b0+2p+1) for result rows 4q .. 4q+3
 };
 
-__global__ __launch_bounds__(256, 2) void gate_up_q4_mt(
+// where a lane's operand row and its four result rows of a tile start
+struct QTile {
+    int aoff[2];                            // word offsets of (tile row r, 8 + r; this lane's 16 bytes of a pair of blocks)
+    int soff[4];                            // element offsets of the result rows in a scale matrix
+};
+
+template <int WAVES>
+__global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void gate_up_q4_mt(
     const bf16_t *__restrict__ x, int T, int d, int G, const uint32_t *__restrict__ Gq,
     const bf16_t *__restrict__ Gs, const uint32_t *__restrict__ Uq, const bf16_t *__restrict__ Us,
     const uint8_t *__restrict__ mask, bf16_t *__restrict__ act, int act_stride, AheadPredDev ap)
 {
     constexpr int gs = 128;
+    constexpr int NT = WAVES * 64, kQXBytes = q_x_bytes(WAVES);
+    // x; at the very end the same bytes hold the waves' partial sums, [tile][wave][lane][gate 0..3, up 4..7]
     __shared__ __attribute__((aligned(16))) unsigned char s_x[kQXBytes + 16 * 16];
     __shared__ int s_list[256];
     __shared__ float s_xs[16][64];          // 136 * (sum of x[t] over quantisation block b)
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    if ((int)blockIdx.x < ap.n_pred) {
-        // paper Sec. III-B.3, Pred beside Load/Comp, one layer ahead: the next block's first layer
-        const int j = blockIdx.x * 4 + wave;
-        switch (d) {
-        case 4096: predictor_row_tokens<4096>(ap.x_next, ap.At, ap.h, T, d, ap.r, j, lane); break;
-        case 5120: predictor_row_tokens<5120>(ap.x_next, ap.At, ap.h, T, d, ap.r, j, lane); break;
-        case 8192: predictor_row_tokens<8192>(ap.x_next, ap.At, ap.h, T, d, ap.r, j, lane); break;
-        default: predictor_row_tokens<0>(ap.x_next, ap.At, ap.h, T, d, ap.r, j, lane); break;
-        }
-        return;
-    }
+    static_assert(WAVES * WAVES * 64 * 8 * sizeof(float) <= kQXBytes, "partial sums of a workgroup's tiles fit");
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // in a scalar register: what depends on it is uniform
     const Q4Consts qk = q4_consts();
-    const MaskWords uw = load_union_words<16>(mask, T, G, lane);
-    if (uw.count == 0) return;                              // nothing survives for any token (uniform): no row to read
-    if (wave == 0) write_group_list(uw, lane, s_list);
-    const int nblk = d / kQ4Block, words = d / 8;
-    for (int idx = tid; idx < T * nblk; idx += 256) {
-        const int t = idx / nblk, b = idx - t * nblk;
-        const u32x4 *p = reinterpret_cast<const u32x4 *>(x + (size_t)t * d + b * kQ4Block);
-        float s = 0.0f;
-#pragma unroll
-        for (int k = 0; k < 16; ++k) s = sum8(p[k], s);
-        s_xs[t][b] = 136.0f * s;
-    }
-    __syncthreads();
-    // this wave's tile: rows n0 .. n1-1 of the union's neurons (n1 - n0 <= 16); waves beyond the work
-    // keep taking part in the barriers below with an empty tile
-    // (a wave costs the same whether its tile holds 4 rows or 16, so a small union goes to fewer waves
-    // with full tiles rather than to all of them)
-    const long long total = (long long)uw.count * gs;
-    const int waves = (gridDim.x - ap.n_pred) * 4;
-    const int nw = (int)min((long long)waves, (total + 15) / 16);
-    const int w = (blockIdx.x - ap.n_pred) * 4 + wave;
-    const int n0 = w < nw ? (int)(total * w / nw) : 0, n1 = w < nw ? (int)(total * (w + 1) / nw) : 0;
-    const int cnt = n1 - n0;
     const int i = lane & 15, q = lane >> 4;                 // operand role: row i / token i, element group q
     const int tok = i < T ? i : T - 1;                      // columns >= T repeat the last token, unused
-    auto weight_row = [&](int k) -> size_t {                // tile row k -> row of the weight matrices
-        const int n = cnt > 0 ? (k < cnt ? n0 + k : n1 - 1) : 0;
-        const int u = n / gs;
-        return (size_t)s_list[cnt > 0 ? u : 0] * gs + (n - u * gs);
-    };
-    const size_t arow = weight_row(i);                      // the row this lane feeds into the instruction
-    size_t srow[4];                                         // the rows whose results it holds
-#pragma unroll
-    for (int rr = 0; rr < 4; ++rr) srow[rr] = weight_row(4 * q + rr);
-    const uint32_t *gq = Gq + arow * words + q * 4, *uq = Uq + arow * words + q * 4;
-    auto fetch = [&](CodeBatch &r, const uint32_t *Q, const bf16_t *S, int b0) {
-#pragma unroll
-        for (int k = 0; k < kQBatch; ++k)
-            r.v[k] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(Q + (b0 + k) * 16));
-#pragma unroll
-        for (int h = 0; h < kQBatch / 4; ++h)
-#pragma unroll
-            for (int rr = 0; rr < 4; ++rr)
-                r.sc[h][rr] = *reinterpret_cast<const uint2 *>(S + srow[rr] * nblk + b0 + 4 * h);
-    };
-    // x in LDS: T rows of `span` columns, pitch = span*2 + 16 bytes (16 mod 256: the 16 lanes that read
-    // the same piece of different tokens hit distinct banks)
-    int span = kQXBytes / (2 * T);
-    span = span >= d ? d : (span / (kQBatch * kQ4Block)) * (kQBatch * kQ4Block);
+    // x in LDS: T rows of `span` columns (the row, or half of it), pitch = span*2 + 16 bytes (16 mod 256:
+    // the 16 lanes that read the same piece of different tokens hit distinct banks)
+    const int nspans = (T * d * 2 + kQXBytes - 1) / kQXBytes;      // 1 or 2, by the host's choice of WAVES
+    const int span = d / nspans, bps = span / kQ4Block, ppr = bps / 2;
     const int pitch = span * 2 + 16;
     const unsigned char *xl = s_x + tok * pitch + q * 64;   // + (block in span) * 256 + s * 16
-    f32x4_t cg = {0.f, 0.f, 0.f, 0.f}, cu = {0.f, 0.f, 0.f, 0.f};
-    auto multiply = [&](const CodeBatch &r, int b0, int blk_in_span, f32x4_t &acc) {
+    // Columns k0 .. k0+span-1 of all tokens go straight to LDS, 1 KiB (512 columns of one token) per wave
+    // and instruction, no registers in between: the requests are out before the mask bytes are asked for,
+    // and the weight rows requested once the union is known travel beside them.
+    const uint32_t s_x_addr = (uint32_t)(size_t)s_x;
+    auto x_request = [&](int k0) {
+        const int cpr = span / 512, chunks = T * cpr;       // chunks of a token row, chunks in all: <= kQXBytes / 1024
+        for (int c = wave; c < chunks; c += WAVES) {        // uniform
+            const int t = c / cpr, part = c - t * cpr;
+            load_to_lds16_all(x, (uint32_t)(t * d + k0 + part * 512 + lane * 8) * 2u, s_x_addr + t * pitch + part * 1024);
+        }
+    };
+    // 136 * the sum of every (token, quantisation block) of the range: a wave sums the chunks it asked for
+    // itself (after its own wait for them, no barrier in between); a chunk is four blocks, 16 lanes a block
+    auto x_sums = [&](int k0) {
+        const int cpr = span / 512, chunks = T * cpr;
+        for (int c = wave; c < chunks; c += WAVES) {        // uniform
+            const int t = c / cpr, part = c - t * cpr;
+            float sum = sum8(*reinterpret_cast<const u32x4 *>(s_x + t * pitch + part * 1024 + lane * 16), 0.0f);
+            sum = xor_add<8>(sum);
+            sum = xor_add<4>(sum);
+            sum = xor_add<2>(sum);
+            sum = xor_add<1>(sum);
+            if ((lane & 15) == 0) s_xs[t][k0 / kQ4Block + part * 4 + (lane >> 4)] = 136.0f * sum;
+        }
+    };
+    x_request(0);
+    // the union of the tokens' surviving groups, eight tokens' mask bytes per memory round trip
+    MaskWords uw;
+    {
+        uint32_t any[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int t0 = 0; t0 < 16; t0 += 8) {
+            if (t0 < T) {                                   // uniform
+                uint8_t v[8][4];
+#pragma unroll
+                for (int t = 0; t < 8; ++t)
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        const int g = k * kWave + lane;
+                        v[t][k] = mask[(uint32_t)((t0 + t < T ? t0 + t : T - 1) * G + (g < G ? g : 0))];
+                    }
+#pragma unroll
+                for (int t = 0; t < 8; ++t)
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) any[k] |= v[t][k];
+            }
+        }
+        uw.count = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            uw.w[k] = __ballot(k * kWave + lane < G && any[k] != 0u);
+            uw.count += __popcll(uw.w[k]);
+        }
+    }
+    const int total = uw.count * gs;
+    const int nt = (total + 15) / 16;                       // tiles; rows dealt evenly, at most 16 each
+    const int rows_lo = nt ? total / nt : 0, rows_rem = nt ? total - rows_lo * nt : 0;
+    auto tile_begin = [&](int t) { return t * rows_lo + min(t, rows_rem); };
+    const int nwg = gridDim.x, wg = blockIdx.x;
+    const int t_lo = nt * wg / nwg, ntw = nt * (wg + 1) / nwg - t_lo;           // this workgroup's tiles: <= WAVES
+    // predictor rows of this workgroup; without an overlapped next step (n_pred == 0) they are not computed, but the
+    // waves' stretches are cut as if they were, so that a block's output has the same bits either way
+    const int j_lo = (int)((long long)ap.r * wg / nwg), npr = (int)((long long)ap.r * (wg + 1) / nwg) - j_lo;
+    const int npr_run = ap.n_pred ? npr : 0;
+    if (ntw == 0 && npr_run == 0) return;                   // uniform
+    // predictor rows go to the last waves first: row j_lo + k to wave WAVES-1 - k % WAVES
+    auto rows_of_wave = [&](int v) { const int k0 = WAVES - 1 - v; return k0 < npr ? (npr - k0 + WAVES - 1) / WAVES : 0; };
+    // the cut of the workgroup's ntw * ppr pairs of blocks between the waves; `weight` = pairs a predictor row counts for
+    const int P = ntw * ppr;
+    int cut[WAVES + 1] = {};
+    auto make_cuts = [&](int weight) {
+        const int U = P + weight * npr;
+        int rows_before = 0, worst = 0;
+        cut[0] = 0;
+#pragma unroll
+        for (int v = 0; v < WAVES; ++v) {
+            rows_before += rows_of_wave(v);
+            int c = v == WAVES - 1 ? P : U * (v + 1) / WAVES - weight * rows_before;
+            c = c < cut[v] ? cut[v] : c > P ? P : c;
+            cut[v + 1] = c;
+            if (c > cut[v]) worst = max(worst, (c - 1) / ppr - cut[v] / ppr + 1);
+        }
+        return worst;                                       // the most tiles any wave's stretch touches
+    };
+    if (ntw > 0) {
+        // a row of At for T tokens is about T * d / 512 * 24 vector instructions, a pair of blocks of gate and
+        // up about 250; the stretches must stay within three tiles (three sets of partial sums per wave)
+        int weight = T * (d / 512) / 10;
+        weight = weight < 1 ? 1 : weight > ppr ? ppr : weight;
+        if (make_cuts(npr ? weight : 0) > 3) make_cuts(0);
+    }
+    int p0 = 0, p1 = 0;                                     // (selected, not indexed: the cuts stay in registers)
+    if (ntw > 0) {
+#pragma unroll
+        for (int v = 0; v < WAVES; ++v)
+            if (v == wave) {
+                p0 = cut[v];
+                p1 = cut[v + 1];
+            }
+    }
+    const int tl0 = ntw > 0 ? p0 / ppr : 0, npieces = p1 > p0 ? (p1 - 1) / ppr - tl0 + 1 : 0;
+    const int nblk = d / kQ4Block, words = d / 8;
+    // the tile this wave finishes at the end (local index = wave): whether token i keeps its groups
+    uint8_t keep_first = 0, keep_last = 0;
+    int fin_n0 = 0, fin_n1 = 0;
+    if (ntw > 0) {
+        if (wave == 0) write_group_list(uw, lane, s_list);
+        __syncthreads();                                    // the list
+        if (wave < ntw) {
+            fin_n0 = tile_begin(t_lo + wave);
+            fin_n1 = tile_begin(t_lo + wave + 1);
+            keep_first = mask[(size_t)tok * G + s_list[fin_n0 / gs]];
+            keep_last = mask[(size_t)tok * G + s_list[(fin_n1 - 1) / gs]];
+        }
+    }
+    auto setup = [&](QTile &t, int tile) {
+        const int n0 = tile_begin(tile), n1 = tile_begin(tile + 1);
+        auto weight_row = [&](int k) -> int {               // tile row k -> row of the weight matrices
+            const int n = n0 + k < n1 ? n0 + k : n1 - 1;
+            const int u = n / gs;
+            return s_list[u] * gs + (n - u * gs);
+        };
+        const int bk = (lane >> 3) & 1;
+        t.aoff[0] = weight_row(lane & 7) * words + bk * 16 + q * 4;
+        t.aoff[1] = weight_row(8 + (lane & 7)) * words + bk * 16 + q * 4;
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) t.soff[rr] = weight_row(4 * q + rr) * nblk;
+    };
+    // piece k of this wave's stretch within the range of columns rg: blocks [b_lo, b_hi) of tile tl0 + k
+    auto piece_blocks = [&](int rg, int k, int &b_lo, int &b_hi) {
+        const int first = (tl0 + k) * ppr;
+        b_lo = rg * bps + 2 * (max(p0, first) - first);
+        b_hi = rg * bps + 2 * (min(p1, first + ppr) - first);
+    };
+    // blocks b0 .. b0+7 of the lane's rows, as far as they lie below `end` (uniform conditions)
+    auto fetch = [&](CodeBatch &r_, const uint32_t *Q, const bf16_t *S, const QTile &t, int b0, int end) {
+#pragma unroll
+        for (int k = 0; k < kQBatch; ++k)
+            if (b0 + (k & ~1) < end)
+                r_.v[k] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(Q + t.aoff[k & 1] + (b0 + (k & ~1)) * 16));
+#pragma unroll
+        for (int h = 0; h < kQBatch / 2; ++h)
+            if (b0 + 2 * h < end) {
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr)
+                    r_.sc[h][rr] = *reinterpret_cast<const uint32_t *>(S + t.soff[rr] + b0 + 2 * h);
+            }
+    };
+    // Multiplies blocks b0 .. of the buffer (below `end`); as soon as a pair of blocks has been used, its
+    // registers are asked for the same pair of the buffer's next batch (blocks n0 .. below nend of the rows of
+    // nt_), so a wave's two buffers stay in flight all the time instead of one being idle while it is used.
+    auto multiply = [&](CodeBatch &r_, int b0, int end, int bfirst, f32x4_t &acc, const uint32_t *Q, const bf16_t *S,
+                        const QTile &nt_, int n0, int nend) {
 #pragma unroll
         for (int h = 0; h < kQBatch / 2; ++h) {
+            if (b0 + 2 * h >= end && n0 + 2 * h >= nend) break;         // uniform
+            if (b0 + 2 * h < end) {
             // two quantisation blocks at a time: two independent chains of four matrix instructions
             f32x4_t t[2];
-            u32x4 xb[2][4];
+            u32x4 xb[2][4], c[2];
+            operand_pair(r_.v[2 * h], r_.v[2 * h + 1], c[0], c[1]);
 #pragma unroll
             for (int bk = 0; bk < 2; ++bk) {
                 t[bk] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int s = 0; s < 4; ++s)
-                    xb[bk][s] = *reinterpret_cast<const u32x4 *>(xl + (blk_in_span + 2 * h + bk) * 256 + s * 16);
+                    xb[bk][s] = *reinterpret_cast<const u32x4 *>(xl + (b0 - bfirst + 2 * h + bk) * 256 + s * 16);
             }
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
 #pragma unroll
                 for (int bk = 0; bk < 2; ++bk) {
-                    const u32x4 &c = r.v[2 * h + bk];
-                    const uint32_t word = s == 0 ? c.x : s == 1 ? c.y : s == 2 ? c.z : c.w;
+                    const uint32_t word = s == 0 ? c[bk].x : s == 1 ? c[bk].y : s == 2 ? c[bk].z : c[bk].w;
                     t[bk] = mfma16q(q4_word_bf16(word, qk), xb[bk][s], t[bk]);
                 }
             }
 #pragma unroll
             for (int bk = 0; bk < 2; ++bk) {
-                const int blk = 2 * h + bk;                 // 0..7 within the batch: scales sc[blk / 4], element blk % 4
-                const float xo = s_xs[tok][b0 + blk];
+                const float xo = s_xs[tok][b0 + 2 * h + bk];
 #pragma unroll
                 for (int rr = 0; rr < 4; ++rr) {
-                    const uint32_t pair = (blk & 2) ? r.sc[blk >> 2][rr].y : r.sc[blk >> 2][rr].x;
-                    const float scale = (blk & 1) ? bf16_hi(pair) : bf16_lo(pair);
+                    const float scale = bk ? bf16_hi(r_.sc[h][rr]) : bf16_lo(r_.sc[h][rr]);
                     acc[rr] = __builtin_fmaf(scale, t[bk][rr] - xo, acc[rr]);
                 }
+            }
+            }
+            if (n0 + 2 * h < nend) {                        // uniform
+                r_.v[2 * h] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(Q + nt_.aoff[0] + (n0 + 2 * h) * 16));
+                r_.v[2 * h + 1] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(Q + nt_.aoff[1] + (n0 + 2 * h) * 16));
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr)
+                    r_.sc[h][rr] = *reinterpret_cast<const uint32_t *>(S + nt_.soff[rr] + n0 + 2 * h);
             }
             __builtin_amdgcn_sched_barrier(0);              // keeps one pair's operands live at a time
         }
     };
-    CodeBatch R0, R1;
-    const bool busy = cnt > 0;                              // a wave without rows only stages x and meets the barriers
-    if (busy) fetch(R0, gq, Gs, 0);
-    for (int k0 = 0; k0 < d; k0 += span) {
-        const int n = min(span, d - k0);                    // columns of this range, a multiple of 1024
-        __syncthreads();                                    // everybody is done with the previous range
-        {
-            // pieces of 16 bytes, token-major; eight loads go out before the first store (one memory
-            // round trip per eight pieces and thread, not one per piece)
-            const int n8 = n / 8, pieces = T * n8;
-            int t = tid / n8, c = tid - t * n8;
-            for (int base = tid; base < pieces; base += 256 * 8) {
-                u32x4 v[8];
-                int dst[8];
+    // partial sums of the (up to three) tiles of the stretch
+    f32x4_t sg[3], su[3];
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const bool ok = base + 256 * j < pieces;
-                    const int tt = ok ? t : 0, cc = ok ? c : 0;
-                    v[j] = *reinterpret_cast<const u32x4 *>(x + (size_t)tt * d + k0 + cc * 8);
-                    dst[j] = ok ? tt * pitch + cc * 16 : -1;
-                    c += 256;
-                    while (c >= n8) {
-                        c -= n8;
-                        ++t;
-                    }
+    for (int k = 0; k < 3; ++k) sg[k] = su[k] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    if (ntw > 0) {
+        QTile cur;
+        CodeBatch R0, R1;                                   // gate and up codes of the same blocks
+        for (int rg = 0; rg < nspans; ++rg) {               // uniform
+            if (rg > 0) {
+                __syncthreads();                            // everybody is done with the previous range
+                x_request(rg * span);
+            }
+            int wb0 = 0, wb1 = 0;
+            if (npieces > 0) {
+                setup(cur, t_lo + tl0);
+                piece_blocks(rg, 0, wb0, wb1);
+                fetch(R0, Gq, Gs, cur, wb0, wb1);
+                fetch(R1, Uq, Us, cur, wb0, wb1);
+            }
+            wait_all_loads();                               // x is in LDS (and the first batches are here)
+            x_sums(rg * span);
+            __syncthreads();
+            for (int k = 0; k < npieces; ++k) {
+                f32x4_t cg = k == 0 ? sg[0] : k == 1 ? sg[1] : sg[2];
+                f32x4_t cu = k == 0 ? su[0] : k == 1 ? su[1] : su[2];
+                int nb0 = 0, nb1 = 0;                       // the next piece of this range, if any
+                if (k + 1 < npieces) piece_blocks(rg, k + 1, nb0, nb1);
+                for (int b0 = wb0; b0 < wb1; b0 += kQBatch) {
+                    // the buffers are refilled from the same rows, or, in the piece's last batch, from the
+                    // next piece's rows if there is one
+                    const bool last = b0 + kQBatch >= wb1;
+                    if (last && k + 1 < npieces) setup(cur, t_lo + tl0 + k + 1);
+                    const int rn0 = last ? nb0 : b0 + kQBatch, rn1 = last ? nb1 : wb1;
+                    multiply(R0, b0, wb1, rg * bps, cg, Gq, Gs, cur, rn0, rn1);
+                    multiply(R1, b0, wb1, rg * bps, cu, Uq, Us, cur, rn0, rn1);
                 }
-#pragma unroll
-                for (int j = 0; j < 8; ++j)
-                    if (dst[j] >= 0) *reinterpret_cast<u32x4 *>(s_x + dst[j]) = v[j];
+                if (k == 0) {
+                    sg[0] = cg;
+                    su[0] = cu;
+                } else if (k == 1) {
+                    sg[1] = cg;
+                    su[1] = cu;
+                } else {
+                    sg[2] = cg;
+                    su[2] = cu;
+                }
+                wb0 = nb0;
+                wb1 = nb1;
             }
         }
-        __syncthreads();
-        const int bfirst = k0 / kQ4Block, bend = (k0 + n) / kQ4Block;
-        for (int b0 = bfirst; busy && b0 < bend; b0 += kQBatch) {
-            fetch(R1, uq, Us, b0);
-            multiply(R0, b0, b0 - bfirst, cg);
-            fetch(R0, gq, Gs, b0 + kQBatch < nblk ? b0 + kQBatch : b0);      // past the end: a duplicate, unused
-            multiply(R1, b0, b0 - bfirst, cu);
+    }
+    // this wave's predictor rows
+    for (int k = WAVES - 1 - wave; k < npr_run; k += WAVES) {
+        const int j = j_lo + k;
+        switch (d) {
+        case 4096: predictor_row_tokens_batched<4096, 2>(ap.x_next, ap.At, ap.h, T, ap.r, j, lane); break;
+        case 5120: predictor_row_tokens_batched<5120, 2>(ap.x_next, ap.At, ap.h, T, ap.r, j, lane); break;
+        case 8192: predictor_row_tokens<8192>(ap.x_next, ap.At, ap.h, T, d, ap.r, j, lane); break;
+        default: predictor_row_tokens<0>(ap.x_next, ap.At, ap.h, T, d, ap.r, j, lane); break;
         }
     }
-    // D: column = token i, rows 4q..4q+3 of the tile
-    if (i < T) {
+    if (ntw == 0) return;                                   // uniform
+    __syncthreads();                                        // nobody reads x any more: its bytes take the partial sums
+    float *part = reinterpret_cast<float *>(s_x);
 #pragma unroll
-        for (int rr = 0; rr < 4; ++rr) {
-            const int nn = n0 + 4 * q + rr;
-            if (nn < n1) {
-                const int g = s_list[nn / gs];
-                const float v = mask[(size_t)i * G + g] ? silu_mul(cg[rr], cu[rr]) : 0.0f;
-                act[(size_t)i * act_stride + nn] = f32_to_bf16(v);
+    for (int k = 0; k < 3; ++k) {
+        if (k < npieces) {
+            float *dst = part + ((size_t)((tl0 + k) * WAVES + wave) * 64 + lane) * 8;
+            *reinterpret_cast<f32x4_t *>(dst) = sg[k];
+            *reinterpret_cast<f32x4_t *>(dst + 4) = su[k];
+        }
+    }
+    __syncthreads();
+    // wave v finishes tile v of the workgroup: the stretches that touch it, in the order of the row.
+    // D: column = token i, rows 4q..4q+3 of the tile
+    if (wave < ntw) {
+        f32x4_t g_ = {0.f, 0.f, 0.f, 0.f}, u_ = {0.f, 0.f, 0.f, 0.f};
+        const int first = wave * ppr;
+#pragma unroll
+        for (int v = 0; v < WAVES; ++v) {
+            if (cut[v] < first + ppr && cut[v + 1] > first && cut[v + 1] > cut[v]) {        // uniform
+                const float *src = part + ((size_t)(wave * WAVES + v) * 64 + lane) * 8;
+                const f32x4_t a = *reinterpret_cast<const f32x4_t *>(src), b = *reinterpret_cast<const f32x4_t *>(src + 4);
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr) {
+                    g_[rr] += a[rr];
+                    u_[rr] += b[rr];
+                }
+            }
+        }
+        if (i < T) {
+            const int u_first = fin_n0 / gs;
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) {
+                const int nn = fin_n0 + 4 * q + rr;
+                if (nn < fin_n1) {
+                    const uint8_t keep = nn / gs == u_first ? keep_first : keep_last;
+                    act[(size_t)i * act_stride + nn] = f32_to_bf16(keep ? silu_mul(g_[rr], u_[rr]) : 0.0f);
+                }
             }
         }
     }
@@ -352,18 +553,24 @@ bool q4_mfma_path_supported(int T, int d, int G, int gs)
 }
 
 hipError_t launch_ffn_q4_mfma(const bf16_t *x, int T, int d, int G, const Q4Weights &w, const uint8_t *mask,
-                              bf16_t *y, const DecodeScratch &ws, hipStream_t s, const AheadArgs *ahead,
+                              bf16_t *y, const DecodeScratch &ws, hipStream_t s, int rank, const AheadArgs *ahead,
                               bool *ahead_fused)
 {
     const int ffn = G * kQ4Block;
     bf16_t *act = reinterpret_cast<bf16_t *>(ws.act);
     const AheadArgs *ah = (ahead && ahead_fused) ? ahead : nullptr;
     if (ahead_fused) *ahead_fused = ah != nullptr;
-    const AheadPredDev ap = ahead_pred_dev(ah);
+    AheadPredDev ap = ahead_pred_dev(ah);
+    ap.r = rank;                                            // the work is shaped by it whether or not the rows ride along
     const int n_mask = ah ? T : 0;
     const AheadDev nx = ah ? ahead_dev(*ah) : AheadDev{};
-    launch_timed("gate_up_q4_mt", gate_up_q4_mt, dim3(kQGateUpBlocks + ap.n_pred), dim3(256), s, x, T, d, G, w.gate_codes,
-                 w.gate_scales, w.up_codes, w.up_scales, mask, act, ffn, ap);
+    // the predictor rows ride inside the same workgroups: ap.n_pred only says whether there are any
+    if ((size_t)T * d * sizeof(bf16_t) <= (size_t)q_x_bytes(4))
+        launch_timed("gate_up_q4_mt", gate_up_q4_mt<4>, dim3(q_gate_up_blocks(4)), dim3(256), s, x, T, d, G, w.gate_codes,
+                     w.gate_scales, w.up_codes, w.up_scales, mask, act, ffn, ap);
+    else
+        launch_timed("gate_up_q4_mt", gate_up_q4_mt<8>, dim3(q_gate_up_blocks(8)), dim3(512), s, x, T, d, G, w.gate_codes,
+                     w.gate_scales, w.up_codes, w.up_scales, mask, act, ffn, ap);
     static const hipError_t lds_ok = hipFuncSetAttribute(reinterpret_cast<const void *>(down_q4_mt),
                                                          hipFuncAttributeMaxDynamicSharedMemorySize,
                                                          (int)q_down_lds_bytes(16));

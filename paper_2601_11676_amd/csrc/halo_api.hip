@@ -418,7 +418,7 @@ int halo_group_sparse_ffn_q4(const halo_shape *shape, const void *x, int32_t T, 
     const Q4Weights w{(const uint32_t *)Wg_codes, (const bf16_t *)Wg_scales, (const uint32_t *)Wu_codes,
                       (const bf16_t *)Wu_scales, (const uint32_t *)Wd_codes, (const bf16_t *)Wd_scales};
     hipError_t e = launch_ffn_q4(shape->dtype, x, T, shape->d, shape->n_groups, shape->group_size, w, mask, y,
-                                 ws.dec, static_cast<hipStream_t>(stream));
+                                 ws.dec, static_cast<hipStream_t>(stream), shape->rank);
     return e == hipSuccess ? HALO_OK : HALO_ERR_HIP;
 }
 
@@ -456,7 +456,8 @@ int halo_ffn_forward_q4(const halo_shape *shape, const void *x, const void *x_pr
     if (e != hipSuccess) return HALO_ERR_HIP;
     const Q4Weights w{(const uint32_t *)Wg_codes, (const bf16_t *)Wg_scales, (const uint32_t *)Wu_codes,
                       (const bf16_t *)Wu_scales, (const uint32_t *)Wd_codes, (const bf16_t *)Wd_scales};
-    e = launch_ffn_q4(shape->dtype, x, T, shape->d, shape->n_groups, shape->group_size, w, mk, y, ws.dec, s);
+    e = launch_ffn_q4(shape->dtype, x, T, shape->d, shape->n_groups, shape->group_size, w, mk, y, ws.dec, s,
+                      shape->rank);
     return e == hipSuccess ? HALO_OK : HALO_ERR_HIP;
 }
 
@@ -601,7 +602,7 @@ int halo_ffn_forward_ahead_q4(const halo_shape *shape, const void *x, int32_t T,
                       (const bf16_t *)Wu_scales, (const uint32_t *)Wd_codes, (const bf16_t *)Wd_scales};
     bool fused = false;
     hipError_t e = launch_ffn_q4(shape->dtype, x, T, shape->d, shape->n_groups, shape->group_size, w, mask_cur,
-                                 y, ws.dec, s, &ah, &fused);
+                                 y, ws.dec, s, shape->rank, &ah, &fused);
     if (e != hipSuccess) return HALO_ERR_HIP;
     if (!fused) {
         e = launch_predictor(shape->dtype, x_pred_next, T, shape->d, shape->rank, shape->n_groups, At_next,

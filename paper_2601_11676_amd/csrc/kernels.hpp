@@ -117,15 +117,17 @@ struct Q4Weights {
     const bf16_t *down_scales;    // [G][d]
 };
 bool q4_shape_supported(int d, int gs);
+// rank: the predictor's size; the few-token kernel shapes its work around the predictor rows it carries when
+// one step is overlapped with the next, and shapes it the same way when it carries none (same bits either way)
 hipError_t launch_ffn_q4(int dtype, const void *x, int T, int d, int G, int gs, const Q4Weights &w,
-                         const uint8_t *mask, void *y, const DecodeScratch &ws, hipStream_t s,
+                         const uint8_t *mask, void *y, const DecodeScratch &ws, hipStream_t s, int rank,
                          const AheadArgs *ahead = nullptr, bool *ahead_fused = nullptr);
 
 // ffn_q4_mt.hip : 4-bit weights, 2..16 tokens, matrix cores
 bool q4_mfma_path_supported(int T, int d, int G, int gs);
 hipError_t launch_ffn_q4_mfma(const bf16_t *x, int T, int d, int G, const Q4Weights &w, const uint8_t *mask,
-                              bf16_t *y, const DecodeScratch &ws, hipStream_t s, const AheadArgs *ahead = nullptr,
-                              bool *ahead_fused = nullptr);
+                              bf16_t *y, const DecodeScratch &ws, hipStream_t s, int rank,
+                              const AheadArgs *ahead = nullptr, bool *ahead_fused = nullptr);
 
 // mha_decode.hip : head-sparse attention for one new token (bf16, head dimension 128)
 struct MhaScratch {

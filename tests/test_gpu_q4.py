@@ -73,6 +73,8 @@ def test_q4_one_token_streaming_path(d, G, K):
     (16, 4096, 6, 256),
     (5, 4096, 20, 256),      # union larger than any token's set; ragged neuron runs per wave
     (3, 512, 3, 40),         # a single chunk per row
+    (6, 5120, 90, 256),      # more 16-row tiles than workgroups: a workgroup walks several
+    (16, 8192, 40, 256),     # x larger than its LDS space: staged a range of columns at a time, per tile
 ])
 def test_q4_few_tokens_matrix_core_path(T, d, G, r):
     w = dataclasses.replace(hs.LLAMA13B_STACK, name="case", d=d, ffn=G * 128, rank=r, T=T, layers=1, seed=18)
