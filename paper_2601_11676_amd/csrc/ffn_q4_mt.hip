@@ -423,11 +423,16 @@ __global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void gate_up_q4_mt(
 // ---------------------------------------------------------------------------
 // down.  grid: d/16 (+ n_mask) workgroups of 256 threads.  A workgroup owns 16 output rows; a group's
 // 16 x 128 tile of codes is 1 KiB of consecutive bytes = one load per lane (row i, codes 32q..32q+31).
-// The four waves split the union's groups, eight groups per batch: the batch's activations (T rows of
-// 8 x 128 values, consecutive in the compact layout) are staged in a private LDS region with coalesced
-// loads and read from there in operand order.
+// The four waves split the union's groups, four groups per batch.  While a batch is multiplied the next
+// batch's codes, scales and activations are on their way, the activations (T rows of 4 x 128 values,
+// consecutive in the compact layout) into registers; they are written to the wave's private LDS region,
+// from where they are read in operand order, once the multiplication is done with the region.  (With one
+// batch at a time -- loads, wait, activations, wait, multiply -- a wave waited for memory three times per
+// eight groups and the kernel ran at 1.5 TB/s.)
+// TMAX: the token rows a wave fetches per batch (rows past T repeat the last token's, unused): fixed at
+// compile time so that every load is issued unconditionally and the compiler can count the loads in flight.
 // ---------------------------------------------------------------------------
-constexpr int kQDownGroups = 8;
+constexpr int kQDownGroups = 4;
 constexpr int kQActPitch = kQDownGroups * 256 + 16;     // bytes per token row of a batch (16 mod 256)
 
 // dynamic LDS of the kernel: [red: 4 x 64 x 4 floats][list: 256 ints][activations: 4 waves x T rows of
@@ -439,6 +444,12 @@ inline size_t q_down_lds_bytes(int T)
     return need > sizeof(MaskShared) ? need : sizeof(MaskShared);
 }
 
+struct DownBatch {
+    u32x4 r[kQDownGroups];                  // codes of the batch's groups: row i of the tile, codes 32q..32q+31
+    uint2 sc[kQDownGroups];                 // scales of rows 4q .. 4q+3
+};
+
+template <int TMAX>
 __global__ __launch_bounds__(256) void down_q4_mt(
     int T, int d, int G, const uint32_t *__restrict__ Dq, const bf16_t *__restrict__ Ds,
     const uint8_t *__restrict__ mask, const bf16_t *__restrict__ act, int act_stride, bf16_t *__restrict__ y,
@@ -463,7 +474,8 @@ __global__ __launch_bounds__(256) void down_q4_mt(
     const Q4Consts qk = q4_consts();
     float(*red)[64][4] = reinterpret_cast<float(*)[64][4]>(lds);
     int *s_list = reinterpret_cast<int *>(lds + 4 * 64 * 4 * sizeof(float));
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int i = lane & 15, q = lane >> 4;
     const int j0 = (blockIdx.x - n_mask) * 16;
     const MaskWords uw = load_union_words<16>(mask, T, G, lane);
@@ -471,44 +483,36 @@ __global__ __launch_bounds__(256) void down_q4_mt(
     __syncthreads();
     const int n_u = uw.count;
     const int u0 = n_u * wave / 4, u1 = n_u * (wave + 1) / 4;
+    const int nbat = (u1 - u0 + kQDownGroups - 1) / kQDownGroups;
     const int tok = i < T ? i : T - 1;
     const size_t gwords = (size_t)d * (gs / 8);                      // words per group
     const uint32_t *ctile = Dq + (size_t)(j0 + i) * (gs / 8) + q * 4;   // row i of the tile, codes 32q..32q+31
     unsigned char *mine = lds + kQDownFixed + (size_t)wave * T * kQActPitch;
     const unsigned char *al = mine + tok * kQActPitch + q * 64;      // + (group in batch) * 256 + s * 16
     f32x4_t c = {0.f, 0.f, 0.f, 0.f};
-    for (int ub = u0; ub < u1; ub += kQDownGroups) {
-        u32x4 r[kQDownGroups];
-        uint2 sc[kQDownGroups];
+    // batch b of the wave's share: groups u0 + 4b .., those past the end of the share repeat its last one
+    // (in range, unused).  A token's row of the batch is 4 groups x 16 pieces = one piece per lane.
+    u32x4 av[TMAX];
+    auto issue = [&](DownBatch &B, int b) {
+        const int ub = u0 + b * kQDownGroups;
 #pragma unroll
         for (int k = 0; k < kQDownGroups; ++k) {
-            const int u = ub + k < u1 ? ub + k : ub;                 // past the end: in-range duplicate
-            const int g = s_list[u];
-            r[k] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(ctile + g * gwords));
-            sc[k] = *reinterpret_cast<const uint2 *>(Ds + (size_t)g * d + j0 + 4 * q);   // scales of rows 4q..4q+3
+            const int g = s_list[min(ub + k, u1 - 1)];
+            B.r[k] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(ctile + g * gwords));
+            B.sc[k] = *reinterpret_cast<const uint2 *>(Ds + (size_t)g * d + j0 + 4 * q);   // scales of rows 4q..4q+3
         }
-        // the batch's activations: token t, bytes [ub*256, ub*256 + nb*256) of its row; the region is the
-        // wave's own and LDS operations of a wave complete in order, so no barrier is needed
-        const int nb = min(kQDownGroups, u1 - ub);
-        // a token's row of the batch is 8 groups x 16 pieces; groups past the end of the wave's share
-        // repeat its last one (in range, unused).  Eight loads go out before the first store.
-        for (int t0 = 0; t0 < T; t0 += 4) {
-            u32x4 v[8];
+        const int un = min(ub + (lane >> 4), u1 - 1);                // position in the union of this lane's piece
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int p = lane + 64 * j;                         // 0..511: token t0 + p/128, piece p%128
-                const int t = min(t0 + (p >> 7), T - 1), piece = p & 127;
-                const int k = min(piece >> 4, nb - 1);
-                v[j] = *reinterpret_cast<const u32x4 *>(act + (size_t)t * act_stride + (size_t)(ub + k) * gs +
-                                                        (piece & 15) * 8);
-            }
+        for (int t = 0; t < TMAX; ++t)
+            av[t] = *reinterpret_cast<const u32x4 *>(act + (size_t)min(t, T - 1) * act_stride + (size_t)un * gs + (lane & 15) * 8);
+    };
+    // the region is the wave's own and LDS operations of a wave complete in order, so no barrier is needed
+    auto store_act = [&]() {
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int p = lane + 64 * j;
-                const int t = t0 + (p >> 7);
-                if (t < T) *reinterpret_cast<u32x4 *>(mine + t * kQActPitch + (p & 127) * 16) = v[j];
-            }
-        }
+        for (int t = 0; t < TMAX; ++t)
+            if (t < T) *reinterpret_cast<u32x4 *>(mine + t * kQActPitch + lane * 16) = av[t];
+    };
+    auto multiply = [&](const DownBatch &B, int nb) {
 #pragma unroll
         for (int k = 0; k < kQDownGroups; ++k) {
             if (k < nb) {                                            // uniform
@@ -517,10 +521,10 @@ __global__ __launch_bounds__(256) void down_q4_mt(
                 for (int s = 0; s < 4; ++s) b[s] = *reinterpret_cast<const u32x4 *>(al + k * 256 + s * 16);
                 f32x4_t t0 = {0.f, 0.f, 0.f, 0.f}, t1 = {0.f, 0.f, 0.f, 0.f};
                 float asum = 0.0f;
-                t0 = mfma16q(q4_word_bf16(r[k].x, qk), b[0], t0);
-                t1 = mfma16q(q4_word_bf16(r[k].y, qk), b[1], t1);
-                t0 = mfma16q(q4_word_bf16(r[k].z, qk), b[2], t0);
-                t1 = mfma16q(q4_word_bf16(r[k].w, qk), b[3], t1);
+                t0 = mfma16q(q4_word_bf16(B.r[k].x, qk), b[0], t0);
+                t1 = mfma16q(q4_word_bf16(B.r[k].y, qk), b[1], t1);
+                t0 = mfma16q(q4_word_bf16(B.r[k].z, qk), b[2], t0);
+                t1 = mfma16q(q4_word_bf16(B.r[k].w, qk), b[3], t1);
 #pragma unroll
                 for (int s = 0; s < 4; ++s) asum = sum8(b[s], asum);
                 const f32x4_t t = t0 + t1;
@@ -528,12 +532,24 @@ __global__ __launch_bounds__(256) void down_q4_mt(
                 asum += __shfl_xor(asum, 16);
                 asum += __shfl_xor(asum, 32);
                 const float xo = 136.0f * asum;
-                c[0] = __builtin_fmaf(bf16_lo(sc[k].x), t[0] - xo, c[0]);
-                c[1] = __builtin_fmaf(bf16_hi(sc[k].x), t[1] - xo, c[1]);
-                c[2] = __builtin_fmaf(bf16_lo(sc[k].y), t[2] - xo, c[2]);
-                c[3] = __builtin_fmaf(bf16_hi(sc[k].y), t[3] - xo, c[3]);
+                c[0] = __builtin_fmaf(bf16_lo(B.sc[k].x), t[0] - xo, c[0]);
+                c[1] = __builtin_fmaf(bf16_hi(B.sc[k].x), t[1] - xo, c[1]);
+                c[2] = __builtin_fmaf(bf16_lo(B.sc[k].y), t[2] - xo, c[2]);
+                c[3] = __builtin_fmaf(bf16_hi(B.sc[k].y), t[3] - xo, c[3]);
             }
         }
+    };
+    if (nbat > 0) {                                                  // uniform per wave; no barrier inside
+        DownBatch cur, nxt;
+        issue(cur, 0);
+        store_act();
+        for (int b = 0; b + 1 < nbat; ++b) {
+            issue(nxt, b + 1);
+            multiply(cur, kQDownGroups);
+            store_act();
+            cur = nxt;
+        }
+        multiply(cur, u1 - u0 - (nbat - 1) * kQDownGroups);
     }
 #pragma unroll
     for (int rr = 0; rr < 4; ++rr) red[wave][lane][rr] = c[rr];
@@ -571,12 +587,23 @@ hipError_t launch_ffn_q4_mfma(const bf16_t *x, int T, int d, int G, const Q4Weig
     else
         launch_timed("gate_up_q4_mt", gate_up_q4_mt<8>, dim3(q_gate_up_blocks(8)), dim3(512), s, x, T, d, G, w.gate_codes,
                      w.gate_scales, w.up_codes, w.up_scales, mask, act, ffn, ap);
-    static const hipError_t lds_ok = hipFuncSetAttribute(reinterpret_cast<const void *>(down_q4_mt),
-                                                         hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                         (int)q_down_lds_bytes(16));
-    if (lds_ok != hipSuccess) return lds_ok;
-    down_q4_mt<<<dim3(d / 16 + n_mask), dim3(256), q_down_lds_bytes(T), s>>>(T, d, G, w.down_codes, w.down_scales,
-                                                                            mask, act, ffn, y, n_mask, nx);
+    const dim3 dgrid(d / 16 + n_mask), dblock(256);
+    const size_t dlds = q_down_lds_bytes(T);
+#define HALO_DOWN_Q4(TM)                                                                                         \
+    do {                                                                                                         \
+        static const hipError_t lds_ok = hipFuncSetAttribute(reinterpret_cast<const void *>(down_q4_mt<TM>),     \
+                                                             hipFuncAttributeMaxDynamicSharedMemorySize,         \
+                                                             (int)q_down_lds_bytes(16));                         \
+        if (lds_ok != hipSuccess) return lds_ok;                                                                 \
+        down_q4_mt<TM><<<dgrid, dblock, dlds, s>>>(T, d, G, w.down_codes, w.down_scales, mask, act, ffn, y, n_mask, nx); \
+    } while (0)
+    if (T <= 4)
+        HALO_DOWN_Q4(4);
+    else if (T <= 8)
+        HALO_DOWN_Q4(8);
+    else
+        HALO_DOWN_Q4(16);
+#undef HALO_DOWN_Q4
     return hipGetLastError();
 }
 
