@@ -421,36 +421,42 @@ __global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void gate_up_q4_mt(
 }
 
 // ---------------------------------------------------------------------------
-// down.  grid: d/16 (+ n_mask) workgroups of 256 threads.  A workgroup owns 16 output rows; a group's
-// 16 x 128 tile of codes is 1 KiB of consecutive bytes = one load per lane (row i, codes 32q..32q+31).
-// The four waves split the union's groups, four groups per batch.  While a batch is multiplied the next
-// batch's codes, scales and activations are on their way, the activations (T rows of 4 x 128 values,
-// consecutive in the compact layout) into registers; they are written to the wave's private LDS region,
-// from where they are read in operand order, once the multiplication is done with the region.  (With one
-// batch at a time -- loads, wait, activations, wait, multiply -- a wave waited for memory three times per
-// eight groups and the kernel ran at 1.5 TB/s.)
+// down.  A workgroup owns 16 * TILES output rows; a group's 16 x 128 tile of codes is 1 KiB of consecutive
+// bytes = one load per lane (row i, codes 32q..32q+31).  The waves split the union's groups, four groups per
+// batch.  While a batch is multiplied the next batch's codes, scales and activations are on their way, the
+// activations (T rows of 4 x 128 values, consecutive in the compact layout) into registers; they are
+// written to the wave's private LDS region, from where they are read in operand order, once the
+// multiplication is done with the region.  (With one batch at a time -- loads, wait, activations, wait,
+// multiply -- a wave waited for memory three times per eight groups and the kernel ran at 1.5 TB/s.)
+// Every workgroup reads all of the tokens' activations, T * 256 bytes per group beside the 1 KiB of codes
+// of a 16-row tile: with eight tokens that is twice the codes' bytes, and the loads a compute unit can
+// have in flight are what bounds the kernel.  TILES = 2 (eight waves, 32 rows: long rows, d >= 8192, where
+// d/32 workgroups still cover the chip) uses every activation byte for two tiles.
 // TMAX: the token rows a wave fetches per batch (rows past T repeat the last token's, unused): fixed at
 // compile time so that every load is issued unconditionally and the compiler can count the loads in flight.
+// grid: d / (16 * TILES) (+ n_mask) workgroups of 64 * WAVES threads.
 // ---------------------------------------------------------------------------
 constexpr int kQDownGroups = 4;
 constexpr int kQActPitch = kQDownGroups * 256 + 16;     // bytes per token row of a batch (16 mod 256)
 
-// dynamic LDS of the kernel: [red: 4 x 64 x 4 floats][list: 256 ints][activations: 4 waves x T rows of
-// kQActPitch bytes]; the mask workgroups use the same bytes as a MaskShared
-constexpr size_t kQDownFixed = 4 * 64 * 4 * sizeof(float) + 256 * sizeof(int);
-inline size_t q_down_lds_bytes(int T)
+// dynamic LDS of the kernel: [list: 256 ints][activations: WAVES x T rows of kQActPitch bytes]; at the end a
+// wave's partial sums (64 x 4 TILES floats <= 2 rows) take the place of its activations; the mask
+// workgroups use the same bytes as a MaskShared
+constexpr size_t kQDownFixed = 256 * sizeof(int);
+inline size_t q_down_lds_bytes(int T, int waves)
 {
-    const size_t need = kQDownFixed + (size_t)4 * T * kQActPitch;
+    const size_t need = kQDownFixed + (size_t)waves * T * kQActPitch;
     return need > sizeof(MaskShared) ? need : sizeof(MaskShared);
 }
 
+template <int TILES>
 struct DownBatch {
-    u32x4 r[kQDownGroups];                  // codes of the batch's groups: row i of the tile, codes 32q..32q+31
-    uint2 sc[kQDownGroups];                 // scales of rows 4q .. 4q+3
+    u32x4 r[TILES][kQDownGroups];           // codes of the batch's groups: row i of each tile, codes 32q..32q+31
+    uint2 sc[TILES][kQDownGroups];          // scales of rows 4q .. 4q+3 of each tile
 };
 
-template <int TMAX>
-__global__ __launch_bounds__(256) void down_q4_mt(
+template <int TMAX, int TILES, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void down_q4_mt(
     int T, int d, int G, const uint32_t *__restrict__ Dq, const bf16_t *__restrict__ Ds,
     const uint8_t *__restrict__ mask, const bf16_t *__restrict__ act, int act_stride, bf16_t *__restrict__ y,
     int n_mask, AheadDev nx)
@@ -461,45 +467,48 @@ __global__ __launch_bounds__(256) void down_q4_mt(
         // paper Sec. III-B.3, one layer ahead: second predictor layer, ranking and mask of the next
         // block for token blockIdx.x (dispatched first: it is the longest dependent chain)
         const int t = blockIdx.x;
-        mask_scores_block<256, bf16_t, true>(*reinterpret_cast<MaskShared *>(lds), threadIdx.x, nx.h + (size_t)t * nx.r,
-                                             nx.Bt, nx.r, nx.scores + (size_t)t * G, G, nx.K, nx.prio_dev, nx.n_dev,
-                                             nx.drop ? nx.drop + (size_t)t * nx.n_dev : nullptr,
-                                             nx.order ? nx.order + (size_t)t * G : nullptr,
-                                             nx.group_dev ? nx.group_dev + (size_t)t * G : nullptr,
-                                             nx.mask + (size_t)t * G,
-                                             nx.surv_idx ? nx.surv_idx + (size_t)t * nx.K : nullptr,
-                                             nx.n_surv ? nx.n_surv + t : nullptr);
+        mask_scores_block<WAVES * 64, bf16_t, true>(
+            *reinterpret_cast<MaskShared *>(lds), threadIdx.x, nx.h + (size_t)t * nx.r, nx.Bt, nx.r,
+            nx.scores + (size_t)t * G, G, nx.K, nx.prio_dev, nx.n_dev, nx.drop ? nx.drop + (size_t)t * nx.n_dev : nullptr,
+            nx.order ? nx.order + (size_t)t * G : nullptr, nx.group_dev ? nx.group_dev + (size_t)t * G : nullptr,
+            nx.mask + (size_t)t * G, nx.surv_idx ? nx.surv_idx + (size_t)t * nx.K : nullptr,
+            nx.n_surv ? nx.n_surv + t : nullptr);
         return;
     }
     const Q4Consts qk = q4_consts();
-    float(*red)[64][4] = reinterpret_cast<float(*)[64][4]>(lds);
-    int *s_list = reinterpret_cast<int *>(lds + 4 * 64 * 4 * sizeof(float));
+    static_assert(64 * 4 * TILES * sizeof(float) <= 2 * kQActPitch, "a wave's partial sums fit in its region (T >= 2)");
+    int *s_list = reinterpret_cast<int *>(lds);
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int i = lane & 15, q = lane >> 4;
-    const int j0 = (blockIdx.x - n_mask) * 16;
+    const int j0 = (blockIdx.x - n_mask) * 16 * TILES;
     const MaskWords uw = load_union_words<16>(mask, T, G, lane);
     if (wave == 0) write_group_list(uw, lane, s_list);
     __syncthreads();
     const int n_u = uw.count;
-    const int u0 = n_u * wave / 4, u1 = n_u * (wave + 1) / 4;
+    const int u0 = n_u * wave / WAVES, u1 = n_u * (wave + 1) / WAVES;
     const int nbat = (u1 - u0 + kQDownGroups - 1) / kQDownGroups;
     const int tok = i < T ? i : T - 1;
     const size_t gwords = (size_t)d * (gs / 8);                      // words per group
-    const uint32_t *ctile = Dq + (size_t)(j0 + i) * (gs / 8) + q * 4;   // row i of the tile, codes 32q..32q+31
+    const uint32_t *ctile = Dq + (size_t)(j0 + i) * (gs / 8) + q * 4;   // row i of the first tile, codes 32q..32q+31
     unsigned char *mine = lds + kQDownFixed + (size_t)wave * T * kQActPitch;
     const unsigned char *al = mine + tok * kQActPitch + q * 64;      // + (group in batch) * 256 + s * 16
-    f32x4_t c = {0.f, 0.f, 0.f, 0.f};
+    f32x4_t c[TILES];
+#pragma unroll
+    for (int tl = 0; tl < TILES; ++tl) c[tl] = f32x4_t{0.f, 0.f, 0.f, 0.f};
     // batch b of the wave's share: groups u0 + 4b .., those past the end of the share repeat its last one
     // (in range, unused).  A token's row of the batch is 4 groups x 16 pieces = one piece per lane.
     u32x4 av[TMAX];
-    auto issue = [&](DownBatch &B, int b) {
+    auto issue = [&](DownBatch<TILES> &B, int b) {
         const int ub = u0 + b * kQDownGroups;
 #pragma unroll
         for (int k = 0; k < kQDownGroups; ++k) {
             const int g = s_list[min(ub + k, u1 - 1)];
-            B.r[k] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(ctile + g * gwords));
-            B.sc[k] = *reinterpret_cast<const uint2 *>(Ds + (size_t)g * d + j0 + 4 * q);   // scales of rows 4q..4q+3
+#pragma unroll
+            for (int tl = 0; tl < TILES; ++tl) {
+                B.r[tl][k] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(ctile + g * gwords + tl * 16 * (gs / 8)));
+                B.sc[tl][k] = *reinterpret_cast<const uint2 *>(Ds + (size_t)g * d + j0 + 16 * tl + 4 * q);   // rows 4q..4q+3
+            }
         }
         const int un = min(ub + (lane >> 4), u1 - 1);                // position in the union of this lane's piece
 #pragma unroll
@@ -512,35 +521,38 @@ __global__ __launch_bounds__(256) void down_q4_mt(
         for (int t = 0; t < TMAX; ++t)
             if (t < T) *reinterpret_cast<u32x4 *>(mine + t * kQActPitch + lane * 16) = av[t];
     };
-    auto multiply = [&](const DownBatch &B, int nb) {
+    auto multiply = [&](const DownBatch<TILES> &B, int nb) {
 #pragma unroll
         for (int k = 0; k < kQDownGroups; ++k) {
             if (k < nb) {                                            // uniform
                 u32x4 b[4];
 #pragma unroll
                 for (int s = 0; s < 4; ++s) b[s] = *reinterpret_cast<const u32x4 *>(al + k * 256 + s * 16);
-                f32x4_t t0 = {0.f, 0.f, 0.f, 0.f}, t1 = {0.f, 0.f, 0.f, 0.f};
                 float asum = 0.0f;
-                t0 = mfma16q(q4_word_bf16(B.r[k].x, qk), b[0], t0);
-                t1 = mfma16q(q4_word_bf16(B.r[k].y, qk), b[1], t1);
-                t0 = mfma16q(q4_word_bf16(B.r[k].z, qk), b[2], t0);
-                t1 = mfma16q(q4_word_bf16(B.r[k].w, qk), b[3], t1);
 #pragma unroll
                 for (int s = 0; s < 4; ++s) asum = sum8(b[s], asum);
-                const f32x4_t t = t0 + t1;
                 // the four lanes of a token (one per q) hold its 128 activations between them
                 asum += __shfl_xor(asum, 16);
                 asum += __shfl_xor(asum, 32);
                 const float xo = 136.0f * asum;
-                c[0] = __builtin_fmaf(bf16_lo(B.sc[k].x), t[0] - xo, c[0]);
-                c[1] = __builtin_fmaf(bf16_hi(B.sc[k].x), t[1] - xo, c[1]);
-                c[2] = __builtin_fmaf(bf16_lo(B.sc[k].y), t[2] - xo, c[2]);
-                c[3] = __builtin_fmaf(bf16_hi(B.sc[k].y), t[3] - xo, c[3]);
+#pragma unroll
+                for (int tl = 0; tl < TILES; ++tl) {
+                    f32x4_t t0 = {0.f, 0.f, 0.f, 0.f}, t1 = {0.f, 0.f, 0.f, 0.f};
+                    t0 = mfma16q(q4_word_bf16(B.r[tl][k].x, qk), b[0], t0);
+                    t1 = mfma16q(q4_word_bf16(B.r[tl][k].y, qk), b[1], t1);
+                    t0 = mfma16q(q4_word_bf16(B.r[tl][k].z, qk), b[2], t0);
+                    t1 = mfma16q(q4_word_bf16(B.r[tl][k].w, qk), b[3], t1);
+                    const f32x4_t t = t0 + t1;
+                    c[tl][0] = __builtin_fmaf(bf16_lo(B.sc[tl][k].x), t[0] - xo, c[tl][0]);
+                    c[tl][1] = __builtin_fmaf(bf16_hi(B.sc[tl][k].x), t[1] - xo, c[tl][1]);
+                    c[tl][2] = __builtin_fmaf(bf16_lo(B.sc[tl][k].y), t[2] - xo, c[tl][2]);
+                    c[tl][3] = __builtin_fmaf(bf16_hi(B.sc[tl][k].y), t[3] - xo, c[tl][3]);
+                }
             }
         }
     };
     if (nbat > 0) {                                                  // uniform per wave; no barrier inside
-        DownBatch cur, nxt;
+        DownBatch<TILES> cur, nxt;
         issue(cur, 0);
         store_act();
         for (int b = 0; b + 1 < nbat; ++b) {
@@ -551,14 +563,20 @@ __global__ __launch_bounds__(256) void down_q4_mt(
         }
         multiply(cur, u1 - u0 - (nbat - 1) * kQDownGroups);
     }
+    // a wave's partial sums go where its activations were (its own region, it is done with them)
+    auto red = [&](int w) { return reinterpret_cast<float *>(lds + kQDownFixed + (size_t)w * T * kQActPitch) + lane * 4 * TILES; };
 #pragma unroll
-    for (int rr = 0; rr < 4; ++rr) red[wave][lane][rr] = c[rr];
+    for (int tl = 0; tl < TILES; ++tl)
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) red(wave)[4 * tl + rr] = c[tl][rr];
     __syncthreads();
-    if (wave == 0 && i < T) {
+    if (wave < TILES && i < T) {                                     // wave tl finishes tile tl
 #pragma unroll
         for (int rr = 0; rr < 4; ++rr) {
-            const float v = ((red[0][lane][rr] + red[1][lane][rr]) + red[2][lane][rr]) + red[3][lane][rr];
-            y[(size_t)i * d + j0 + 4 * q + rr] = f32_to_bf16(v);
+            float v = red(0)[4 * wave + rr];
+#pragma unroll
+            for (int w = 1; w < WAVES; ++w) v += red(w)[4 * wave + rr];
+            y[(size_t)i * d + j0 + 16 * wave + 4 * q + rr] = f32_to_bf16(v);
         }
     }
 }
@@ -587,22 +605,32 @@ hipError_t launch_ffn_q4_mfma(const bf16_t *x, int T, int d, int G, const Q4Weig
     else
         launch_timed("gate_up_q4_mt", gate_up_q4_mt<8>, dim3(q_gate_up_blocks(8)), dim3(512), s, x, T, d, G, w.gate_codes,
                      w.gate_scales, w.up_codes, w.up_scales, mask, act, ffn, ap);
-    const dim3 dgrid(d / 16 + n_mask), dblock(256);
-    const size_t dlds = q_down_lds_bytes(T);
-#define HALO_DOWN_Q4(TM)                                                                                         \
+    // long rows: 32 rows to a workgroup of eight waves, so that the activations are read half as often
+    const bool wide = d >= 8192 && d % 32 == 0;
+#define HALO_DOWN_Q4(TM, TILES, WAVES)                                                                           \
     do {                                                                                                         \
-        static const hipError_t lds_ok = hipFuncSetAttribute(reinterpret_cast<const void *>(down_q4_mt<TM>),     \
-                                                             hipFuncAttributeMaxDynamicSharedMemorySize,         \
-                                                             (int)q_down_lds_bytes(16));                         \
+        static const hipError_t lds_ok = hipFuncSetAttribute(                                                    \
+            reinterpret_cast<const void *>(down_q4_mt<TM, TILES, WAVES>), hipFuncAttributeMaxDynamicSharedMemorySize, \
+            (int)q_down_lds_bytes(16, WAVES));                                                            \
         if (lds_ok != hipSuccess) return lds_ok;                                                                 \
-        down_q4_mt<TM><<<dgrid, dblock, dlds, s>>>(T, d, G, w.down_codes, w.down_scales, mask, act, ffn, y, n_mask, nx); \
+        down_q4_mt<TM, TILES, WAVES><<<dim3(d / (16 * TILES) + n_mask), dim3(WAVES * 64), q_down_lds_bytes(T, WAVES), s>>>( \
+            T, d, G, w.down_codes, w.down_scales, mask, act, ffn, y, n_mask, nx);                                \
     } while (0)
-    if (T <= 4)
-        HALO_DOWN_Q4(4);
-    else if (T <= 8)
-        HALO_DOWN_Q4(8);
-    else
-        HALO_DOWN_Q4(16);
+    if (wide) {
+        if (T <= 4)
+            HALO_DOWN_Q4(4, 2, 8);
+        else if (T <= 8)
+            HALO_DOWN_Q4(8, 2, 8);
+        else
+            HALO_DOWN_Q4(16, 2, 8);
+    } else {
+        if (T <= 4)
+            HALO_DOWN_Q4(4, 1, 4);
+        else if (T <= 8)
+            HALO_DOWN_Q4(8, 1, 4);
+        else
+            HALO_DOWN_Q4(16, 1, 4);
+    }
 #undef HALO_DOWN_Q4
     return hipGetLastError();
 }
