@@ -294,10 +294,13 @@ def main_stack(args, w):
     t_gen = time.perf_counter()
     layers = []
     for l in range(L):
-        Wg, Wu, WdT = hs.ffn_weights(w, l, dev)
         At, Bt = hs.predictor_weights(w, l, dev)
-        layers.append((At, Bt, Wg, Wu, H.pack_down_proj(WdT, w.group_size)))
-        del WdT
+        if args.q4:                                   # (At, Bt, the six code / scale arrays)
+            layers.append((At, Bt, hs.ffn_weights_q4(w, l, dev)))
+        else:
+            Wg, Wu, WdT = hs.ffn_weights(w, l, dev)
+            layers.append((At, Bt, Wg, Wu, H.pack_down_proj(WdT, w.group_size)))
+            del WdT
         if l % 10 == 9:
             print(f"[bench] generated {l + 1} of {L} layers, {torch.cuda.memory_allocated() / 1e9:.1f} GB resident",
                   file=sys.stderr, flush=True)
@@ -321,6 +324,16 @@ def main_stack(args, w):
         h.copy_(h0[s])
         H.halo_stack_residual_norm(h, None, xbuf[0], stream=st)
         for l in range(L):
+            if args.q4:
+                q4 = layers[l][2]
+                if l + 1 < L:
+                    At, Bt = layers[l + 1][:2]
+                    H.halo_ffn_forward_ahead_q4(shape, xbuf[l], q4, masks[s, l], ybuf[l], xbuf[l], At, Bt, k_keep,
+                                                prio_dev, w.n_dev, drops[s, l + 1], masks[s, l + 1], ws, stream=st)
+                else:
+                    H.halo_group_sparse_ffn_q4(shape, xbuf[l], q4, masks[s, l], ybuf[l], ws, stream=st)
+                H.halo_stack_residual_norm(h, ybuf[l], xbuf[l + 1], stream=st)
+                continue
             _, _, Wg, Wu, Wd = layers[l]
             if l + 1 < L:
                 At, Bt = layers[l + 1][:2]
@@ -339,7 +352,7 @@ def main_stack(args, w):
     def enqueue():
         for s in range(W, W + K):
             stack_pass(s)
-    per_layer_est = {5120: 60.0, 8192: 235.0}.get(d, 100.0)
+    per_layer_est = {5120: 60.0, 8192: 235.0}.get(d, 100.0) * (0.55 if args.q4 else 1.0)
     elapsed, times, reps = timed_graph(torch, st, enqueue, K, per_layer_est * L, args.replays, not args.no_graph)
     h_timed = h_out[W:W + K].clone()
 
@@ -358,6 +371,8 @@ def main_stack(args, w):
     union = mask_np.any(axis=2).sum(axis=2)                     # [K][L] groups read per layer
     n_surv = mask_np.sum(axis=3)                                # [K][L][T]
     group_bytes = w.group_size * d * esz
+    if args.q4:                                                 # codes + one bf16 scale per 128 elements
+        group_bytes = w.group_size * (d // 2 + (d // 128) * 2)
     ffn_bytes = float(union.sum()) * 3 * group_bytes
     flat_union = union.reshape(-1)                              # launch order: step-major, layer-minor
     timed_union = flat_union[::every][:kern_n]
@@ -365,11 +380,11 @@ def main_stack(args, w):
     achieved = gate_up_bytes / (kern_ms * 1e-3) / 1e9 if kern_ms > 0 else 0.0
     ceil = measured_ceilings(torch, H, st, float(union[:, 1:].mean()) * 2 * group_bytes, False)
     out = {
-        "metric": f"FFN-stack tokens/s (decode), {w.name}: {L} layers resident, keep {keep}",
+        "metric": f"FFN-stack tokens/s (decode), {w.name}: {L} layers resident, keep {keep}" + (", 4-bit weights" if args.q4 else ""),
         "value": K * T / elapsed, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": elapsed / K * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": w.dtype, "data": "synthetic",
-        "config": {"workload": w.name + "_full_stack", "d": d, "ffn": w.ffn, "n_groups": G, "group_size": w.group_size,
+        "dtype": w.dtype + (" activations, 4-bit block-quantised FFN weights" if args.q4 else ""), "data": "synthetic",
+        "config": {"workload": w.name + "_full_stack" + ("_q4" if args.q4 else ""), "d": d, "ffn": w.ffn, "n_groups": G, "group_size": w.group_size,
                    "rank": w.rank, "tokens_per_step": T, "layers": L, "keep": keep, "k_keep": k_keep,
                    "n_dev": w.n_dev, "plr": [float(v) for v in w.device_plr()], "seed": w.seed,
                    "resident_GB": torch.cuda.memory_allocated() / 1e9, "graph": not args.no_graph,
@@ -384,7 +399,7 @@ def main_stack(args, w):
                        "frac_of_measured_stream": ffn_bytes / elapsed / 1e9 / ceil["read_stream_GBps"],
                        "graph_equals_eager": same},
         "roofline": {"bound": "hbm", "kernel": kern_name, "achieved": achieved, "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": read_traffic(kern_name, w.name),
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": read_traffic(kern_name, w.name + ("_q4" if args.q4 else "")),
                      "launches": int(kern_n), "avg_us": kern_ms / max(kern_n, 1) * 1e3,
                      "bytes_per_launch": gate_up_bytes / max(kern_n, 1),
                      "measured_peak": ceil["read_stream_GBps"],
@@ -404,9 +419,15 @@ def main_stack(args, w):
         check = sorted({1, L // 2})
         cpu_t, worst, masks_ok = 0.0, 0.0, True
         for l in check:
-            At, Bt, Wg, Wu, Wd = layers[l]
-            WdT = Wd.permute(0, 2, 1).reshape(w.ffn, d)           # back to neuron-major for the oracle
-            host = [t.float().cpu().numpy() for t in (At, Bt, Wg, Wu, WdT)]
+            if args.q4:
+                At, Bt, q4 = layers[l]
+                host = [At.float().cpu().numpy(), Bt.float().cpu().numpy(),
+                        *ref.dequant_ffn_q4([t.float().cpu().numpy() if t.dtype == torch.bfloat16 else t.cpu().numpy()
+                                             for t in q4])]
+            else:
+                At, Bt, Wg, Wu, Wd = layers[l]
+                WdT = Wd.permute(0, 2, 1).reshape(w.ffn, d)       # back to neuron-major for the oracle
+                host = [t.float().cpu().numpy() for t in (At, Bt, Wg, Wu, WdT)]
             t0 = time.perf_counter()
             sc = ref.predict_scores(x_np[l - 1], host[0], host[1])
             m = ref.build_group_mask(sc, k_keep, prio_dev_np, w.n_dev, drops_np[s, l])
@@ -434,7 +455,7 @@ def main():
     ap.add_argument("--copies", type=int, default=16, help="independent weight copies rotated over")
     ap.add_argument("--workload", default="llama7b_decode")
     ap.add_argument("--stack", action="store_true",
-                    help="llama13b_stack / llama70b_stack: a step is the whole stack with every layer resident")
+                    help="llama13b_stack / llama70b_stack: a step is the whole stack with every layer resident (bf16, or 4-bit with --q4)")
     ap.add_argument("--keep", type=float, default=None, help="keep ratio (default: the workload's first)")
     ap.add_argument("--no-graph", action="store_true", help="launch the timed steps eagerly")
     ap.add_argument("--serial", action="store_true",
@@ -496,8 +517,8 @@ def main():
         return
     w = hs.BY_NAME[args.workload]
     if args.stack:
-        if w.layers < 2 or args.q4 or args.serial:
-            print("bench.py: --stack needs a multi-layer workload (bf16 weights, overlapped form)", file=sys.stderr)
+        if w.layers < 2 or args.serial:
+            print("bench.py: --stack needs a multi-layer workload (overlapped form)", file=sys.stderr)
             sys.exit(2)
         main_stack(args, w)
         return
