@@ -176,9 +176,10 @@ def stack_check_layers(w, n_random):
     return sorted(fixed | set(picked))
 
 
-def run_stack_gpu(w, keep, layers=None, check_layers=(), on_layer=None):
+def run_stack_gpu(w, keep, layers=None, check_layers=(), on_layer=None, q4=False):
     """Free-running stack on the GPU with the predictor one layer ahead (layer l+1's mask is
     predicted from layer l's input, as in the paper); layer 0 runs dense and lossless.
+    q4: the layers' FFN weights are 4-bit block-quantised and the `_q4` entry points run.
     For each layer of check_layers, on_layer(l, rec, pd_np, K) is called with
     rec = dict(x, x_prev, y, mask, drop, host) (host copies) while the run goes on -- records
     are not kept, a 70B layer is 2.8 GB as float32.  Returns the final residual stream."""
@@ -191,17 +192,24 @@ def run_stack_gpu(w, keep, layers=None, check_layers=(), on_layer=None):
     ws = torch.empty(H.halo_workspace_bytes(s, T, G), dtype=torch.uint8, device=DEV)
     h = hs.hidden_states(w, 0, DEV, dtype=torch.float32)
     mask = torch.ones((T, G), dtype=torch.uint8, device=DEV)          # layer 0: every group, no loss
-    cur = Layer(w, 0)
+    make = Q4Layer if q4 else Layer
+    cur = make(w, 0)
     x_prev = None
     for l in range(n_layers):
-        nxt = Layer(w, l + 1) if l + 1 < n_layers else None
+        nxt = make(w, l + 1) if l + 1 < n_layers else None
         x = rms_norm(h).to(w.torch_dtype)
         y = torch.empty((T, w.d), dtype=w.torch_dtype, device=DEV)
         if nxt is not None:
             drop_next = hs.drop_outcomes(w, l + 1, 0)
             mask_next = torch.empty((T, G), dtype=torch.uint8, device=DEV)
-            H.halo_ffn_forward_ahead(s, x, cur.Wg, cur.Wu, cur.Wd, mask, y, x, nxt.At, nxt.Bt, K, pd,
-                                     w.n_dev, torch.from_numpy(drop_next).to(DEV), mask_next, ws)
+            if q4:
+                H.halo_ffn_forward_ahead_q4(s, x, cur.q4, mask, y, x, nxt.At, nxt.Bt, K, pd, w.n_dev,
+                                            torch.from_numpy(drop_next).to(DEV), mask_next, ws)
+            else:
+                H.halo_ffn_forward_ahead(s, x, cur.Wg, cur.Wu, cur.Wd, mask, y, x, nxt.At, nxt.Bt, K, pd,
+                                         w.n_dev, torch.from_numpy(drop_next).to(DEV), mask_next, ws)
+        elif q4:
+            H.halo_group_sparse_ffn_q4(s, x, cur.q4, mask, y, ws)
         else:
             H.halo_group_sparse_ffn(s, x, cur.Wg, cur.Wu, cur.Wd, mask, y, ws)
         torch.cuda.synchronize()

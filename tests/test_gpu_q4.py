@@ -210,3 +210,22 @@ def test_q4_llama7b_prefill_all_tokens():
     g = hz.gpu_forward_q4(w, L, x, K, pd, drop)
     c = hz.oracle_forward(w, L, x, K, pd, drop)
     hz.assert_parity(g, c, TOL["bf16"], "q4 7B prefill")
+
+
+@pytest.mark.parametrize("wl,keep,layers", [(hs.LLAMA13B_STACK, 0.3, None), (hs.LLAMA70B_STACK, 0.5, 6)])
+def test_q4_stack_teacher_forced(wl, keep, layers):
+    # the free-running stack over 4-bit weights, predictor one layer ahead (layer 0 dense: every group of
+    # every token, so the few-token kernels walk several tiles per workgroup); checked layers are compared
+    # with the oracle fed the GPU's own layer inputs
+    n = wl.layers if layers is None else layers
+    check = sorted({0, 1, 2, n // 2, n - 1})
+    _say(f"q4 {wl.name} stack of {n} layers, checked {check}")
+    seen = []
+
+    def on_layer(l, rec, pd_np, K):
+        hz.check_stack_layer(wl, l, rec, pd_np, K, TOL["bf16"])
+        seen.append(l)
+        print(f"  layer {l} ok", flush=True)
+    h = hz.run_stack_gpu(wl, keep, layers=layers, check_layers=check, on_layer=on_layer, q4=True)
+    assert torch.isfinite(h).all() and seen == check
+
