@@ -498,12 +498,15 @@ __global__ __launch_bounds__(WAVES * 64) void down_q4_mt(
     for (int tl = 0; tl < TILES; ++tl) c[tl] = f32x4_t{0.f, 0.f, 0.f, 0.f};
     // batch b of the wave's share: groups u0 + 4b .., those past the end of the share repeat its last one
     // (in range, unused).  A token's row of the batch is 4 groups x 16 pieces = one piece per lane.
-    u32x4 av[TMAX];
-    auto issue = [&](DownBatch<TILES> &B, int b) {
+    // the wave's groups (at most 64: G <= 256 over at least four waves), one to a lane: a batch's group ids
+    // come out of this register into scalar registers, where reading the list from LDS put a dependent LDS
+    // round trip and vector address arithmetic in front of every batch's loads (0.6 us per batch of four)
+    const int my_group = s_list[min(u0 + lane, max(u1 - 1, 0))];
+    auto issue = [&](DownBatch<TILES> &B, u32x4 (&av)[TMAX], int b) {
         const int ub = u0 + b * kQDownGroups;
 #pragma unroll
         for (int k = 0; k < kQDownGroups; ++k) {
-            const int g = s_list[min(ub + k, u1 - 1)];
+            const int g = __builtin_amdgcn_readlane(my_group, min(ub + k, u1 - 1) - u0);
 #pragma unroll
             for (int tl = 0; tl < TILES; ++tl) {
                 B.r[tl][k] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(ctile + g * gwords + tl * 16 * (gs / 8)));
@@ -516,7 +519,7 @@ __global__ __launch_bounds__(WAVES * 64) void down_q4_mt(
             av[t] = *reinterpret_cast<const u32x4 *>(act + (size_t)min(t, T - 1) * act_stride + (size_t)un * gs + (lane & 15) * 8);
     };
     // the region is the wave's own and LDS operations of a wave complete in order, so no barrier is needed
-    auto store_act = [&]() {
+    auto store_act = [&](const u32x4 (&av)[TMAX]) {
 #pragma unroll
         for (int t = 0; t < TMAX; ++t)
             if (t < T) *reinterpret_cast<u32x4 *>(mine + t * kQActPitch + lane * 16) = av[t];
@@ -528,13 +531,17 @@ __global__ __launch_bounds__(WAVES * 64) void down_q4_mt(
                 u32x4 b[4];
 #pragma unroll
                 for (int s = 0; s < 4; ++s) b[s] = *reinterpret_cast<const u32x4 *>(al + k * 256 + s * 16);
-                float asum = 0.0f;
-#pragma unroll
-                for (int s = 0; s < 4; ++s) asum = sum8(b[s], asum);
-                // the four lanes of a token (one per q) hold its 128 activations between them
-                asum += __shfl_xor(asum, 16);
-                asum += __shfl_xor(asum, 32);
-                const float xo = 136.0f * asum;
+                // the sum of the token's 128 activations of the group, for the offset: the same matrix
+                // instructions with 1.0 in every element of the other operand (every row of the result is the
+                // sum).  Summing the lane's 32 values and exchanging between the token's four lanes was a
+                // chain of two lane-crossing round trips per group, in a loop that has nothing to hide them.
+                const u32x4 ones = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
+                f32x4_t ts0 = {0.f, 0.f, 0.f, 0.f}, ts1 = {0.f, 0.f, 0.f, 0.f};
+                ts0 = mfma16q(ones, b[0], ts0);
+                ts1 = mfma16q(ones, b[1], ts1);
+                ts0 = mfma16q(ones, b[2], ts0);
+                ts1 = mfma16q(ones, b[3], ts1);
+                const float xo = 136.0f * (ts0[0] + ts1[0]);
 #pragma unroll
                 for (int tl = 0; tl < TILES; ++tl) {
                     f32x4_t t0 = {0.f, 0.f, 0.f, 0.f}, t1 = {0.f, 0.f, 0.f, 0.f};
@@ -553,12 +560,13 @@ __global__ __launch_bounds__(WAVES * 64) void down_q4_mt(
     };
     if (nbat > 0) {                                                  // uniform per wave; no barrier inside
         DownBatch<TILES> cur, nxt;
-        issue(cur, 0);
-        store_act();
+        u32x4 av[TMAX];
+        issue(cur, av, 0);
+        store_act(av);
         for (int b = 0; b + 1 < nbat; ++b) {
-            issue(nxt, b + 1);
+            issue(nxt, av, b + 1);
             multiply(cur, kQDownGroups);
-            store_act();
+            store_act(av);
             cur = nxt;
         }
         multiply(cur, u1 - u0 - (nbat - 1) * kQDownGroups);
