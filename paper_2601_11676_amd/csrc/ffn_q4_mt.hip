@@ -16,6 +16,8 @@
 //     acc += s * (t - 136 * sum x)         since  s * sum (c - 8) x = s * (sum (128 + c) x - 136 sum x).
 // The token side (x, or the activations) is staged in LDS with coalesced loads and read from there in
 // operand order.  D: lane l holds column l%16, rows 4*(l/16)..+3.
+#include <type_traits>
+
 #include "kernels.hpp"
 #include "mask_device.hpp"
 #include "mask_words.hpp"
@@ -436,32 +438,40 @@ __global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void gate_up_q4_mt(
 // compile time so that every load is issued unconditionally and the compiler can count the loads in flight.
 // grid: d / (16 * TILES) (+ n_mask) workgroups of 64 * WAVES threads.
 // ---------------------------------------------------------------------------
-constexpr int kQDownGroups = 4;
-constexpr int kQActPitch = kQDownGroups * 256 + 16;     // bytes per token row of a batch (16 mod 256)
-
-// dynamic LDS of the kernel: [list: 256 ints][activations: WAVES x T rows of kQActPitch bytes]; at the end a
-// wave's partial sums (64 x 4 TILES floats <= 2 rows) take the place of its activations; the mask
+// dynamic LDS of the kernel: [list: 256 ints][activations: WAVES x T rows of GB * 256 + 16 bytes (16 mod 256)];
+// at the end a wave's partial sums (64 x 4 TILES floats <= 2 rows) take the place of its activations; the mask
 // workgroups use the same bytes as a MaskShared
 constexpr size_t kQDownFixed = 256 * sizeof(int);
-inline size_t q_down_lds_bytes(int T, int waves)
+constexpr int q_act_pitch(int gb) { return gb * 256 + 16; }
+// a wave's region: its T activation rows, and room for its partial sums
+__host__ __device__ inline size_t q_down_region(int T, int gb, int tiles)
 {
-    const size_t need = kQDownFixed + (size_t)waves * T * kQActPitch;
+    const size_t rows = (size_t)T * q_act_pitch(gb), sums = (size_t)64 * 4 * tiles * sizeof(float);
+    return rows > sums ? rows : sums;
+}
+inline size_t q_down_lds_bytes(int T, int waves, int gb, int tiles)
+{
+    const size_t need = kQDownFixed + (size_t)waves * q_down_region(T, gb, tiles);
     return need > sizeof(MaskShared) ? need : sizeof(MaskShared);
 }
 
-template <int TILES>
+template <int TILES, int GB>
 struct DownBatch {
-    u32x4 r[TILES][kQDownGroups];           // codes of the batch's groups: row i of each tile, codes 32q..32q+31
-    uint2 sc[TILES][kQDownGroups];          // scales of rows 4q .. 4q+3 of each tile
+    u32x4 r[TILES][GB];                     // codes of the batch's groups: row i of each tile, codes 32q..32q+31
+    uint2 sc[TILES][GB];                    // scales of rows 4q .. 4q+3 of each tile
 };
 
-template <int TMAX, int TILES, int WAVES>
+// GB: groups per batch (4; 2 in the 32-row form, whose registers then leave room for two workgroups of
+// eight waves on a compute unit: with one, the mask workgroups in front of the grid held eight units for
+// themselves and as many projection workgroups started when they were done).
+template <int TMAX, int TILES, int WAVES, int GB>
 __global__ __launch_bounds__(WAVES * 64) void down_q4_mt(
     int T, int d, int G, const uint32_t *__restrict__ Dq, const bf16_t *__restrict__ Ds,
     const uint8_t *__restrict__ mask, const bf16_t *__restrict__ act, int act_stride, bf16_t *__restrict__ y,
     int n_mask, AheadDev nx)
 {
-    constexpr int gs = 128;
+    constexpr int gs = 128, kPitch = q_act_pitch(GB);
+    constexpr int kLanesPerToken = GB * 16, kTokPerLoad = 64 / kLanesPerToken, kActLoads = (TMAX + kTokPerLoad - 1) / kTokPerLoad;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     if ((int)blockIdx.x < n_mask) {
         // paper Sec. III-B.3, one layer ahead: second predictor layer, ranking and mask of the next
@@ -476,7 +486,6 @@ __global__ __launch_bounds__(WAVES * 64) void down_q4_mt(
         return;
     }
     const Q4Consts qk = q4_consts();
-    static_assert(64 * 4 * TILES * sizeof(float) <= 2 * kQActPitch, "a wave's partial sums fit in its region (T >= 2)");
     int *s_list = reinterpret_cast<int *>(lds);
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -487,92 +496,102 @@ __global__ __launch_bounds__(WAVES * 64) void down_q4_mt(
     __syncthreads();
     const int n_u = uw.count;
     const int u0 = n_u * wave / WAVES, u1 = n_u * (wave + 1) / WAVES;
-    const int nbat = (u1 - u0 + kQDownGroups - 1) / kQDownGroups;
+    const int nbat = (u1 - u0 + GB - 1) / GB;
     const int tok = i < T ? i : T - 1;
     const size_t gwords = (size_t)d * (gs / 8);                      // words per group
     const uint32_t *ctile = Dq + (size_t)(j0 + i) * (gs / 8) + q * 4;   // row i of the first tile, codes 32q..32q+31
-    unsigned char *mine = lds + kQDownFixed + (size_t)wave * T * kQActPitch;
-    const unsigned char *al = mine + tok * kQActPitch + q * 64;      // + (group in batch) * 256 + s * 16
+    const size_t region = q_down_region(T, GB, TILES);
+    unsigned char *mine = lds + kQDownFixed + (size_t)wave * region;
+    const unsigned char *al = mine + tok * kPitch + q * 64;          // + (group in batch) * 256 + s * 16
     f32x4_t c[TILES];
 #pragma unroll
     for (int tl = 0; tl < TILES; ++tl) c[tl] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-    // batch b of the wave's share: groups u0 + 4b .., those past the end of the share repeat its last one
-    // (in range, unused).  A token's row of the batch is 4 groups x 16 pieces = one piece per lane.
     // the wave's groups (at most 64: G <= 256 over at least four waves), one to a lane: a batch's group ids
     // come out of this register into scalar registers, where reading the list from LDS put a dependent LDS
     // round trip and vector address arithmetic in front of every batch's loads (0.6 us per batch of four)
     const int my_group = s_list[min(u0 + lane, max(u1 - 1, 0))];
-    auto issue = [&](DownBatch<TILES> &B, u32x4 (&av)[TMAX], int b) {
-        const int ub = u0 + b * kQDownGroups;
+    // Batch b of the wave's share is groups u0 + GB b ..; those past the end of the share repeat its last one
+    // (in range, unused).  Codes and scales of group k of a batch:
+    DownBatch<TILES, GB> B;
+    auto load_group = [&](int b, int k) {
+        const int g = __builtin_amdgcn_readlane(my_group, min(u0 + b * GB + k, u1 - 1) - u0);
 #pragma unroll
-        for (int k = 0; k < kQDownGroups; ++k) {
-            const int g = __builtin_amdgcn_readlane(my_group, min(ub + k, u1 - 1) - u0);
-#pragma unroll
-            for (int tl = 0; tl < TILES; ++tl) {
-                B.r[tl][k] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(ctile + g * gwords + tl * 16 * (gs / 8)));
-                B.sc[tl][k] = *reinterpret_cast<const uint2 *>(Ds + (size_t)g * d + j0 + 16 * tl + 4 * q);   // rows 4q..4q+3
-            }
+        for (int tl = 0; tl < TILES; ++tl) {
+            B.r[tl][k] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(ctile + g * gwords + tl * 16 * (gs / 8)));
+            B.sc[tl][k] = *reinterpret_cast<const uint2 *>(Ds + (size_t)g * d + j0 + 16 * tl + 4 * q);   // rows 4q..4q+3
         }
-        const int un = min(ub + (lane >> 4), u1 - 1);                // position in the union of this lane's piece
+    };
+    // A token's row of a batch is GB groups x 16 pieces of 16 bytes: one piece per lane, 4 / GB tokens per load.
+    u32x4 av[kActLoads];
+    const int a_tok = lane / kLanesPerToken, a_piece = lane % kLanesPerToken;
+    auto load_act = [&](int b) {
+        const int un = min(u0 + b * GB + (a_piece >> 4), u1 - 1);    // position in the union of this lane's piece
 #pragma unroll
-        for (int t = 0; t < TMAX; ++t)
-            av[t] = *reinterpret_cast<const u32x4 *>(act + (size_t)min(t, T - 1) * act_stride + (size_t)un * gs + (lane & 15) * 8);
+        for (int j = 0; j < kActLoads; ++j)
+            av[j] = *reinterpret_cast<const u32x4 *>(act + (size_t)min(j * kTokPerLoad + a_tok, T - 1) * act_stride +
+                                                     (size_t)un * gs + (a_piece & 15) * 8);
     };
     // the region is the wave's own and LDS operations of a wave complete in order, so no barrier is needed
-    auto store_act = [&](const u32x4 (&av)[TMAX]) {
+    auto store_act = [&]() {
 #pragma unroll
-        for (int t = 0; t < TMAX; ++t)
-            if (t < T) *reinterpret_cast<u32x4 *>(mine + t * kQActPitch + lane * 16) = av[t];
+        for (int j = 0; j < kActLoads; ++j) {
+            const int t = j * kTokPerLoad + a_tok;
+            if (t < T) *reinterpret_cast<u32x4 *>(mine + t * kPitch + a_piece * 16) = av[j];
+        }
     };
-    auto multiply = [&](const DownBatch<TILES> &B, int nb) {
+    // Multiplies the first nb groups of the batch in B.  `refill`: as soon as a group's registers are used
+    // they are asked for the same group of batch b + 1 (a full batch: no condition, so the compiler can count
+    // the loads in flight), and the batch is whole.
+    auto multiply = [&](auto refill, int b, int nb) {
+        constexpr bool kRefill = decltype(refill)::value;
 #pragma unroll
-        for (int k = 0; k < kQDownGroups; ++k) {
-            if (k < nb) {                                            // uniform
-                u32x4 b[4];
+        for (int k = 0; k < GB; ++k) {
+            if (kRefill || k < nb) {                                 // uniform
+                u32x4 xb[4];
 #pragma unroll
-                for (int s = 0; s < 4; ++s) b[s] = *reinterpret_cast<const u32x4 *>(al + k * 256 + s * 16);
+                for (int s = 0; s < 4; ++s) xb[s] = *reinterpret_cast<const u32x4 *>(al + k * 256 + s * 16);
                 // the sum of the token's 128 activations of the group, for the offset: the same matrix
                 // instructions with 1.0 in every element of the other operand (every row of the result is the
                 // sum).  Summing the lane's 32 values and exchanging between the token's four lanes was a
                 // chain of two lane-crossing round trips per group, in a loop that has nothing to hide them.
                 const u32x4 ones = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
                 f32x4_t ts0 = {0.f, 0.f, 0.f, 0.f}, ts1 = {0.f, 0.f, 0.f, 0.f};
-                ts0 = mfma16q(ones, b[0], ts0);
-                ts1 = mfma16q(ones, b[1], ts1);
-                ts0 = mfma16q(ones, b[2], ts0);
-                ts1 = mfma16q(ones, b[3], ts1);
+                ts0 = mfma16q(ones, xb[0], ts0);
+                ts1 = mfma16q(ones, xb[1], ts1);
+                ts0 = mfma16q(ones, xb[2], ts0);
+                ts1 = mfma16q(ones, xb[3], ts1);
                 const float xo = 136.0f * (ts0[0] + ts1[0]);
 #pragma unroll
                 for (int tl = 0; tl < TILES; ++tl) {
                     f32x4_t t0 = {0.f, 0.f, 0.f, 0.f}, t1 = {0.f, 0.f, 0.f, 0.f};
-                    t0 = mfma16q(q4_word_bf16(B.r[tl][k].x, qk), b[0], t0);
-                    t1 = mfma16q(q4_word_bf16(B.r[tl][k].y, qk), b[1], t1);
-                    t0 = mfma16q(q4_word_bf16(B.r[tl][k].z, qk), b[2], t0);
-                    t1 = mfma16q(q4_word_bf16(B.r[tl][k].w, qk), b[3], t1);
+                    t0 = mfma16q(q4_word_bf16(B.r[tl][k].x, qk), xb[0], t0);
+                    t1 = mfma16q(q4_word_bf16(B.r[tl][k].y, qk), xb[1], t1);
+                    t0 = mfma16q(q4_word_bf16(B.r[tl][k].z, qk), xb[2], t0);
+                    t1 = mfma16q(q4_word_bf16(B.r[tl][k].w, qk), xb[3], t1);
                     const f32x4_t t = t0 + t1;
                     c[tl][0] = __builtin_fmaf(bf16_lo(B.sc[tl][k].x), t[0] - xo, c[tl][0]);
                     c[tl][1] = __builtin_fmaf(bf16_hi(B.sc[tl][k].x), t[1] - xo, c[tl][1]);
                     c[tl][2] = __builtin_fmaf(bf16_lo(B.sc[tl][k].y), t[2] - xo, c[tl][2]);
                     c[tl][3] = __builtin_fmaf(bf16_hi(B.sc[tl][k].y), t[3] - xo, c[tl][3]);
                 }
+                if (kRefill) load_group(b + 1, k);
             }
         }
     };
     if (nbat > 0) {                                                  // uniform per wave; no barrier inside
-        DownBatch<TILES> cur, nxt;
-        u32x4 av[TMAX];
-        issue(cur, av, 0);
-        store_act(av);
+#pragma unroll
+        for (int k = 0; k < GB; ++k) load_group(0, k);
+        load_act(0);
+        store_act();
         for (int b = 0; b + 1 < nbat; ++b) {
-            issue(nxt, av, b + 1);
-            multiply(cur, kQDownGroups);
-            store_act(av);
-            cur = nxt;
+            load_act(b + 1);
+            multiply(std::true_type{}, b, GB);
+            store_act();
         }
-        multiply(cur, u1 - u0 - (nbat - 1) * kQDownGroups);
+        multiply(std::false_type{}, nbat - 1, u1 - u0 - (nbat - 1) * GB);
     }
     // a wave's partial sums go where its activations were (its own region, it is done with them)
-    auto red = [&](int w) { return reinterpret_cast<float *>(lds + kQDownFixed + (size_t)w * T * kQActPitch) + lane * 4 * TILES; };
+    auto red = [&](int w) { return reinterpret_cast<float *>(lds + kQDownFixed + (size_t)w * region) + lane * 4 * TILES; };
 #pragma unroll
     for (int tl = 0; tl < TILES; ++tl)
 #pragma unroll
@@ -615,29 +634,29 @@ hipError_t launch_ffn_q4_mfma(const bf16_t *x, int T, int d, int G, const Q4Weig
                      w.gate_scales, w.up_codes, w.up_scales, mask, act, ffn, ap);
     // long rows: 32 rows to a workgroup of eight waves, so that the activations are read half as often
     const bool wide = d >= 8192 && d % 32 == 0;
-#define HALO_DOWN_Q4(TM, TILES, WAVES)                                                                           \
+#define HALO_DOWN_Q4(TM, TILES, WAVES, GB)                                                                       \
     do {                                                                                                         \
         static const hipError_t lds_ok = hipFuncSetAttribute(                                                    \
-            reinterpret_cast<const void *>(down_q4_mt<TM, TILES, WAVES>), hipFuncAttributeMaxDynamicSharedMemorySize, \
-            (int)q_down_lds_bytes(16, WAVES));                                                            \
+            reinterpret_cast<const void *>(down_q4_mt<TM, TILES, WAVES, GB>), hipFuncAttributeMaxDynamicSharedMemorySize, \
+            (int)q_down_lds_bytes(16, WAVES, GB, TILES));                                                               \
         if (lds_ok != hipSuccess) return lds_ok;                                                                 \
-        down_q4_mt<TM, TILES, WAVES><<<dim3(d / (16 * TILES) + n_mask), dim3(WAVES * 64), q_down_lds_bytes(T, WAVES), s>>>( \
+        down_q4_mt<TM, TILES, WAVES, GB><<<dim3(d / (16 * TILES) + n_mask), dim3(WAVES * 64), q_down_lds_bytes(T, WAVES, GB, TILES), s>>>( \
             T, d, G, w.down_codes, w.down_scales, mask, act, ffn, y, n_mask, nx);                                \
     } while (0)
     if (wide) {
         if (T <= 4)
-            HALO_DOWN_Q4(4, 2, 8);
+            HALO_DOWN_Q4(4, 2, 8, 2);
         else if (T <= 8)
-            HALO_DOWN_Q4(8, 2, 8);
+            HALO_DOWN_Q4(8, 2, 8, 2);
         else
-            HALO_DOWN_Q4(16, 2, 8);
+            HALO_DOWN_Q4(16, 2, 8, 2);
     } else {
         if (T <= 4)
-            HALO_DOWN_Q4(4, 1, 4);
+            HALO_DOWN_Q4(4, 1, 4, 4);
         else if (T <= 8)
-            HALO_DOWN_Q4(8, 1, 4);
+            HALO_DOWN_Q4(8, 1, 4, 4);
         else
-            HALO_DOWN_Q4(16, 1, 4);
+            HALO_DOWN_Q4(16, 1, 4, 4);
     }
 #undef HALO_DOWN_Q4
     return hipGetLastError();
