@@ -424,12 +424,13 @@ __global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void gate_up_q4_mt(
 
 // ---------------------------------------------------------------------------
 // down.  A workgroup owns 16 * TILES output rows; a group's 16 x 128 tile of codes is 1 KiB of consecutive
-// bytes = one load per lane (row i, codes 32q..32q+31).  The waves split the union's groups, four groups per
-// batch.  While a batch is multiplied the next batch's codes, scales and activations are on their way, the
-// activations (T rows of 4 x 128 values, consecutive in the compact layout) into registers; they are
-// written to the wave's private LDS region, from where they are read in operand order, once the
-// multiplication is done with the region.  (With one batch at a time -- loads, wait, activations, wait,
-// multiply -- a wave waited for memory three times per eight groups and the kernel ran at 1.5 TB/s.)
+// bytes = one load per lane (row i, codes 32q..32q+31).  The waves split the union's groups, GB groups per
+// batch.  The codes and scales of a group are asked for again, for the next batch, as soon as they have been
+// used; the next batch's activations (T rows of GB x 128 values, consecutive in the compact layout) are
+// requested into registers before the current batch is multiplied and written to the wave's private LDS
+// region, from where they are read in operand order, once the multiplication is done with the region.
+// (With one batch at a time -- loads, wait, activations, wait, multiply -- a wave waited for memory three
+// times per eight groups and the kernel ran at 1.5 TB/s.)
 // Every workgroup reads all of the tokens' activations, T * 256 bytes per group beside the 1 KiB of codes
 // of a 16-row tile: with eight tokens that is twice the codes' bytes, and the loads a compute unit can
 // have in flight are what bounds the kernel.  TILES = 2 (eight waves, 32 rows: long rows, d >= 8192, where
