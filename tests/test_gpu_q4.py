@@ -135,6 +135,37 @@ def test_q4_ffn_entry_point_with_handmade_masks_and_errors():
     torch.cuda.synchronize()
 
 
+@pytest.mark.parametrize("T,d,G", [(2, 8192, 6), (4, 5120, 10), (16, 4096, 5), (3, 1024, 70)])
+def test_q4_few_tokens_with_handmade_masks(T, d, G):
+    # the matrix-core kernels on masks no schedule would give: no group at all (exact zeros), one group of one
+    # token, every group of every token, a different single group per token, the last group only
+    w = dataclasses.replace(hs.LLAMA13B_STACK, name="case", d=d, ffn=G * 128, rank=64, T=T, layers=1, seed=31)
+    _say(f"q4 few tokens, handmade masks T={T} d={d} G={G}")
+    L = hz.Q4Layer(w)
+    s = hz.shape_of(w)
+    _, _, Wg, Wu, WdT = L.host()
+    ws = torch.empty(H.halo_workspace_bytes(s, T, G), dtype=torch.uint8, device=hz.DEV)
+    x = hs.hidden_states(w, 1, hz.DEV)
+    xn = hz.to_np32(x)
+    masks = [np.zeros((T, G), np.uint8), np.zeros((T, G), np.uint8), np.ones((T, G), np.uint8),
+             np.zeros((T, G), np.uint8), np.zeros((T, G), np.uint8)]
+    masks[1][T - 1, G // 2] = 1
+    for t in range(T):
+        masks[3][t, (3 * t + 1) % G] = 1
+    masks[4][:, G - 1] = 1
+    for mask_np in masks:
+        y = torch.full((T, d), float("nan"), dtype=torch.bfloat16, device=hz.DEV)
+        H.halo_group_sparse_ffn_q4(s, x, L.q4, torch.from_numpy(mask_np).to(hz.DEV), y, ws)
+        torch.cuda.synchronize()
+        yg = hz.to_np32(y).astype(np.float64)
+        yc = ref.group_sparse_ffn(xn, Wg, Wu, WdT, 128, mask_np)
+        for t in range(T):
+            if not mask_np[t].any():
+                assert not yg[t].any(), t
+            else:
+                assert np.linalg.norm(yg[t] - yc[t]) / np.linalg.norm(yc[t]) <= TOL["bf16"], t
+
+
 @pytest.mark.parametrize("d,T,r,G,K", [
     (4096, 1, 256, 20, 10), (8192, 1, 256, 20, 10), (512, 3, 256, 20, 10), (5120, 4, 256, 20, 10),
     (8192, 8, 256, 20, 10), (384, 3, 256, 20, 10),
