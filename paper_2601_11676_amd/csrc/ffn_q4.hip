@@ -388,6 +388,22 @@ hipError_t launch_ffn_q4(int dtype, const void *x, int T, int d, int G, int gs, 
     }
     if (q4_mfma_path_supported(T, d, G, gs))
         return launch_ffn_q4_mfma(bx, T, d, G, w, mask, by, ws, s, rank, ahead, ahead_fused);
+    if (T > 16 && q4_mfma_path_supported(16, d, G, gs)) {
+        // Many tokens: the matrix-core kernels over tiles of up to 16 tokens, one tile after the other on
+        // the stream (each streams the union of its own tokens' groups; the activation scratch is reused).
+        // No kernel of its own for this case yet: a tile pair of launches is 30-90 us, where the plain path
+        // below takes 50 us per TOKEN at the 7B shape.  A last tile of one token would leave the kernels'
+        // range, so the last two tiles share their tokens.
+        for (int t0 = 0; t0 < T;) {
+            int n = T - t0 > 16 ? 16 : T - t0;
+            if (T - t0 == 17) n = 15;
+            const hipError_t e = launch_ffn_q4_mfma(bx + (size_t)t0 * d, n, d, G, w, mask + (size_t)t0 * G,
+                                                    by + (size_t)t0 * d, ws, s, rank, nullptr, nullptr);
+            if (e != hipSuccess) return e;
+            t0 += n;
+        }
+        return hipSuccess;
+    }
     return q4_generic<bf16_t>(bx, T, d, G, gs, w, mask, by, ws, s);
 }
 

@@ -75,6 +75,9 @@ def test_q4_one_token_streaming_path(d, G, K):
     (3, 512, 3, 40),         # a single chunk per row
     (6, 5120, 90, 256),      # more 16-row tiles than workgroups: a workgroup walks several
     (16, 8192, 40, 256),     # x larger than its LDS space: staged a range of columns at a time, per tile
+    (17, 1024, 9, 64),       # more than 16 tokens: tiles of tokens, here 15 + 2 (no tile of one token)
+    (33, 2048, 12, 64),      # 16 + 15 + 2
+    (100, 1024, 20, 40),     # six tiles of 16 and one of 4
 ])
 def test_q4_few_tokens_matrix_core_path(T, d, G, r):
     w = dataclasses.replace(hs.LLAMA13B_STACK, name="case", d=d, ffn=G * 128, rank=r, T=T, layers=1, seed=18)
