@@ -549,7 +549,8 @@ def main():
     prio_dev = torch.from_numpy(prio_dev_np).to(dev)
     ys = torch.zeros((n_all, T, d), dtype=w.torch_dtype, device=dev)
     masks = torch.zeros((n_all, T, G), dtype=torch.uint8, device=dev)
-    ws = torch.empty(H.halo_workspace_bytes(shape, T, k_keep), dtype=torch.uint8, device=dev)
+    ws_bytes = H.halo_workspace_bytes_q4(shape, T, k_keep) if args.q4 else H.halo_workspace_bytes(shape, T, k_keep)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
     torch.cuda.synchronize()
 
     st = torch.cuda.Stream()               # every library call below goes to this stream (default priority)

@@ -110,6 +110,15 @@ int halo_ratios_min_max(int32_t n_dev, const double *mem, const double *comp, do
 size_t halo_workspace_bytes(const halo_shape *shape, int32_t T, int32_t k_keep);
 
 /*
+ * The same, for callers of the `_q4` entry points further down: for more than 16 tokens (bf16) the bound
+ * also holds one block's FFN weights as bf16 (3 * ffn * d * 2 bytes).  With that room the 4-bit weights of
+ * a many-token call are expanded once into the workspace and the call runs on the bf16 matrix-core
+ * kernels; a `_q4` call given only halo_workspace_bytes works all the same and walks the tokens 16 at a
+ * time instead (several times slower).  Never smaller than halo_workspace_bytes; 0 for invalid arguments.
+ */
+size_t halo_workspace_bytes_q4(const halo_shape *shape, int32_t T, int32_t k_keep);
+
+/*
  * Semantic-aware predictor (paper Sec. III-B.2): one significance value per
  * neuron group from the hidden state, through a two-matrix network
  *     h = ReLU(x A),  scores = h B      (A: d x rank, B: rank x n_groups, no bias).
@@ -261,7 +270,10 @@ int halo_ffn_forward_ahead(const halo_shape *shape, const void *x, int32_t T, co
  * halo_group_sparse_ffn / halo_ffn_forward.  Tuned paths (bf16 activations, n_groups <= 256): one
  * token with d in {4096, 8192} (every surviving code byte streamed once, float ALUs), and 2..16
  * tokens with d a multiple of 1024 up to 8192 (matrix cores, codes expanded in registers); other
- * shapes and float32 activations take a plain path that dequantises element by element.
+ * shapes and float32 activations take a plain path that dequantises element by element.  More than
+ * 16 tokens (same shapes): with a workspace of halo_workspace_bytes_q4 the weights are expanded to bf16
+ * (each value s * (c - 8) rounded to bf16, to nearest even) and the bf16 kernels of
+ * halo_group_sparse_ffn run on them; with less, the 2..16-token kernels walk the tokens 16 at a time.
  */
 int halo_group_sparse_ffn_q4(const halo_shape *shape, const void *x, int32_t T, const void *Wg_codes,
                              const void *Wg_scales, const void *Wu_codes, const void *Wu_scales,

@@ -5,7 +5,7 @@ argument marshalling only; every step of the path runs in the HIP kernels.  PyTo
 tensors are used for device memory and streams, nothing else.
 """
 from .binding import (  # noqa: F401
-    HaloError, Shape, MhaShape, halo_mha_workspace_bytes, halo_head_sparse_mha, halo_mha_forward, halo_mha_forward_ahead, halo_build_schedule, halo_workspace_bytes, halo_predict_scores,
+    HaloError, Shape, MhaShape, halo_mha_workspace_bytes, halo_head_sparse_mha, halo_mha_forward, halo_mha_forward_ahead, halo_build_schedule, halo_workspace_bytes, halo_workspace_bytes_q4, halo_predict_scores,
     halo_build_group_mask, halo_group_sparse_ffn, halo_ffn_forward, halo_ffn_forward_ahead,
     halo_ffn_forward_static, halo_static_scratch_bytes,
     halo_group_sparse_ffn_q4, halo_ffn_forward_q4, halo_ffn_forward_ahead_q4,

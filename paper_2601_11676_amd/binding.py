@@ -87,6 +87,8 @@ def load_library():
     lib.halo_ratios_min_max.argtypes = [i32, vp, vp, C.c_double, C.c_double, vp]
     lib.halo_workspace_bytes.restype = sz
     lib.halo_workspace_bytes.argtypes = [ps, i32, i32]
+    lib.halo_workspace_bytes_q4.restype = sz
+    lib.halo_workspace_bytes_q4.argtypes = [ps, i32, i32]
     lib.halo_predict_scores.restype = C.c_int
     lib.halo_predict_scores.argtypes = [ps, vp, i32, vp, vp, vp, vp, sz, vp]
     lib.halo_build_group_mask.restype = C.c_int
@@ -206,6 +208,10 @@ def halo_ratios_min_max(mem, comp, demand: float, eps: float = 1e-3) -> np.ndarr
 
 def halo_workspace_bytes(shape: Shape, T: int, k_keep: int) -> int:
     return int(load_library().halo_workspace_bytes(C.byref(shape.c), int(T), int(k_keep)))
+
+
+def halo_workspace_bytes_q4(shape: Shape, T: int, k_keep: int) -> int:
+    return int(load_library().halo_workspace_bytes_q4(C.byref(shape.c), int(T), int(k_keep)))
 
 
 def halo_predict_scores(shape: Shape, x, At, Bt, scores, workspace, stream=None) -> None:

@@ -355,6 +355,53 @@ static hipError_t q4_generic(const XT *x, int T, int d, int G, int gs, const Q4W
 
 bool q4_shape_supported(int d, int gs) { return gs == kQ4Block && d % kQ4Block == 0; }
 
+bool q4_expand_supported(int T, int dtype, int d, int G, int gs)
+{
+    return dtype == 1 && T > 16 && q4_shape_supported(d, gs) &&
+           (mfma_path_supported(T, d, gs) || prefill_path_supported(T, d, gs));
+}
+
+// 4-bit codes and their scales -> bf16 values s * (c - 8), each rounded to nearest even: rows of K elements,
+// one scale per 128 consecutive elements of a row (K = d for gate / up; K = 128 with one scale per row for
+// the group-blocked down projection).  A thread takes 16 bytes of codes (32 elements) and writes 64 bytes.
+__global__ __launch_bounds__(256) void expand_q4_kernel(const uint32_t *__restrict__ codes,
+                                                        const bf16_t *__restrict__ scales,
+                                                        bf16_t *__restrict__ out, size_t pieces, int K)
+{
+    const int per_row = K / 32, nblk = K / kQ4Block;
+    for (size_t p = (size_t)blockIdx.x * 256 + threadIdx.x; p < pieces; p += (size_t)gridDim.x * 256) {
+        const size_t row = p / per_row;
+        const int k32 = (int)(p - row * per_row);
+        const u32x4 c = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(codes) + p);
+        const float s = bf16_bits_to_float(scales[row * nblk + k32 / 4]);
+        const uint32_t w[4] = {c.x, c.y, c.z, c.w};
+        u32x4 o[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            uint32_t pr[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float lo = s * (float)((int)((w[j] >> (4 * i)) & 15u) - 8);
+                const float hi = s * (float)((int)((w[j] >> (16 + 4 * i)) & 15u) - 8);
+                pr[i] = (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+            }
+            o[j] = u32x4{pr[0], pr[1], pr[2], pr[3]};
+        }
+        u32x4 *dst = reinterpret_cast<u32x4 *>(out + row * K + (size_t)k32 * 32);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) dst[j] = o[j];
+    }
+}
+
+static hipError_t expand_q4(const uint32_t *codes, const bf16_t *scales, bf16_t *out, size_t rows, int K, hipStream_t s)
+{
+    const size_t pieces = rows * (size_t)(K / 32);
+    const size_t want = (pieces + 255) / 256;
+    const int blocks = (int)(want < 8192 ? want : 8192);
+    expand_q4_kernel<<<dim3(blocks), dim3(256), 0, s>>>(codes, scales, out, pieces, K);
+    return hipGetLastError();
+}
+
 hipError_t launch_ffn_q4(int dtype, const void *x, int T, int d, int G, int gs, const Q4Weights &w,
                          const uint8_t *mask, void *y, const DecodeScratch &ws, hipStream_t s, int rank,
                          const AheadArgs *ahead, bool *ahead_fused)
@@ -388,6 +435,18 @@ hipError_t launch_ffn_q4(int dtype, const void *x, int T, int d, int G, int gs, 
     }
     if (q4_mfma_path_supported(T, d, G, gs))
         return launch_ffn_q4_mfma(bx, T, d, G, w, mask, by, ws, s, rank, ahead, ahead_fused);
+    if (ws.q4_w && q4_expand_supported(T, dtype, d, G, gs)) {
+        // Many tokens and room for a block's weights as bf16: the weights are expanded once (a stream of
+        // 0.5 + 2 bytes per element) and the bf16 matrix-core kernels do the rest, every weight used for
+        // all the tokens that keep its group.
+        const size_t ffn = (size_t)G * gs;
+        bf16_t *Wg = ws.q4_w, *Wu = Wg + ffn * d, *Wd = Wu + ffn * d;
+        hipError_t e = expand_q4(w.gate_codes, w.gate_scales, Wg, ffn, d, s);
+        if (e == hipSuccess) e = expand_q4(w.up_codes, w.up_scales, Wu, ffn, d, s);
+        if (e == hipSuccess) e = expand_q4(w.down_codes, w.down_scales, Wd, (size_t)G * d, gs, s);
+        if (e != hipSuccess) return e;
+        return launch_ffn_decode(dtype, x, T, d, G, gs, Wg, Wu, Wd, mask, y, ws, s);
+    }
     if (T > 16 && q4_mfma_path_supported(16, d, G, gs)) {
         // Many tokens: the matrix-core kernels over tiles of up to 16 tokens, one tile after the other on
         // the stream (each streams the union of its own tokens' groups; the activation scratch is reused).

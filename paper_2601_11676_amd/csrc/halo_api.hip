@@ -44,7 +44,8 @@ struct Workspace {
     DecodeScratch dec{};
     size_t bytes = 0;
 
-    Workspace(const halo_shape &s, int T, int K, void *base)
+    // q4_room: also room for one block's weights as bf16 (the 4-bit entry points with many tokens)
+    Workspace(const halo_shape &s, int T, int K, void *base, bool q4_room = false)
     {
         char *p = static_cast<char *>(base);
         size_t off = 0;
@@ -82,6 +83,9 @@ struct Workspace {
             }
         }
         dec.partial = reinterpret_cast<float *>(take(partial_elems * sizeof(float)));
+        // appended last: the layout in front of it is the same with and without
+        if (q4_room && q4_expand_supported(T, s.dtype, s.d, s.n_groups, s.group_size))
+            dec.q4_w = reinterpret_cast<bf16_t *>(take((size_t)3 * s.ffn * s.d * sizeof(bf16_t)));
         bytes = off;
     }
 };
@@ -288,6 +292,19 @@ size_t halo_workspace_bytes(const halo_shape *shape, int32_t T, int32_t k_keep)
     return Workspace(*shape, T, k_keep, nullptr).bytes;
 }
 
+size_t halo_workspace_bytes_q4(const halo_shape *shape, int32_t T, int32_t k_keep)
+{
+    if (check_shape(shape) != HALO_OK || T < 0 || k_keep < 0 || k_keep > shape->n_groups) return 0;
+    return Workspace(*shape, T, k_keep, nullptr, true).bytes;
+}
+
+// the workspace of a 4-bit call: with the room for expanded weights when the caller gave that much
+static Workspace q4_workspace(const halo_shape &s, int T, int K, void *base, size_t ws_bytes)
+{
+    Workspace big(s, T, K, base, true);
+    return ws_bytes >= big.bytes ? big : Workspace(s, T, K, base);
+}
+
 int halo_predict_scores(const halo_shape *shape, const void *x, int32_t T, const void *At,
                         const void *Bt, float *scores, void *workspace, size_t ws_bytes,
                         void *stream)
@@ -413,7 +430,7 @@ int halo_group_sparse_ffn_q4(const halo_shape *shape, const void *x, int32_t T, 
         misaligned(Wu_scales) || misaligned(Wd_codes) || misaligned(Wd_scales) || misaligned(y))
         return HALO_ERR_ARG;
     if (!workspace || misaligned(workspace)) return HALO_ERR_WORKSPACE;
-    Workspace ws(*shape, T, 0, workspace);
+    Workspace ws = q4_workspace(*shape, T, 0, workspace, ws_bytes);
     if (ws_bytes < ws.bytes) return HALO_ERR_WORKSPACE;
     const Q4Weights w{(const uint32_t *)Wg_codes, (const bf16_t *)Wg_scales, (const uint32_t *)Wu_codes,
                       (const bf16_t *)Wu_scales, (const uint32_t *)Wd_codes, (const bf16_t *)Wd_scales};
@@ -443,7 +460,7 @@ int halo_ffn_forward_q4(const halo_shape *shape, const void *x, const void *x_pr
         misaligned(Wd_scales) || misaligned(y) || (scores && misaligned(scores)))
         return HALO_ERR_ARG;
     if (!workspace || misaligned(workspace)) return HALO_ERR_WORKSPACE;
-    Workspace ws(*shape, T, k_keep, workspace);
+    Workspace ws = q4_workspace(*shape, T, k_keep, workspace, ws_bytes);
     if (ws_bytes < ws.bytes) return HALO_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     float *sc = scores ? scores : ws.scores;
@@ -592,7 +609,7 @@ int halo_ffn_forward_ahead_q4(const halo_shape *shape, const void *x, int32_t T,
         (scores_next && misaligned(scores_next)))
         return HALO_ERR_ARG;
     if (!workspace || misaligned(workspace)) return HALO_ERR_WORKSPACE;
-    Workspace ws(*shape, T, k_keep, workspace);
+    Workspace ws = q4_workspace(*shape, T, k_keep, workspace, ws_bytes);
     if (ws_bytes < ws.bytes) return HALO_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     float *sc = scores_next ? scores_next : ws.scores;

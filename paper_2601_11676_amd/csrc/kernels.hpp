@@ -30,6 +30,7 @@ struct DecodeScratch {
     int32_t *tok_cnt;   // [G]
     int32_t *slot;      // [T][G] position of the token in its group's list, -1 = not kept
     float *partial;     // [splits][T][d] prefill: the down projection's sums per range of groups
+    bf16_t *q4_w = nullptr;   // 4-bit callers with many tokens: room for Wg, Wu [ffn][d] and Wd [G][d][gs] as bf16, or null
 };
 // The next block's prediction (predictor + mask from x_next), see halo_ffn_forward_ahead.
 struct AheadArgs {
@@ -117,6 +118,8 @@ struct Q4Weights {
     const bf16_t *down_scales;    // [G][d]
 };
 bool q4_shape_supported(int d, int gs);
+// many tokens over 4-bit weights can run on the bf16 matrix-core kernels once the weights are expanded
+bool q4_expand_supported(int T, int dtype, int d, int G, int gs);
 // rank: the predictor's size; the few-token kernel shapes its work around the predictor rows it carries when
 // one step is overlapped with the next, and shapes it the same way when it carries none (same bits either way)
 hipError_t launch_ffn_q4(int dtype, const void *x, int T, int d, int G, int gs, const Q4Weights &w,

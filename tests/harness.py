@@ -51,11 +51,13 @@ class Q4Layer:
         return self._host
 
 
-def gpu_forward_q4(w, layer: Q4Layer, x, K, prio_dev_np, drop_np):
-    """halo_ffn_forward_q4 through the C boundary; returns numpy outputs."""
+def gpu_forward_q4(w, layer: Q4Layer, x, K, prio_dev_np, drop_np, big_workspace=False):
+    """halo_ffn_forward_q4 through the C boundary; returns numpy outputs.  big_workspace: sized by
+    halo_workspace_bytes_q4 (many tokens then run on expanded weights)."""
     s = shape_of(w)
     T, G = x.shape[0], w.n_groups
-    ws = torch.empty(H.halo_workspace_bytes(s, T, K), dtype=torch.uint8, device=DEV)
+    size = H.halo_workspace_bytes_q4(s, T, K) if big_workspace else H.halo_workspace_bytes(s, T, K)
+    ws = torch.empty(size, dtype=torch.uint8, device=DEV)
     pd = torch.from_numpy(np.ascontiguousarray(prio_dev_np)).to(DEV)
     dr = None if drop_np is None else torch.from_numpy(np.ascontiguousarray(drop_np)).to(DEV)
     y = torch.full((T, w.d), float("nan"), dtype=w.torch_dtype, device=DEV)

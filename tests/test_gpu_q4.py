@@ -233,17 +233,38 @@ def test_q4_full_size_single_layer_of_the_stacks(wl):
     hz.assert_parity(g, c, TOL["bf16"], "q4 " + wl.name)
 
 
-def test_q4_llama7b_prefill_all_tokens():
+@pytest.mark.parametrize("big_workspace", [False, True])
+def test_q4_llama7b_prefill_all_tokens(big_workspace):
+    # 512 tokens over 4-bit weights: with the plain workspace the few-token kernels walk the tokens 16 at a
+    # time; with room for a block's weights as bf16 they are expanded once and the bf16 kernels run
     w = hs.LLAMA7B_PREFILL
-    _say("q4 7B prefill, 512 tokens, every token")
+    _say(f"q4 7B prefill, 512 tokens, every token, big workspace {big_workspace}")
+    s = hz.shape_of(w)
+    K = w.k_keep()
+    small, big = H.halo_workspace_bytes(s, w.T, K), H.halo_workspace_bytes_q4(s, w.T, K)
+    assert big == small + 3 * w.ffn * w.d * 2 and H.halo_workspace_bytes_q4(s, 16, K) == H.halo_workspace_bytes(s, 16, K)
     L = hz.Q4Layer(w)
     x = hs.hidden_states(w, 0, hz.DEV)
-    K = w.k_keep()
     pd = H.halo_build_schedule(K, w.device_plr())
     drop = hs.drop_outcomes(w)
-    g = hz.gpu_forward_q4(w, L, x, K, pd, drop)
+    g = hz.gpu_forward_q4(w, L, x, K, pd, drop, big_workspace=big_workspace)
     c = hz.oracle_forward(w, L, x, K, pd, drop)
     hz.assert_parity(g, c, TOL["bf16"], "q4 7B prefill")
+
+
+@pytest.mark.parametrize("T,d,G", [(17, 1024, 9), (40, 2048, 12), (300, 1024, 20)])
+def test_q4_many_tokens_on_expanded_weights(T, d, G):
+    # small shapes through the expansion to bf16 (workspace of halo_workspace_bytes_q4)
+    w = dataclasses.replace(hs.LLAMA13B_STACK, name="case", d=d, ffn=G * 128, rank=64, T=T, layers=1, seed=19)
+    _say(f"q4 many tokens, expanded weights T={T} d={d} G={G}")
+    L = hz.Q4Layer(w)
+    x = hs.hidden_states(w, 0, hz.DEV)
+    K = max(1, G // 2)
+    pd = H.halo_build_schedule(K, w.device_plr())
+    drop = hs.drop_outcomes(w, T=T)
+    g = hz.gpu_forward_q4(w, L, x, K, pd, drop, big_workspace=True)
+    c = hz.oracle_forward(w, L, x, K, pd, drop)
+    hz.assert_parity(g, c, TOL["bf16"], "q4 many tokens expanded")
 
 
 @pytest.mark.parametrize("wl,keep,layers", [(hs.LLAMA13B_STACK, 0.3, None), (hs.LLAMA70B_STACK, 0.5, 6)])
