@@ -364,6 +364,8 @@ bool q4_expand_supported(int T, int dtype, int d, int G, int gs)
 // 4-bit codes and their scales -> bf16 values s * (c - 8), each rounded to nearest even: rows of K elements,
 // one scale per 128 consecutive elements of a row (K = d for gate / up; K = 128 with one scale per row for
 // the group-blocked down projection).  A thread takes 16 bytes of codes (32 elements) and writes 64 bytes.
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+
 __global__ __launch_bounds__(256) void expand_q4_kernel(const uint32_t *__restrict__ codes,
                                                         const bf16_t *__restrict__ scales,
                                                         bf16_t *__restrict__ out, size_t pieces, int K)
@@ -373,7 +375,7 @@ __global__ __launch_bounds__(256) void expand_q4_kernel(const uint32_t *__restri
         const size_t row = p / per_row;
         const int k32 = (int)(p - row * per_row);
         const u32x4 c = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(codes) + p);
-        const float s = bf16_bits_to_float(scales[row * nblk + k32 / 4]);
+        const float s = bf16_bits_to_float(scales[row * nblk + k32 / 4]), off = -136.0f * s;
         const uint32_t w[4] = {c.x, c.y, c.z, c.w};
         u32x4 o[4];
 #pragma unroll
@@ -381,9 +383,11 @@ __global__ __launch_bounds__(256) void expand_q4_kernel(const uint32_t *__restri
             uint32_t pr[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const float lo = s * (float)((int)((w[j] >> (4 * i)) & 15u) - 8);
-                const float hi = s * (float)((int)((w[j] >> (16 + 4 * i)) & 15u) - 8);
-                pr[i] = (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+                // the pair (2i, 2i+1) as the bf16 values 128 + c; s * (128 + c) - 136 s = s * (c - 8), exact in
+                // float (an 8-bit by 8-bit product and a difference of neighbours); one instruction rounds both
+                const uint32_t pair = ((w[j] >> (4 * i)) & 0x000F000Fu) | 0x43004300u;
+                const f32x2_t v = {__builtin_fmaf(bf16_lo(pair), s, off), __builtin_fmaf(bf16_hi(pair), s, off)};
+                pr[i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
             }
             o[j] = u32x4{pr[0], pr[1], pr[2], pr[3]};
         }
