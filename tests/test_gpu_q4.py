@@ -175,6 +175,7 @@ def test_q4_few_tokens_with_handmade_masks(T, d, G):
     (4096, 1, 256, 86, 43),      # enough surviving neurons for the runs to be cut by weight around the predictor rows
     (4096, 1, 512, 86, 60),      # two predictor rows per gate/up workgroup
     (4096, 1, 128, 20, 10),      # a predictor size that is not dealt evenly: workgroups of its own
+    (1024, 20, 64, 12, 6),       # more than 16 tokens: tiles of tokens, the prediction enqueued after the FFN
 ])
 def test_q4_one_step_ahead_overlap_equals_the_serial_pass(d, T, r, G, K):
     # predictor + mask of step s+1 beside (or, for shapes without spare workgroups, after) the FFN of step s
