@@ -363,46 +363,53 @@ bool q4_expand_supported(int T, int dtype, int d, int G, int gs)
 
 // 4-bit codes and their scales -> bf16 values s * (c - 8), each rounded to nearest even: rows of K elements,
 // one scale per 128 consecutive elements of a row (K = d for gate / up; K = 128 with one scale per row for
-// the group-blocked down projection).  A thread takes 16 bytes of codes (32 elements) and writes 64 bytes.
+// the group-blocked down projection).  A thread takes one word of codes (8 elements) at a time and writes
+// 16 bytes, so that a wave's store instruction covers 1 KiB of consecutive bytes (16 bytes of codes per
+// thread made every store instruction touch 64 cache lines, 16 bytes of each).
 typedef float f32x2_t __attribute__((ext_vector_type(2)));
 
 __global__ __launch_bounds__(256) void expand_q4_kernel(const uint32_t *__restrict__ codes,
                                                         const bf16_t *__restrict__ scales,
-                                                        bf16_t *__restrict__ out, size_t pieces, int K)
+                                                        bf16_t *__restrict__ out, size_t words)
 {
-    const int per_row = K / 32, nblk = K / kQ4Block;
-    for (size_t p = (size_t)blockIdx.x * 256 + threadIdx.x; p < pieces; p += (size_t)gridDim.x * 256) {
-        const size_t row = p / per_row;
-        const int k32 = (int)(p - row * per_row);
-        const u32x4 c = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(codes) + p);
-        const float s = bf16_bits_to_float(scales[row * nblk + k32 / 4]), off = -136.0f * s;
-        const uint32_t w[4] = {c.x, c.y, c.z, c.w};
-        u32x4 o[4];
+    constexpr int U = 4;                                    // words per thread and pass, all requested first
+    const int words_per_block = kQ4Block / 8;
+    const size_t stride = (size_t)gridDim.x * 256;
+    for (size_t w0 = (size_t)blockIdx.x * 256 + threadIdx.x; w0 < words; w0 += stride * U) {
+        uint32_t w[U];
+        float s[U];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            uint32_t pr[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                // the pair (2i, 2i+1) as the bf16 values 128 + c; s * (128 + c) - 136 s = s * (c - 8), exact in
-                // float (an 8-bit by 8-bit product and a difference of neighbours); one instruction rounds both
-                const uint32_t pair = ((w[j] >> (4 * i)) & 0x000F000Fu) | 0x43004300u;
-                const f32x2_t v = {__builtin_fmaf(bf16_lo(pair), s, off), __builtin_fmaf(bf16_hi(pair), s, off)};
-                pr[i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
-            }
-            o[j] = u32x4{pr[0], pr[1], pr[2], pr[3]};
+        for (int u = 0; u < U; ++u) {
+            const size_t i = w0 + u * stride < words ? w0 + u * stride : w0;
+            w[u] = __builtin_nontemporal_load(codes + i);
+            s[u] = bf16_bits_to_float(scales[i / words_per_block]);    // blocks follow each other row after row
         }
-        u32x4 *dst = reinterpret_cast<u32x4 *>(out + row * K + (size_t)k32 * 32);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) dst[j] = o[j];
+        for (int u = 0; u < U; ++u) {
+            if (w0 + u * stride < words) {
+                const float off = -136.0f * s[u];
+                uint32_t pr[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    // the pair (2i, 2i+1) as the bf16 values 128 + c; s * (128 + c) - 136 s = s * (c - 8), exact
+                    // in float (an 8-bit by 8-bit product and a difference of neighbours); one instruction
+                    // rounds both
+                    const uint32_t pair = ((w[u] >> (4 * i)) & 0x000F000Fu) | 0x43004300u;
+                    const f32x2_t v = {__builtin_fmaf(bf16_lo(pair), s[u], off), __builtin_fmaf(bf16_hi(pair), s[u], off)};
+                    pr[i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+                }
+                reinterpret_cast<u32x4 *>(out)[w0 + u * stride] = u32x4{pr[0], pr[1], pr[2], pr[3]};
+            }
+        }
     }
 }
 
 static hipError_t expand_q4(const uint32_t *codes, const bf16_t *scales, bf16_t *out, size_t rows, int K, hipStream_t s)
 {
-    const size_t pieces = rows * (size_t)(K / 32);
-    const size_t want = (pieces + 255) / 256;
-    const int blocks = (int)(want < 8192 ? want : 8192);
-    expand_q4_kernel<<<dim3(blocks), dim3(256), 0, s>>>(codes, scales, out, pieces, K);
+    const size_t words = rows * (size_t)(K / 8);
+    const size_t want = (words + 1023) / 1024;
+    const int blocks = (int)(want < 16384 ? want : 16384);
+    expand_q4_kernel<<<dim3(blocks), dim3(256), 0, s>>>(codes, scales, out, words);
     return hipGetLastError();
 }
 

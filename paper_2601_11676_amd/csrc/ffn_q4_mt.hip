@@ -105,7 +105,7 @@ __global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void gate_up_q4_mt(
     const uint8_t *__restrict__ mask, bf16_t *__restrict__ act, int act_stride, AheadPredDev ap)
 {
     constexpr int gs = 128;
-    constexpr int NT = WAVES * 64, kQXBytes = q_x_bytes(WAVES);
+    constexpr int kQXBytes = q_x_bytes(WAVES);
     // x; at the very end the same bytes hold the waves' partial sums, [tile][wave][lane][gate 0..3, up 4..7]
     __shared__ __attribute__((aligned(16))) unsigned char s_x[kQXBytes + 16 * 16];
     __shared__ int s_list[256];
