@@ -79,6 +79,21 @@ def test_workspace_bytes():
     assert H.halo_workspace_bytes(H.Shape(4090, 11008, 128, 256), 1, 4) == 0
 
 
+def test_workspace_bytes_q4():
+    # the bound for callers of the 4-bit entry points: the plain one, plus one block's weights as bf16 once
+    # more than 16 tokens can run on the bf16 kernels; never smaller, never falling as T grows
+    s = H.Shape(4096, 11008, 128, 256, "bf16")
+    for T in (1, 2, 16):
+        assert H.halo_workspace_bytes_q4(s, T, 43) == H.halo_workspace_bytes(s, T, 43)
+    for T in (17, 64, 512, 2000):
+        assert H.halo_workspace_bytes_q4(s, T, 43) == H.halo_workspace_bytes(s, T, 43) + 3 * 11008 * 4096 * 2
+    sizes = [H.halo_workspace_bytes_q4(s, T, 43) for T in range(1, 2200, 7)]
+    assert all(b >= a > 0 for a, b in zip(sizes, sizes[1:]))
+    assert H.halo_workspace_bytes_q4(s, 1, 87) == 0 and H.halo_workspace_bytes_q4(s, -1, 4) == 0
+    f = H.Shape(4096, 11008, 128, 256, "f32")                  # float32 activations: the plain path, no extra room
+    assert H.halo_workspace_bytes_q4(f, 512, 43) == H.halo_workspace_bytes(f, 512, 43)
+
+
 def test_entry_points_validate_before_any_gpu_work():
     lib = H.load_library()
     s = H.Shape(256, 1024, 128, 64, "f32")
